@@ -1,0 +1,194 @@
+/*
+ * mbu.h - C ABI of the MI355X (gfx950) masked-binary U-Net inference library.
+ *
+ * The library executes the inference path of MBU-Net: binary activations a in
+ * {-1,+1} bit-packed along channels, ternary ("masked") weights w in {-1,0,+1}
+ * held as two bit planes (subtractive encoding, Sec. 3.2.1, Eq. 2), a 3x3
+ * convolution whose every output is an integer dot product, and a fused epilogue
+ * that compares with a per-channel integer threshold and re-packs the result
+ * (Sec. 3.2.2, Algorithm 1).  Around it: bitwise pooling / up-sampling / skip
+ * concatenation (Sec. 2.1, Sec. 3.2.2) and full-precision first and last layers
+ * (Sec. 4.1).
+ *
+ * Conventions, valid for every entry point unless stated otherwise
+ *  - Return value: MBU_OK (0) or a negative mbu_status.  mbu_last_error() gives a
+ *    thread-local description of the last failure.  Arguments are validated on
+ *    the host BEFORE anything is launched; an invalid call launches nothing.
+ *  - All data pointers are DEVICE pointers owned by the caller (hipMalloc or a
+ *    framework allocator) unless the parameter is documented as a host pointer.
+ *    The library never allocates, frees or synchronises device memory.
+ *  - Device pointers must be 16-byte aligned (MBU_ERR_ALIGN otherwise).
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls are asynchronous with respect to the host and ordered on `stream`.
+ *  - Packed activations: tensor [N][H][W][Cw] of uint32, Cw = ceil(C/32);
+ *    channel c lives in bit (c % 32) of word (c / 32); bit 1 means +1, bit 0
+ *    means -1.  Bits of the last word beyond C are 0 on output and ignored on
+ *    input (their weights are packed as masked).
+ *  - Unpacked layouts: activations NHWC, conv weights OHWI = [Cout][3][3][Cin],
+ *    images and logits NCHW float32.
+ */
+#ifndef MBU_H_
+#define MBU_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum mbu_status {
+    MBU_OK = 0,
+    MBU_ERR_NULL = -1,       /* a required pointer is NULL                           */
+    MBU_ERR_SHAPE = -2,      /* non-positive / unsupported / inconsistent dimensions */
+    MBU_ERR_ALIGN = -3,      /* a device pointer is not 16-byte aligned              */
+    MBU_ERR_WORKSPACE = -4,  /* workspace too small                                  */
+    MBU_ERR_HIP = -5,        /* the HIP runtime reported a launch/runtime failure    */
+    MBU_ERR_ARG = -6         /* bad enum value, aliasing outputs, malformed blob     */
+} mbu_status;
+
+/* Which implementation mbu_conv3x3_masked_binary (and the network) uses. */
+typedef enum mbu_conv_path {
+    MBU_PATH_AUTO = 0,   /* library picks per layer shape (default)                       */
+    MBU_PATH_VALU = 1,   /* bit path: one bitfield-insert + one accumulating popcount per  */
+                         /* 32 taps on the vector ALU (Eq. 2 on packed words)             */
+    MBU_PATH_MFMA = 2    /* bits expanded on the fly to 4-bit {-1,0,+1} codes and         */
+                         /* contracted on the matrix cores, fp32 accumulators (exact)     */
+} mbu_conv_path;
+
+/* Description of the last failure on this thread ("" if none).  Host pointer,
+ * owned by the library, valid until the next failing call on the thread. */
+const char *mbu_last_error(void);
+
+/* Select the convolution implementation process-wide.  MBU_ERR_ARG on a bad value. */
+int mbu_set_conv_path(int path);
+int mbu_get_conv_path(void);
+
+/* Bit-packing of activations (Sec. 1: many binary values are grouped into one word
+ * so one instruction handles them; Algorithm 1 consumes such fragments).
+ *   src       NHWC [N][H][W][C]; src_dtype 0: int8 values, bit = (v > 0);
+ *             src_dtype 1: float32 values, bit = (v >= 0)
+ *   dst       uint32 [N][H][W][ceil(C/32)], pad bits written as 0
+ * Errors: NULL pointers, non-positive dims, bad dtype, misaligned pointers. */
+int mbu_pack_act(const void *src, int src_dtype, int N, int H, int W, int C,
+                 uint32_t *dst, void *stream);
+
+/* Size in bytes of the opaque packed-weight blob for a Cout x 3 x 3 x Cin layer.
+ * `bytes` is a host pointer.  Cout must be a multiple of 32 (packed outputs). */
+int mbu_packed_weights_bytes(int Cout, int Cin, size_t *bytes);
+
+/* Subtractive two-plane encoding of masked weights (Sec. 3.2.1: b = b_pos - b_neg).
+ *   w_ohwi   device int8 [Cout][3][3][Cin], values in {-1,0,+1} (anything else is
+ *            treated by sign: >0 as +1, <0 as -1)
+ *   packed   device blob of mbu_packed_weights_bytes(Cout,Cin) bytes, 16-byte
+ *            aligned, written completely; layout is private to the library and
+ *            holds the bit planes in the orders the kernels read them plus the
+ *            per-(channel, tap) kept-weight counts used at image borders.
+ * Channel padding up to the next multiple of 32/64 is packed as masked (0). */
+int mbu_pack_weights(const int8_t *w_ohwi, int Cout, int Cin, void *packed,
+                     void *stream);
+
+/* Masked-binary 3x3 convolution, stride 1, padding 1, with the fused threshold /
+ * sign / bit-pack epilogue (Algorithm 1; layer definition in Sec. 3.1.1).
+ *   acc[n,y,x,o] = sum_{ky,kx,c} w[o,ky,kx,c] * a[n,y+ky-1,x+kx-1,c]
+ * where taps outside the image contribute 0 (they behave as masked weights), and
+ *   bit[n,y,x,o] = (acc >= thresh[o])           (a tie gives +1).
+ *   act       packed activations [N][H][W][ceil(Cin/32)]
+ *   packed_w  blob from mbu_pack_weights for (Cout, Cin)
+ *   thresh    int32 [Cout]
+ *   out_bits  packed [N][H][W][Cout/32], or NULL
+ *   out_acc   int32 NHWC [N][H][W][Cout], or NULL (debug/parity; costs bandwidth)
+ * At least one output must be non-NULL; outputs must not alias `act`.
+ * Errors: NULL/misaligned pointers, non-positive dims, Cout % 32 != 0, blob that
+ * was packed for other (Cout, Cin) is undefined behaviour (checked only by size
+ * arguments, the header is device memory). */
+int mbu_conv3x3_masked_binary(const uint32_t *act, int N, int H, int W, int Cin,
+                              const void *packed_w, int Cout, const int32_t *thresh,
+                              uint32_t *out_bits, int32_t *out_acc, void *stream);
+
+/* 2x2 stride-2 max pooling on +-1 values = bitwise OR of the four packed words
+ * (Sec. 3.2.2 lists pooling as trivial).  H and W must be even.
+ *   in [N][H][W][Cw] -> out [N][H/2][W/2][Cw], Cw = ceil(C/32). */
+int mbu_maxpool2x2_bits(const uint32_t *in, int N, int H, int W, int C,
+                        uint32_t *out, void *stream);
+
+/* 2x nearest-neighbour up-sampling of packed activations: out[y][x] = in[y/2][x/2].
+ * Stands in the decoder where Sec. 2.1 describes a transposed convolution.
+ *   in [N][H][W][Cw] -> out [N][2H][2W][Cw]. */
+int mbu_upsample2x_bits(const uint32_t *in, int N, int H, int W, int C,
+                        uint32_t *out, void *stream);
+
+/* Skip concatenation along channels (Sec. 2.1): channels of `a` first, then `b`.
+ * Ca must be a multiple of 32 so that the result stays word aligned.
+ *   a [N][H][W][Ca/32], b [N][H][W][ceil(Cb/32)] -> out [N][H][W][Ca/32+ceil(Cb/32)] */
+int mbu_concat_bits(const uint32_t *a, int Ca, const uint32_t *b, int Cb,
+                    int N, int H, int W, uint32_t *out, void *stream);
+
+/* One masked-binary layer of the network: host struct, device pointers inside. */
+typedef struct mbu_conv_layer {
+    const void *packed_w;    /* blob from mbu_pack_weights(cout, cin)  */
+    const int32_t *thresh;   /* int32 [cout]                           */
+    int cin;
+    int cout;
+} mbu_conv_layer;
+
+/* Network descriptor (host struct).  The network is: float32 3x3 stem
+ * in_channels -> base with zero threshold and binarisation (Sec. 4.1: first layer
+ * full precision); `levels` encoder levels of two masked-binary 3x3 layers each,
+ * followed by 2x2 pooling; a bottleneck of two layers; `levels` decoder levels of
+ * [2x up-sampling, concatenation skip-then-up, two layers]; float32 1x1 classifier
+ * base -> n_classes (last layer full precision).  `convs` lists the
+ * 2*(2*levels+1) masked-binary layers in execution order and must be consistent
+ * (each layer's cin equals what the walk produces), else MBU_ERR_SHAPE. */
+typedef struct mbu_unet_desc {
+    int levels;
+    int base;                       /* channels after the stem; multiple of 32   */
+    int in_channels;                /* image channels (3)                        */
+    int n_classes;
+    const float *stem_w;            /* device [base][3][3][in_channels]          */
+    const mbu_conv_layer *convs;    /* host array, 2*(2*levels+1) entries        */
+    const float *cls_w;             /* device [n_classes][base]                  */
+    const float *cls_b;             /* device [n_classes]                        */
+    void **step_events;             /* optional host array of mbu_unet_num_steps()+1
+                                       hipEvent_t: event i is recorded on the stream
+                                       before step i, the last one after the final
+                                       step.  NULL = no events.                   */
+} mbu_unet_desc;
+
+/* Number of kernel steps the forward pass runs (stem, each conv, pool, up-sample +
+ * concatenation, classifier) for this descriptor. */
+int mbu_unet_num_steps(const mbu_unet_desc *d);
+
+/* Describes step `step` (0-based): a short static name, where its packed output
+ * lives inside the workspace (byte offset), and the output's shape.  The last step
+ * (classifier) writes to the logits, its offset is reported as (size_t)-1.
+ * All out-pointers are host pointers and may be NULL. */
+int mbu_unet_step_info(const mbu_unet_desc *d, int N, int H, int W, int step,
+                       const char **name, size_t *ws_offset, int *h, int *w, int *c);
+
+/* Workspace size (bytes) mbu_unet_forward needs for this shape. */
+int mbu_unet_workspace_bytes(const mbu_unet_desc *d, int N, int H, int W, size_t *bytes);
+
+/* Whole-network inference on one stream (Sec. 2.1 for the topology; Algorithm 1 for
+ * every inner layer; Sec. 4.1 for the float32 ends).  All intermediate activations
+ * stay bit-packed in `workspace`; every step's output keeps its own region so it
+ * can be inspected afterwards through mbu_unet_step_info.
+ *   image_nchw   float32 [N][in_channels][H][W]
+ *   logits_nchw  float32 [N][n_classes][H][W]
+ * H and W must be multiples of 2^levels. */
+int mbu_unet_forward(const mbu_unet_desc *d, const float *image_nchw, int N, int H, int W,
+                     float *logits_nchw, void *workspace, size_t workspace_bytes,
+                     void *stream);
+
+/* Thin helpers over HIP events so that a caller without HIP headers (the Python
+ * binding) can time work on the stream the kernels were launched on.  Events are
+ * host handles.  mbu_event_elapsed_ms synchronises on `stop`. */
+int mbu_event_create(void **event);
+int mbu_event_destroy(void *event);
+int mbu_event_record(void *event, void *stream);
+int mbu_event_elapsed_ms(void *start, void *stop, float *ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MBU_H_ */

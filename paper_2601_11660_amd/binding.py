@@ -1,0 +1,288 @@
+"""Thin ctypes binding over the C ABI declared in include/mbu.h.
+
+Argument marshalling only: every step of the path runs in the HIP kernels of
+libmbu_hip.so.  PyTorch supplies device memory and the current stream, nothing else.
+There is no CPU fallback: if the library has not been built, importing the entry
+points raises.
+"""
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmbu_hip.so")
+
+MBU_OK = 0
+MBU_ERR_NULL, MBU_ERR_SHAPE, MBU_ERR_ALIGN, MBU_ERR_WORKSPACE, MBU_ERR_HIP, MBU_ERR_ARG = -1, -2, -3, -4, -5, -6
+PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
+
+EXPORTS = [
+    "mbu_last_error", "mbu_set_conv_path", "mbu_get_conv_path", "mbu_pack_act",
+    "mbu_packed_weights_bytes", "mbu_pack_weights", "mbu_conv3x3_masked_binary",
+    "mbu_maxpool2x2_bits", "mbu_upsample2x_bits", "mbu_concat_bits", "mbu_unet_num_steps",
+    "mbu_unet_step_info", "mbu_unet_workspace_bytes", "mbu_unet_forward",
+    "mbu_event_create", "mbu_event_destroy", "mbu_event_record", "mbu_event_elapsed_ms",
+]
+
+
+class MbuError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"mbu error {code}: {msg}")
+        self.code = code
+
+
+class ConvLayer(ctypes.Structure):
+    _fields_ = [("packed_w", ctypes.c_void_p), ("thresh", ctypes.c_void_p),
+                ("cin", ctypes.c_int), ("cout", ctypes.c_int)]
+
+
+class UNetDesc(ctypes.Structure):
+    _fields_ = [("levels", ctypes.c_int), ("base", ctypes.c_int),
+                ("in_channels", ctypes.c_int), ("n_classes", ctypes.c_int),
+                ("stem_w", ctypes.c_void_p), ("convs", ctypes.POINTER(ConvLayer)),
+                ("cls_w", ctypes.c_void_p), ("cls_b", ctypes.c_void_p),
+                ("step_events", ctypes.POINTER(ctypes.c_void_p))]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded C-ABI library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it first "
+                               "(python -m paper_2601_11660_amd.build); there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        L.mbu_last_error.restype = ctypes.c_char_p
+        vp, ci = ctypes.c_void_p, ctypes.c_int
+        L.mbu_pack_act.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp]
+        L.mbu_packed_weights_bytes.argtypes = [ci, ci, ctypes.POINTER(ctypes.c_size_t)]
+        L.mbu_pack_weights.argtypes = [vp, ci, ci, vp, vp]
+        L.mbu_conv3x3_masked_binary.argtypes = [vp, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp]
+        L.mbu_maxpool2x2_bits.argtypes = [vp, ci, ci, ci, ci, vp, vp]
+        L.mbu_upsample2x_bits.argtypes = [vp, ci, ci, ci, ci, vp, vp]
+        L.mbu_concat_bits.argtypes = [vp, ci, vp, ci, ci, ci, ci, vp, vp]
+        L.mbu_unet_num_steps.argtypes = [ctypes.POINTER(UNetDesc)]
+        L.mbu_unet_step_info.argtypes = [ctypes.POINTER(UNetDesc), ci, ci, ci, ci,
+                                         ctypes.POINTER(ctypes.c_char_p),
+                                         ctypes.POINTER(ctypes.c_size_t),
+                                         ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ci)]
+        L.mbu_unet_workspace_bytes.argtypes = [ctypes.POINTER(UNetDesc), ci, ci, ci,
+                                               ctypes.POINTER(ctypes.c_size_t)]
+        L.mbu_unet_forward.argtypes = [ctypes.POINTER(UNetDesc), vp, ci, ci, ci, vp, vp,
+                                       ctypes.c_size_t, vp]
+        L.mbu_event_create.argtypes = [ctypes.POINTER(vp)]
+        L.mbu_event_destroy.argtypes = [vp]
+        L.mbu_event_record.argtypes = [vp, vp]
+        L.mbu_event_elapsed_ms.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_float)]
+        _lib = L
+    return _lib
+
+
+def last_error() -> str:
+    return lib().mbu_last_error().decode()
+
+
+def check(rc: int) -> None:
+    if rc != MBU_OK:
+        raise MbuError(rc, last_error())
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: torch.Tensor, dtypes) -> int:
+    if not t.is_cuda:
+        raise ValueError("expected a device tensor")
+    if t.dtype not in dtypes:
+        raise ValueError(f"expected dtype in {dtypes}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError("expected a contiguous tensor")
+    return t.data_ptr()
+
+
+def set_conv_path(path: int) -> None:
+    check(lib().mbu_set_conv_path(path))
+
+
+def get_conv_path() -> int:
+    return lib().mbu_get_conv_path()
+
+
+# Packed words are stored in int32 tensors (same bits as the ABI's uint32).
+def pack_act(x: torch.Tensor) -> torch.Tensor:
+    """mbu_pack_act: NHWC int8 (bit = v > 0) or float32 (bit = v >= 0) -> [N,H,W,ceil(C/32)]."""
+    N, H, W, C = x.shape
+    dt = 0 if x.dtype == torch.int8 else 1
+    out = torch.empty((N, H, W, (C + 31) // 32), dtype=torch.int32, device=x.device)
+    check(lib().mbu_pack_act(_dev(x, (torch.int8, torch.float32)), dt, N, H, W, C,
+                             out.data_ptr(), _stream()))
+    return out
+
+
+def packed_weights_bytes(cout: int, cin: int) -> int:
+    n = ctypes.c_size_t(0)
+    check(lib().mbu_packed_weights_bytes(cout, cin, ctypes.byref(n)))
+    return n.value
+
+
+def pack_weights(w_ohwi: torch.Tensor) -> torch.Tensor:
+    """mbu_pack_weights: device int8 [Cout,3,3,Cin] in {-1,0,+1} -> opaque blob (uint8 tensor)."""
+    cout, kh, kw, cin = w_ohwi.shape
+    assert kh == 3 and kw == 3
+    blob = torch.empty(packed_weights_bytes(cout, cin), dtype=torch.uint8, device=w_ohwi.device)
+    check(lib().mbu_pack_weights(_dev(w_ohwi, (torch.int8,)), cout, cin, blob.data_ptr(), _stream()))
+    return blob
+
+
+def conv3x3_masked_binary(act: torch.Tensor, cin: int, packed_w: torch.Tensor, cout: int,
+                          thresh: torch.Tensor, want_bits: bool = True, want_acc: bool = False,
+                          out_bits: Optional[torch.Tensor] = None,
+                          out_acc: Optional[torch.Tensor] = None
+                          ) -> Tuple[Optional[torch.Tensor], Optional[torch.Tensor]]:
+    """mbu_conv3x3_masked_binary -> (packed bits [N,H,W,Cout/32] or None, int32 acc NHWC or None)."""
+    N, H, W, _ = act.shape
+    if want_bits and out_bits is None:
+        out_bits = torch.empty((N, H, W, cout // 32), dtype=torch.int32, device=act.device)
+    if want_acc and out_acc is None:
+        out_acc = torch.empty((N, H, W, cout), dtype=torch.int32, device=act.device)
+    check(lib().mbu_conv3x3_masked_binary(
+        _dev(act, (torch.int32,)), N, H, W, cin, _dev(packed_w, (torch.uint8,)), cout,
+        _dev(thresh, (torch.int32,)),
+        out_bits.data_ptr() if out_bits is not None else None,
+        out_acc.data_ptr() if out_acc is not None else None, _stream()))
+    return out_bits, out_acc
+
+
+def maxpool2x2_bits(x: torch.Tensor, c: int) -> torch.Tensor:
+    N, H, W, Cw = x.shape
+    out = torch.empty((N, H // 2, W // 2, Cw), dtype=torch.int32, device=x.device)
+    check(lib().mbu_maxpool2x2_bits(_dev(x, (torch.int32,)), N, H, W, c, out.data_ptr(), _stream()))
+    return out
+
+
+def upsample2x_bits(x: torch.Tensor, c: int) -> torch.Tensor:
+    N, H, W, Cw = x.shape
+    out = torch.empty((N, 2 * H, 2 * W, Cw), dtype=torch.int32, device=x.device)
+    check(lib().mbu_upsample2x_bits(_dev(x, (torch.int32,)), N, H, W, c, out.data_ptr(), _stream()))
+    return out
+
+
+def concat_bits(a: torch.Tensor, ca: int, b: torch.Tensor, cb: int) -> torch.Tensor:
+    N, H, W, Caw = a.shape
+    out = torch.empty((N, H, W, Caw + b.shape[3]), dtype=torch.int32, device=a.device)
+    check(lib().mbu_concat_bits(_dev(a, (torch.int32,)), ca, _dev(b, (torch.int32,)), cb, N, H, W,
+                                out.data_ptr(), _stream()))
+    return out
+
+
+class Event:
+    """HIP event recorded on a given stream through the library's helpers."""
+
+    def __init__(self):
+        h = ctypes.c_void_p()
+        check(lib().mbu_event_create(ctypes.byref(h)))
+        self.handle = h
+
+    def record(self, stream: Optional[int] = None):
+        check(lib().mbu_event_record(self.handle, _stream() if stream is None else stream))
+
+    def elapsed_ms(self, stop: "Event") -> float:
+        ms = ctypes.c_float()
+        check(lib().mbu_event_elapsed_ms(self.handle, stop.handle, ctypes.byref(ms)))
+        return ms.value
+
+    def __del__(self):
+        try:
+            lib().mbu_event_destroy(self.handle)
+        except Exception:
+            pass
+
+
+class UNet:
+    """Owner of the device tensors and the host descriptor for mbu_unet_forward."""
+
+    def __init__(self, stem_w: torch.Tensor, convs: Sequence[Tuple[torch.Tensor, torch.Tensor]],
+                 cls_w: torch.Tensor, cls_b: torch.Tensor, levels: int = 4):
+        """stem_w float32 [base,3,3,Ci]; convs: (w int8 OHWI, theta int32) device tensors in
+        execution order; cls_w float32 [K,base]; cls_b float32 [K]."""
+        self.levels = levels
+        self.base = stem_w.shape[0]
+        self.in_channels = stem_w.shape[3]
+        self.n_classes = cls_w.shape[0]
+        self.stem_w = stem_w.contiguous()
+        self.cls_w = cls_w.contiguous()
+        self.cls_b = cls_b.contiguous()
+        self.blobs: List[torch.Tensor] = []
+        self.thetas: List[torch.Tensor] = []
+        self.shapes: List[Tuple[int, int]] = []
+        for w, th in convs:
+            self.blobs.append(pack_weights(w.contiguous()))
+            self.thetas.append(th.contiguous())
+            self.shapes.append((w.shape[3], w.shape[0]))
+        n = len(self.blobs)
+        self._layers = (ConvLayer * n)()
+        for i in range(n):
+            self._layers[i].packed_w = self.blobs[i].data_ptr()
+            self._layers[i].thresh = self.thetas[i].data_ptr()
+            self._layers[i].cin, self._layers[i].cout = self.shapes[i]
+        self.desc = UNetDesc(levels=levels, base=self.base, in_channels=self.in_channels,
+                             n_classes=self.n_classes, stem_w=self.stem_w.data_ptr(),
+                             convs=self._layers, cls_w=self.cls_w.data_ptr(),
+                             cls_b=self.cls_b.data_ptr(), step_events=None)
+        self.num_steps = lib().mbu_unet_num_steps(ctypes.byref(self.desc))
+        if self.num_steps < 0:
+            check(self.num_steps)
+        self._events: Optional[List[Event]] = None
+        self._ev_arr = None
+        self.workspace: Optional[torch.Tensor] = None
+
+    def workspace_bytes(self, N: int, H: int, W: int) -> int:
+        n = ctypes.c_size_t(0)
+        check(lib().mbu_unet_workspace_bytes(ctypes.byref(self.desc), N, H, W, ctypes.byref(n)))
+        return n.value
+
+    def enable_step_events(self, on: bool = True) -> None:
+        if on:
+            self._events = [Event() for _ in range(self.num_steps + 1)]
+            self._ev_arr = (ctypes.c_void_p * (self.num_steps + 1))(*[e.handle for e in self._events])
+            self.desc.step_events = ctypes.cast(self._ev_arr, ctypes.POINTER(ctypes.c_void_p))
+        else:
+            self._events, self._ev_arr = None, None
+            self.desc.step_events = None
+
+    def step_times_ms(self) -> List[float]:
+        assert self._events is not None
+        return [self._events[i].elapsed_ms(self._events[i + 1]) for i in range(self.num_steps)]
+
+    def step_info(self, N: int, H: int, W: int, step: int):
+        name = ctypes.c_char_p()
+        off = ctypes.c_size_t()
+        h, w, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+        check(lib().mbu_unet_step_info(ctypes.byref(self.desc), N, H, W, step, ctypes.byref(name),
+                                       ctypes.byref(off), ctypes.byref(h), ctypes.byref(w),
+                                       ctypes.byref(c)))
+        return name.value.decode(), off.value, h.value, w.value, c.value
+
+    def forward(self, image: torch.Tensor, logits: Optional[torch.Tensor] = None) -> torch.Tensor:
+        N, Ci, H, W = image.shape
+        need = self.workspace_bytes(N, H, W)
+        if self.workspace is None or self.workspace.numel() < need:
+            self.workspace = torch.empty(need, dtype=torch.uint8, device=image.device)
+        if logits is None:
+            logits = torch.empty((N, self.n_classes, H, W), dtype=torch.float32, device=image.device)
+        check(lib().mbu_unet_forward(ctypes.byref(self.desc), _dev(image, (torch.float32,)), N, H, W,
+                                     logits.data_ptr(), self.workspace.data_ptr(),
+                                     self.workspace.numel(), _stream()))
+        return logits
+
+    def step_output(self, N: int, H: int, W: int, step: int) -> torch.Tensor:
+        """Packed output of a step of the last forward pass, as an int32 view [N,h,w,c/32]."""
+        _, off, h, w, c = self.step_info(N, H, W, step)
+        n = N * h * w * (c // 32) * 4
+        return self.workspace[off:off + n].view(torch.int32).view(N, h, w, c // 32)

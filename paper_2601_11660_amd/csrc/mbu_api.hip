@@ -1,0 +1,384 @@
+// C-ABI entry points: argument validation, dispatch, and the network walk.
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+#include "mbu_internal.h"
+
+namespace mbu {
+
+static thread_local char g_err[512] = "";
+static int g_conv_path = MBU_PATH_AUTO;
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int check_launch(const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(MBU_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    return MBU_OK;
+}
+
+BlobLayout blob_layout(int cout, int cin)
+{
+    BlobLayout L;
+    L.cout = cout;
+    L.cin = cin;
+    L.cin_words = ceil_div(cin, 32);
+    L.cout_pad64 = ceil_div(cout, 64) * 64;
+    L.ksteps = ceil_div(cin, 64);
+    L.cout_tiles32 = L.cout_pad64 / 32;
+    size_t plane = (size_t)9 * L.cin_words * L.cout_pad64 * sizeof(uint32_t);
+    size_t off = 256;  // reserved header room
+    L.off_pos = off; off = round_up(off + plane, 256);
+    L.off_neg = off; off = round_up(off + plane, 256);
+    L.off_cnt = off; off = round_up(off + (size_t)10 * L.cout_pad64 * sizeof(int32_t), 256);
+    L.off_f4 = off;  off = round_up(off + (size_t)L.cout_tiles32 * 9 * L.ksteps * 64 * 16, 256);
+    L.total = off;
+    return L;
+}
+
+static int check_dims4(const char *fn, int N, int H, int W, int C)
+{
+    if (N <= 0 || H <= 0 || W <= 0 || C <= 0)
+        return fail(MBU_ERR_SHAPE, "%s: dimensions must be positive (N=%d H=%d W=%d C=%d)", fn, N, H, W, C);
+    if ((double)N * H * W * ((C + 31) / 32) > 4.0e9)
+        return fail(MBU_ERR_SHAPE, "%s: tensor too large", fn);
+    return MBU_OK;
+}
+
+#define MBU_REQ_PTR(fn, p)                                                        \
+    do {                                                                          \
+        if ((p) == nullptr) return mbu::fail(MBU_ERR_NULL, "%s: %s is NULL", fn, #p); \
+        if (!mbu::aligned16(p)) return mbu::fail(MBU_ERR_ALIGN, "%s: %s is not 16-byte aligned", fn, #p); \
+    } while (0)
+
+// ------------------------------------------------------------------ network plan
+struct Step {
+    enum Kind { STEM, CONV, POOL, UPCAT, CLS } kind;
+    const char *name;
+    int conv;        // index into d->convs for CONV
+    int in, in2;     // producing steps of the inputs (-1 = image); in2 = low-res input of UPCAT
+    int h, w, c;     // output shape
+    size_t off;      // workspace offset of the output
+};
+
+static const char *kConvNames[] = {"enc1a", "enc1b", "enc2a", "enc2b", "enc3a", "enc3b", "enc4a",
+                                   "enc4b", "enc5a", "enc5b", "enc6a", "enc6b"};
+static const char *kDecNames[] = {"dec1a", "dec1b", "dec2a", "dec2b", "dec3a", "dec3b", "dec4a",
+                                  "dec4b", "dec5a", "dec5b", "dec6a", "dec6b"};
+static const char *kPoolNames[] = {"pool1", "pool2", "pool3", "pool4", "pool5", "pool6"};
+static const char *kCatNames[] = {"cat1", "cat2", "cat3", "cat4", "cat5", "cat6"};
+
+static int build_plan(const mbu_unet_desc *d, int N, int H, int W, std::vector<Step> &steps,
+                      size_t *ws_bytes)
+{
+    const char *fn = "mbu_unet";
+    if (!d) return fail(MBU_ERR_NULL, "%s: descriptor is NULL", fn);
+    if (d->levels < 1 || d->levels > 6) return fail(MBU_ERR_SHAPE, "%s: levels must be 1..6", fn);
+    if (d->base <= 0 || d->base % 32) return fail(MBU_ERR_SHAPE, "%s: base must be a positive multiple of 32", fn);
+    if (d->in_channels != 1 && d->in_channels != 3) return fail(MBU_ERR_SHAPE, "%s: in_channels must be 1 or 3", fn);
+    if (d->n_classes <= 0 || d->n_classes > 64) return fail(MBU_ERR_SHAPE, "%s: n_classes must be 1..64", fn);
+    if (d->base != 32 && d->base != 64 && d->base != 128)
+        return fail(MBU_ERR_SHAPE, "%s: base must be 32, 64 or 128 (classifier width)", fn);
+    if (!d->convs) return fail(MBU_ERR_NULL, "%s: convs is NULL", fn);
+    int rc = check_dims4(fn, N, H, W, d->base);
+    if (rc) return rc;
+    int m = 1 << d->levels;
+    if (H % m || W % m) return fail(MBU_ERR_SHAPE, "%s: H and W must be multiples of %d", fn, m);
+
+    size_t off = 0;
+    auto push = [&](Step::Kind k, const char *name, int conv, int in, int in2, int h, int w, int c) {
+        Step s{k, name, conv, in, in2, h, w, c, off};
+        if (k != Step::CLS) off += round_up((size_t)N * h * w * (c / 32) * 4, 256);
+        else s.off = (size_t)-1;
+        steps.push_back(s);
+        return (int)steps.size() - 1;
+    };
+    int ci = 0;
+    auto conv = [&](const char *name, int in, int h, int w, int cin) -> int {
+        const mbu_conv_layer &L = d->convs[ci];
+        if (L.cin != cin) return -1 - ci;
+        if (L.cout <= 0 || L.cout % 32) return -1 - ci;
+        return push(Step::CONV, name, ci++, in, -1, h, w, L.cout);
+    };
+    int h = H, w = W;
+    int cur = push(Step::STEM, "stem", -1, -1, -1, h, w, d->base);
+    std::vector<int> skips;
+    for (int l = 0; l < d->levels; ++l) {
+        for (int j = 0; j < 2; ++j) {
+            cur = conv(kConvNames[2 * l + j], cur, h, w, steps[cur].c);
+            if (cur < 0) return fail(MBU_ERR_SHAPE, "%s: conv layer %d has inconsistent channels", fn, -1 - cur);
+        }
+        skips.push_back(cur);
+        h /= 2; w /= 2;
+        cur = push(Step::POOL, kPoolNames[l], -1, cur, -1, h, w, steps[cur].c);
+    }
+    for (int j = 0; j < 2; ++j) {
+        cur = conv(j ? "midb" : "mida", cur, h, w, steps[cur].c);
+        if (cur < 0) return fail(MBU_ERR_SHAPE, "%s: conv layer %d has inconsistent channels", fn, -1 - cur);
+    }
+    for (int l = d->levels - 1; l >= 0; --l) {
+        h *= 2; w *= 2;
+        int sk = skips[l];
+        cur = push(Step::UPCAT, kCatNames[l], -1, sk, cur, h, w, steps[sk].c + steps[cur].c);
+        for (int j = 0; j < 2; ++j) {
+            cur = conv(kDecNames[2 * l + j], cur, h, w, steps[cur].c);
+            if (cur < 0) return fail(MBU_ERR_SHAPE, "%s: conv layer %d has inconsistent channels", fn, -1 - cur);
+        }
+    }
+    if (steps[cur].c != d->base)
+        return fail(MBU_ERR_SHAPE, "%s: last layer must produce %d channels, got %d", fn, d->base, steps[cur].c);
+    push(Step::CLS, "classifier", -1, cur, -1, h, w, d->n_classes);
+    if (ws_bytes) *ws_bytes = off;
+    return MBU_OK;
+}
+
+static int run_conv(const uint32_t *act, int N, int H, int W, int Cin, const void *packed_w,
+                    int Cout, const int32_t *thresh, uint32_t *out_bits, int32_t *out_acc,
+                    hipStream_t s)
+{
+    BlobLayout L = blob_layout(Cout, Cin);
+    int path = g_conv_path;
+    if (path == MBU_PATH_AUTO) path = MBU_PATH_MFMA;
+    if (path == MBU_PATH_VALU)
+        return launch_conv_valu(act, N, H, W, L, packed_w, thresh, out_bits, out_acc, s);
+    return launch_conv_mfma(act, N, H, W, L, packed_w, thresh, out_bits, out_acc, s);
+}
+
+}  // namespace mbu
+
+using namespace mbu;
+
+extern "C" {
+
+const char *mbu_last_error(void) { return g_err; }
+
+int mbu_set_conv_path(int path)
+{
+    if (path != MBU_PATH_AUTO && path != MBU_PATH_VALU && path != MBU_PATH_MFMA)
+        return fail(MBU_ERR_ARG, "mbu_set_conv_path: unknown path %d", path);
+    g_conv_path = path;
+    return MBU_OK;
+}
+
+int mbu_get_conv_path(void) { return g_conv_path; }
+
+int mbu_pack_act(const void *src, int src_dtype, int N, int H, int W, int C, uint32_t *dst,
+                 void *stream)
+{
+    const char *fn = "mbu_pack_act";
+    MBU_REQ_PTR(fn, src);
+    MBU_REQ_PTR(fn, dst);
+    if (src_dtype != 0 && src_dtype != 1) return fail(MBU_ERR_ARG, "%s: src_dtype must be 0 (int8) or 1 (float32)", fn);
+    int rc = check_dims4(fn, N, H, W, C);
+    if (rc) return rc;
+    return launch_pack_act(src, src_dtype, (long)N * H * W, C, dst, (hipStream_t)stream);
+}
+
+int mbu_packed_weights_bytes(int Cout, int Cin, size_t *bytes)
+{
+    const char *fn = "mbu_packed_weights_bytes";
+    if (!bytes) return fail(MBU_ERR_NULL, "%s: bytes is NULL", fn);
+    if (Cout <= 0 || Cin <= 0 || Cout % 32) return fail(MBU_ERR_SHAPE, "%s: need Cin > 0 and Cout a positive multiple of 32 (Cout=%d Cin=%d)", fn, Cout, Cin);
+    if (Cout > 65536 || Cin > 65536) return fail(MBU_ERR_SHAPE, "%s: channel count too large", fn);
+    *bytes = blob_layout(Cout, Cin).total;
+    return MBU_OK;
+}
+
+int mbu_pack_weights(const int8_t *w_ohwi, int Cout, int Cin, void *packed, void *stream)
+{
+    const char *fn = "mbu_pack_weights";
+    MBU_REQ_PTR(fn, w_ohwi);
+    MBU_REQ_PTR(fn, packed);
+    size_t bytes;
+    int rc = mbu_packed_weights_bytes(Cout, Cin, &bytes);
+    if (rc) return rc;
+    return launch_pack_weights(w_ohwi, blob_layout(Cout, Cin), packed, (hipStream_t)stream);
+}
+
+int mbu_conv3x3_masked_binary(const uint32_t *act, int N, int H, int W, int Cin,
+                              const void *packed_w, int Cout, const int32_t *thresh,
+                              uint32_t *out_bits, int32_t *out_acc, void *stream)
+{
+    const char *fn = "mbu_conv3x3_masked_binary";
+    MBU_REQ_PTR(fn, act);
+    MBU_REQ_PTR(fn, packed_w);
+    MBU_REQ_PTR(fn, thresh);
+    if (!out_bits && !out_acc) return fail(MBU_ERR_NULL, "%s: out_bits and out_acc are both NULL", fn);
+    if (out_bits && !aligned16(out_bits)) return fail(MBU_ERR_ALIGN, "%s: out_bits is not 16-byte aligned", fn);
+    if (out_acc && !aligned16(out_acc)) return fail(MBU_ERR_ALIGN, "%s: out_acc is not 16-byte aligned", fn);
+    if ((const void *)out_bits == (const void *)act || (const void *)out_acc == (const void *)act)
+        return fail(MBU_ERR_ARG, "%s: outputs must not alias the input", fn);
+    int rc = check_dims4(fn, N, H, W, Cin);
+    if (rc) return rc;
+    if (Cout <= 0 || Cout % 32) return fail(MBU_ERR_SHAPE, "%s: Cout must be a positive multiple of 32, got %d", fn, Cout);
+    if (Cout > 65536 || Cin > 65536) return fail(MBU_ERR_SHAPE, "%s: channel count too large", fn);
+    rc = check_dims4(fn, N, H, W, Cout);
+    if (rc) return rc;
+    return run_conv(act, N, H, W, Cin, packed_w, Cout, thresh, out_bits, out_acc, (hipStream_t)stream);
+}
+
+int mbu_maxpool2x2_bits(const uint32_t *in, int N, int H, int W, int C, uint32_t *out, void *stream)
+{
+    const char *fn = "mbu_maxpool2x2_bits";
+    MBU_REQ_PTR(fn, in);
+    MBU_REQ_PTR(fn, out);
+    int rc = check_dims4(fn, N, H, W, C);
+    if (rc) return rc;
+    if ((H & 1) || (W & 1)) return fail(MBU_ERR_SHAPE, "%s: H and W must be even (H=%d W=%d)", fn, H, W);
+    return launch_maxpool(in, N, H, W, ceil_div(C, 32), out, (hipStream_t)stream);
+}
+
+int mbu_upsample2x_bits(const uint32_t *in, int N, int H, int W, int C, uint32_t *out, void *stream)
+{
+    const char *fn = "mbu_upsample2x_bits";
+    MBU_REQ_PTR(fn, in);
+    MBU_REQ_PTR(fn, out);
+    int rc = check_dims4(fn, N, H, W, C);
+    if (rc) return rc;
+    if ((double)N * H * W * 4.0 * ((C + 31) / 32) > 4.0e9) return fail(MBU_ERR_SHAPE, "%s: output too large", fn);
+    return launch_upsample(in, N, H, W, ceil_div(C, 32), out, (hipStream_t)stream);
+}
+
+int mbu_concat_bits(const uint32_t *a, int Ca, const uint32_t *b, int Cb, int N, int H, int W,
+                    uint32_t *out, void *stream)
+{
+    const char *fn = "mbu_concat_bits";
+    MBU_REQ_PTR(fn, a);
+    MBU_REQ_PTR(fn, b);
+    MBU_REQ_PTR(fn, out);
+    int rc = check_dims4(fn, N, H, W, Ca);
+    if (rc) return rc;
+    rc = check_dims4(fn, N, H, W, Cb);
+    if (rc) return rc;
+    if (Ca % 32) return fail(MBU_ERR_SHAPE, "%s: Ca must be a multiple of 32, got %d", fn, Ca);
+    return launch_concat(a, Ca / 32, b, ceil_div(Cb, 32), (long)N * H * W, out, (hipStream_t)stream);
+}
+
+int mbu_unet_num_steps(const mbu_unet_desc *d)
+{
+    if (!d) return fail(MBU_ERR_NULL, "mbu_unet_num_steps: descriptor is NULL");
+    if (d->levels < 1 || d->levels > 6) return fail(MBU_ERR_SHAPE, "mbu_unet_num_steps: levels must be 1..6");
+    return 1 + 3 * d->levels + 2 + 3 * d->levels + 1;
+}
+
+int mbu_unet_step_info(const mbu_unet_desc *d, int N, int H, int W, int step, const char **name,
+                       size_t *ws_offset, int *h, int *w, int *c)
+{
+    std::vector<Step> steps;
+    int rc = build_plan(d, N, H, W, steps, nullptr);
+    if (rc) return rc;
+    if (step < 0 || step >= (int)steps.size()) return fail(MBU_ERR_ARG, "mbu_unet_step_info: step %d out of range", step);
+    const Step &s = steps[step];
+    if (name) *name = s.name;
+    if (ws_offset) *ws_offset = s.off;
+    if (h) *h = s.h;
+    if (w) *w = s.w;
+    if (c) *c = s.c;
+    return MBU_OK;
+}
+
+int mbu_unet_workspace_bytes(const mbu_unet_desc *d, int N, int H, int W, size_t *bytes)
+{
+    if (!bytes) return fail(MBU_ERR_NULL, "mbu_unet_workspace_bytes: bytes is NULL");
+    std::vector<Step> steps;
+    return build_plan(d, N, H, W, steps, bytes);
+}
+
+int mbu_unet_forward(const mbu_unet_desc *d, const float *image_nchw, int N, int H, int W,
+                     float *logits_nchw, void *workspace, size_t workspace_bytes, void *stream)
+{
+    const char *fn = "mbu_unet_forward";
+    std::vector<Step> steps;
+    size_t need = 0;
+    int rc = build_plan(d, N, H, W, steps, &need);
+    if (rc) return rc;
+    MBU_REQ_PTR(fn, image_nchw);
+    MBU_REQ_PTR(fn, logits_nchw);
+    MBU_REQ_PTR(fn, workspace);
+    MBU_REQ_PTR(fn, d->stem_w);
+    MBU_REQ_PTR(fn, d->cls_w);
+    MBU_REQ_PTR(fn, d->cls_b);
+    if (workspace_bytes < need)
+        return fail(MBU_ERR_WORKSPACE, "%s: workspace has %zu bytes, %zu needed", fn, workspace_bytes, need);
+    int nconv = 2 * (2 * d->levels + 1);
+    for (int i = 0; i < nconv; ++i) {
+        MBU_REQ_PTR(fn, d->convs[i].packed_w);
+        MBU_REQ_PTR(fn, d->convs[i].thresh);
+    }
+    hipStream_t s = (hipStream_t)stream;
+    uint8_t *ws = (uint8_t *)workspace;
+    auto buf = [&](int step) { return (uint32_t *)(ws + steps[step].off); };
+    for (size_t i = 0; i < steps.size(); ++i) {
+        const Step &st = steps[i];
+        if (d->step_events && hipEventRecord((hipEvent_t)d->step_events[i], s) != hipSuccess)
+            return fail(MBU_ERR_HIP, "%s: hipEventRecord failed", fn);
+        switch (st.kind) {
+        case Step::STEM:
+            rc = launch_stem(image_nchw, N, d->in_channels, H, W, d->stem_w, d->base, buf((int)i), s);
+            break;
+        case Step::CONV: {
+            const mbu_conv_layer &L = d->convs[st.conv];
+            rc = run_conv(buf(st.in), N, st.h, st.w, L.cin, L.packed_w, L.cout, L.thresh,
+                          buf((int)i), nullptr, s);
+            break;
+        }
+        case Step::POOL:
+            rc = launch_maxpool(buf(st.in), N, st.h * 2, st.w * 2, st.c / 32, buf((int)i), s);
+            break;
+        case Step::UPCAT:
+            rc = launch_upcat(buf(st.in), steps[st.in].c / 32, buf(st.in2), steps[st.in2].c / 32, N,
+                              st.h, st.w, buf((int)i), s);
+            break;
+        case Step::CLS:
+            rc = launch_classifier(buf(st.in), N, st.h, st.w, steps[st.in].c, d->cls_w, d->cls_b,
+                                   d->n_classes, logits_nchw, s);
+            break;
+        }
+        if (rc) return rc;
+    }
+    if (d->step_events && hipEventRecord((hipEvent_t)d->step_events[steps.size()], s) != hipSuccess)
+        return fail(MBU_ERR_HIP, "%s: hipEventRecord failed", fn);
+    return MBU_OK;
+}
+
+int mbu_event_create(void **event)
+{
+    if (!event) return fail(MBU_ERR_NULL, "mbu_event_create: event is NULL");
+    hipEvent_t e;
+    if (hipEventCreate(&e) != hipSuccess) return fail(MBU_ERR_HIP, "hipEventCreate failed");
+    *event = (void *)e;
+    return MBU_OK;
+}
+
+int mbu_event_destroy(void *event)
+{
+    if (!event) return fail(MBU_ERR_NULL, "mbu_event_destroy: event is NULL");
+    return hipEventDestroy((hipEvent_t)event) == hipSuccess ? MBU_OK : fail(MBU_ERR_HIP, "hipEventDestroy failed");
+}
+
+int mbu_event_record(void *event, void *stream)
+{
+    if (!event) return fail(MBU_ERR_NULL, "mbu_event_record: event is NULL");
+    return hipEventRecord((hipEvent_t)event, (hipStream_t)stream) == hipSuccess
+               ? MBU_OK : fail(MBU_ERR_HIP, "hipEventRecord failed");
+}
+
+int mbu_event_elapsed_ms(void *start, void *stop, float *ms)
+{
+    if (!start || !stop || !ms) return fail(MBU_ERR_NULL, "mbu_event_elapsed_ms: NULL argument");
+    if (hipEventSynchronize((hipEvent_t)stop) != hipSuccess) return fail(MBU_ERR_HIP, "hipEventSynchronize failed");
+    if (hipEventElapsedTime(ms, (hipEvent_t)start, (hipEvent_t)stop) != hipSuccess)
+        return fail(MBU_ERR_HIP, "hipEventElapsedTime failed");
+    return MBU_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,69 @@
+// Internal declarations shared by the translation units of the HIP library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "mbu.h"
+
+namespace mbu {
+
+// Record a failure description for mbu_last_error() and return `code`.
+int fail(int code, const char *fmt, ...);
+// Turn the HIP error state after a launch into a status.
+int check_launch(const char *what);
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
+inline size_t round_up(size_t v, size_t m) { return (v + m - 1) / m * m; }
+
+// ---- layout of the packed-weight blob (all offsets in bytes from the blob start) ----
+// Section V (vector-ALU path): two bit planes, each uint32 [9][cin_words][cout_pad64]
+// (tap-major, output channel fastest so 64 lanes read 64 consecutive words), and the
+// kept-weight counts int32 [10][cout_pad64]: rows 0..8 per tap, row 9 the total.
+// Section M (matrix-core path): 4-bit codes, uint4 [cout_tiles32][9][ksteps][64 lanes],
+// one 16-byte fragment per lane and (32 output channels, tap, 64 input channels).
+struct BlobLayout {
+    int cout, cin;
+    int cin_words;     // ceil(cin/32)
+    int cout_pad64;    // cout rounded up to 64
+    int ksteps;        // ceil(cin/64): 64-channel steps of the matrix path
+    int cout_tiles32;  // cout/32
+    size_t off_pos, off_neg, off_cnt, off_f4, total;
+};
+BlobLayout blob_layout(int cout, int cin);
+
+// Row order of output channels inside one 32-channel matrix tile: tile row i holds
+// output channel tile_row_to_channel(i) of the tile, chosen so that the sixteen
+// accumulator registers of a lane map to sixteen consecutive output-channel bits.
+__host__ __device__ inline int tile_row_to_channel(int i) {
+    // accumulator register r of lane-half h holds tile row 8*(r/4) + 4*h + r%4
+    int g = i >> 3, h = (i >> 2) & 1, j = i & 3;
+    return 16 * h + 4 * g + j;
+}
+__host__ __device__ inline int tile_channel_to_row(int c) {
+    int h = c >> 4, g = (c >> 2) & 3, j = c & 3;
+    return 8 * g + 4 * h + j;
+}
+
+// ---- kernel launchers (arguments already validated) ----
+int launch_pack_act(const void *src, int dtype, long pixels, int C, uint32_t *dst, hipStream_t s);
+int launch_pack_weights(const int8_t *w, const BlobLayout &L, void *blob, hipStream_t s);
+int launch_conv_valu(const uint32_t *act, int N, int H, int W, const BlobLayout &L,
+                     const void *blob, const int32_t *thresh, uint32_t *out_bits,
+                     int32_t *out_acc, hipStream_t s);
+int launch_conv_mfma(const uint32_t *act, int N, int H, int W, const BlobLayout &L,
+                     const void *blob, const int32_t *thresh, uint32_t *out_bits,
+                     int32_t *out_acc, hipStream_t s);
+int launch_maxpool(const uint32_t *in, int N, int H, int W, int Cw, uint32_t *out, hipStream_t s);
+int launch_upsample(const uint32_t *in, int N, int H, int W, int Cw, uint32_t *out, hipStream_t s);
+int launch_concat(const uint32_t *a, int Caw, const uint32_t *b, int Cbw, long pixels,
+                  uint32_t *out, hipStream_t s);
+// out[n][y][x] = [ skip[n][y][x] | up[n][y/2][x/2] ]  (H, W are the output size)
+int launch_upcat(const uint32_t *skip, int Csw, const uint32_t *low, int Clw,
+                 int N, int H, int W, uint32_t *out, hipStream_t s);
+int launch_stem(const float *img, int N, int Ci, int H, int W, const float *w, int Co,
+                uint32_t *out_bits, hipStream_t s);
+int launch_classifier(const uint32_t *act, int N, int H, int W, int C, const float *w,
+                      const float *b, int K, float *out, hipStream_t s);
+
+}  // namespace mbu

@@ -1,0 +1,115 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the header
+declares, and rejects bad arguments before launching anything (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2601_11660_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_symbols():
+    txt = open(os.path.join(ROOT, "include", "mbu.h")).read()
+    txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
+    return sorted(set(re.findall(r"\b(mbu_[a-z0-9_]+)\s*\(", txt)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    syms = header_symbols()
+    assert len(syms) >= 18
+    for s in syms:
+        assert hasattr(L, s), s
+    assert sorted(B.EXPORTS) == syms
+
+
+def test_null_and_alignment_errors():
+    L = B.lib()
+    assert L.mbu_pack_act(None, 0, 1, 4, 4, 32, None, None) == B.MBU_ERR_NULL
+    assert "NULL" in B.last_error()
+    fake, fake2 = 0x10000, 0x20000    # never dereferenced: validation fails first
+    assert L.mbu_pack_act(fake, 0, 1, 4, 4, 32, fake2 + 4, None) == B.MBU_ERR_ALIGN
+    assert L.mbu_pack_act(fake, 7, 1, 4, 4, 32, fake2, None) == B.MBU_ERR_ARG
+    assert L.mbu_pack_act(fake, 0, 0, 4, 4, 32, fake2, None) == B.MBU_ERR_SHAPE
+    assert L.mbu_maxpool2x2_bits(fake, 1, 3, 4, 32, fake2, None) == B.MBU_ERR_SHAPE
+    assert L.mbu_maxpool2x2_bits(fake, 1, 4, 4, 32, None, None) == B.MBU_ERR_NULL
+    assert L.mbu_upsample2x_bits(None, 1, 4, 4, 32, fake2, None) == B.MBU_ERR_NULL
+    assert L.mbu_concat_bits(fake, 48, fake2, 32, 1, 4, 4, fake, None) == B.MBU_ERR_SHAPE
+    assert L.mbu_pack_weights(None, 64, 64, fake, None) == B.MBU_ERR_NULL
+    assert L.mbu_pack_weights(fake, 48, 64, fake2, None) == B.MBU_ERR_SHAPE
+
+
+def test_conv_argument_validation():
+    L = B.lib()
+    a, w, t, o = 0x10000, 0x20000, 0x30000, 0x40000
+    f = L.mbu_conv3x3_masked_binary
+    assert f(a, 1, 8, 8, 64, w, 64, t, None, None, None) == B.MBU_ERR_NULL
+    assert f(a, 1, 8, 8, 64, w, 48, t, o, None, None) == B.MBU_ERR_SHAPE
+    assert f(a, 1, 8, 0, 64, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
+    assert f(a, 1, 8, 8, 64, w, 64, t, a, None, None) == B.MBU_ERR_ARG
+    assert f(a, 1, 8, 8, 64, w, 64, t + 8, o, None, None) == B.MBU_ERR_ALIGN
+    assert f(None, 1, 8, 8, 64, w, 64, t, o, None, None) == B.MBU_ERR_NULL
+
+
+def test_packed_weight_size_and_path_switch():
+    assert B.packed_weights_bytes(64, 64) > 2 * 9 * 64 * 64 // 8
+    with pytest.raises(B.MbuError):
+        B.packed_weights_bytes(40, 64)
+    n = ctypes.c_size_t()
+    assert B.lib().mbu_packed_weights_bytes(64, 64, None) == B.MBU_ERR_NULL
+    assert B.lib().mbu_set_conv_path(9) == B.MBU_ERR_ARG
+    B.set_conv_path(B.PATH_VALU)
+    assert B.get_conv_path() == B.PATH_VALU
+    B.set_conv_path(B.PATH_AUTO)
+
+
+def _desc(levels=4, base=64, convs=None):
+    d = B.UNetDesc(levels=levels, base=base, in_channels=3, n_classes=19)
+    if convs is not None:
+        arr = (B.ConvLayer * len(convs))()
+        for i, (ci, co) in enumerate(convs):
+            arr[i].cin, arr[i].cout = ci, co
+            arr[i].packed_w, arr[i].thresh = 0x10000, 0x20000
+        d.convs = arr
+        d._keep = arr
+    return d
+
+
+def test_unet_plan_validation_and_workspace():
+    from paper_2601_11660_amd import synth
+    plan = synth.unet_channel_plan(64, 4)
+    d = _desc(convs=[(ci, co) for _, ci, co, _ in plan])
+    L = B.lib()
+    assert L.mbu_unet_num_steps(ctypes.byref(d)) == 28
+    n = ctypes.c_size_t()
+    assert L.mbu_unet_workspace_bytes(ctypes.byref(d), 1, 64, 128, ctypes.byref(n)) == 0
+    # every step's packed output, 256-byte aligned regions
+    expect = 0
+    names = []
+    for s in range(27):
+        name = ctypes.c_char_p()
+        off = ctypes.c_size_t()
+        h, w, c = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+        assert L.mbu_unet_step_info(ctypes.byref(d), 1, 64, 128, s, ctypes.byref(name),
+                                    ctypes.byref(off), ctypes.byref(h), ctypes.byref(w),
+                                    ctypes.byref(c)) == 0
+        assert off.value == expect
+        expect += (h.value * w.value * (c.value // 32) * 4 + 255) // 256 * 256
+        names.append(name.value.decode())
+    assert n.value == expect
+    assert names[:4] == ["stem", "enc1a", "enc1b", "pool1"] and names[15:19] == ["cat4", "dec4a", "dec4b", "cat3"]
+    # H not a multiple of 16
+    assert L.mbu_unet_workspace_bytes(ctypes.byref(d), 1, 72, 128, ctypes.byref(n)) == B.MBU_ERR_SHAPE
+    # inconsistent channel plan
+    bad = [(ci, co) for _, ci, co, _ in plan]
+    bad[10] = (1024, 512)
+    d2 = _desc(convs=bad)
+    assert L.mbu_unet_workspace_bytes(ctypes.byref(d2), 1, 64, 128, ctypes.byref(n)) == B.MBU_ERR_SHAPE
+    assert "layer 10" in B.last_error()
+    # forward: workspace too small / NULL image are caught before any launch
+    assert L.mbu_unet_forward(ctypes.byref(d), None, 1, 64, 128, 0x50000, 0x60000, 1 << 40, None) == B.MBU_ERR_NULL
+    d.stem_w, d.cls_w, d.cls_b = 0x70000, 0x80000, 0x90000
+    assert L.mbu_unet_forward(ctypes.byref(d), 0x40000, 1, 64, 128, 0x50000, 0x60000, 16, None) == B.MBU_ERR_WORKSPACE
