@@ -129,14 +129,11 @@ def main():
 
     # K event sets so that every timed step keeps its own per-kernel timestamps
     K = args.steps
-    ev_sets = []
-    for _ in range(K):
-        net.enable_step_events(True)
-        ev_sets.append((net._events, net._ev_arr, net.desc.step_events))
+    ev_sets = [net.new_event_set() for _ in range(K)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(K):
-        net._events, net._ev_arr, net.desc.step_events = ev_sets[k]
+        net.use_event_set(ev_sets[k])
         net.forward(image, logits)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
@@ -145,10 +142,9 @@ def main():
     infos = [net.step_info(N, H, W, s) for s in range(net.num_steps)]
     step_ms = np.zeros(net.num_steps)
     for k in range(K):
-        net._events = ev_sets[k][0]
-        step_ms += np.array(net.step_times_ms())
+        step_ms += np.array(net.step_times_ms(ev_sets[k]))
     step_ms /= K
-    net.enable_step_events(False)
+    net.use_event_set(None)
 
     per_layer, conv_ms, conv_ops = [], 0.0, 0.0
     ci = 0

@@ -204,6 +204,14 @@ class Event:
             pass
 
 
+class EventSet:
+    """Events plus the host array of their handles that the descriptor points to."""
+
+    def __init__(self, n: int):
+        self.events = [Event() for _ in range(n)]
+        self.array = (ctypes.c_void_p * n)(*[e.handle.value for e in self.events])
+
+
 class UNet:
     """Owner of the device tensors and the host descriptor for mbu_unet_forward."""
 
@@ -238,8 +246,7 @@ class UNet:
         self.num_steps = lib().mbu_unet_num_steps(ctypes.byref(self.desc))
         if self.num_steps < 0:
             check(self.num_steps)
-        self._events: Optional[List[Event]] = None
-        self._ev_arr = None
+        self._events: Optional[EventSet] = None
         self.workspace: Optional[torch.Tensor] = None
 
     def workspace_bytes(self, N: int, H: int, W: int) -> int:
@@ -247,18 +254,24 @@ class UNet:
         check(lib().mbu_unet_workspace_bytes(ctypes.byref(self.desc), N, H, W, ctypes.byref(n)))
         return n.value
 
-    def enable_step_events(self, on: bool = True) -> None:
-        if on:
-            self._events = [Event() for _ in range(self.num_steps + 1)]
-            self._ev_arr = (ctypes.c_void_p * (self.num_steps + 1))(*[e.handle for e in self._events])
-            self.desc.step_events = ctypes.cast(self._ev_arr, ctypes.POINTER(ctypes.c_void_p))
-        else:
-            self._events, self._ev_arr = None, None
-            self.desc.step_events = None
+    def new_event_set(self) -> "EventSet":
+        """A fresh set of num_steps+1 events for one forward pass."""
+        return EventSet(self.num_steps + 1)
 
-    def step_times_ms(self) -> List[float]:
-        assert self._events is not None
-        return [self._events[i].elapsed_ms(self._events[i + 1]) for i in range(self.num_steps)]
+    def use_event_set(self, es: Optional["EventSet"]) -> None:
+        """Make the next forward passes record their per-step events into `es`
+        (None switches event recording off)."""
+        self._events = es
+        self.desc.step_events = (ctypes.cast(es.array, ctypes.POINTER(ctypes.c_void_p))
+                                 if es is not None else None)
+
+    def enable_step_events(self, on: bool = True) -> None:
+        self.use_event_set(self.new_event_set() if on else None)
+
+    def step_times_ms(self, es: Optional["EventSet"] = None) -> List[float]:
+        es = es if es is not None else self._events
+        assert es is not None
+        return [es.events[i].elapsed_ms(es.events[i + 1]) for i in range(self.num_steps)]
 
     def step_info(self, N: int, H: int, W: int, step: int):
         name = ctypes.c_char_p()

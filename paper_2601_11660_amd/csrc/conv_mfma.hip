@@ -166,10 +166,10 @@ int launch_conv_mfma(const uint32_t *act, int N, int H, int W, const BlobLayout 
     dim3 grid((unsigned)tiles, (unsigned)(L.cout_pad64 / 64));
     const uint4 *wfrag = (const uint4 *)((const uint8_t *)blob + L.off_f4);
     if (out_acc)
-        hipLaunchKernelGGL(conv_mfma_kernel<true>, grid, dim3(256), 0, s, act, N, H, W,
+        MBU_LAUNCH(conv_mfma_kernel<true>, grid, dim3(256), 0, s, act, N, H, W,
                            L.cin_words, L.ksteps, wfrag, L.cout, thresh, out_bits, out_acc);
     else
-        hipLaunchKernelGGL(conv_mfma_kernel<false>, grid, dim3(256), 0, s, act, N, H, W,
+        MBU_LAUNCH(conv_mfma_kernel<false>, grid, dim3(256), 0, s, act, N, H, W,
                            L.cin_words, L.ksteps, wfrag, L.cout, thresh, out_bits, out_acc);
     return check_launch("conv_mfma");
 }

@@ -120,7 +120,7 @@ static int launch_t(const uint32_t *act, int N, int H, int W, const BlobLayout &
     const uint8_t *b = (const uint8_t *)blob;
     long strips = (long)N * H * ceil_div(W, TX);
     dim3 grid((unsigned)((strips + 3) / 4), (unsigned)(L.cout_pad64 / 64));
-    hipLaunchKernelGGL((conv_valu_kernel<WCH, TX>), grid, dim3(256), 0, s, act, N, H, W,
+    MBU_LAUNCH((conv_valu_kernel<WCH, TX>), grid, dim3(256), 0, s, act, N, H, W,
                        L.cin_words, ceil_div(L.cin_words, WCH),
                        (const uint32_t *)(b + L.off_pos), (const uint32_t *)(b + L.off_neg),
                        (const int32_t *)(b + L.off_cnt), L.cout_pad64, L.cout, thresh, out_bits,

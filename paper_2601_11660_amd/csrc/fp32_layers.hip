@@ -59,10 +59,10 @@ int launch_stem(const float *img, int N, int Ci, int H, int W, const float *w, i
     unsigned blocks = (unsigned)((total + 255) / 256);
     size_t shmem = (size_t)Co * 9 * Ci * sizeof(float);
     if (Ci == 3)
-        hipLaunchKernelGGL(stem_kernel<3>, dim3(blocks), dim3(256), shmem, s, img, N, H, W, w, Co,
+        MBU_LAUNCH(stem_kernel<3>, dim3(blocks), dim3(256), shmem, s, img, N, H, W, w, Co,
                            out_bits);
     else if (Ci == 1)
-        hipLaunchKernelGGL(stem_kernel<1>, dim3(blocks), dim3(256), shmem, s, img, N, H, W, w, Co,
+        MBU_LAUNCH(stem_kernel<1>, dim3(blocks), dim3(256), shmem, s, img, N, H, W, w, Co,
                            out_bits);
     else
         return fail(MBU_ERR_SHAPE, "stem supports 1 or 3 image channels, got %d", Ci);
@@ -113,9 +113,9 @@ int launch_classifier(const uint32_t *act, int N, int H, int W, int C, const flo
     size_t shmem = ((size_t)K * C + K) * sizeof(float);
     if (shmem > 60000) return fail(MBU_ERR_SHAPE, "classifier weights do not fit in LDS");
     switch (C / 32) {
-    case 1: hipLaunchKernelGGL(classifier_kernel<1>, dim3(blocks), dim3(256), shmem, s, act, N, H, W, w, b, K, out); break;
-    case 2: hipLaunchKernelGGL(classifier_kernel<2>, dim3(blocks), dim3(256), shmem, s, act, N, H, W, w, b, K, out); break;
-    case 4: hipLaunchKernelGGL(classifier_kernel<4>, dim3(blocks), dim3(256), shmem, s, act, N, H, W, w, b, K, out); break;
+    case 1: MBU_LAUNCH(classifier_kernel<1>, dim3(blocks), dim3(256), shmem, s, act, N, H, W, w, b, K, out); break;
+    case 2: MBU_LAUNCH(classifier_kernel<2>, dim3(blocks), dim3(256), shmem, s, act, N, H, W, w, b, K, out); break;
+    case 4: MBU_LAUNCH(classifier_kernel<4>, dim3(blocks), dim3(256), shmem, s, act, N, H, W, w, b, K, out); break;
     default: return fail(MBU_ERR_SHAPE, "classifier supports 32, 64 or 128 input channels, got %d", C);
     }
     return check_launch("classifier");

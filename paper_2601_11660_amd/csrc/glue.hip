@@ -101,7 +101,7 @@ int launch_maxpool(const uint32_t *in, int N, int H, int W, int Cw, uint32_t *ou
     long total = (long)N * Ho * Wo * Cv;
     if (total == 0) return MBU_OK;
     unsigned blocks = (unsigned)((total + 255) / 256);
-    MBU_DISPATCH_V(v, hipLaunchKernelGGL(maxpool_kernel<V>, dim3(blocks), dim3(256), 0, s,
+    MBU_DISPATCH_V(v, MBU_LAUNCH(maxpool_kernel<V>, dim3(blocks), dim3(256), 0, s,
                                          (const V *)in, total, Wo, Ho, Cv, (V *)out));
     return check_launch("maxpool2x2_bits");
 }
@@ -112,7 +112,7 @@ int launch_upsample(const uint32_t *in, int N, int H, int W, int Cw, uint32_t *o
     long total = (long)N * Ho * Wo * Cv;
     if (total == 0) return MBU_OK;
     unsigned blocks = (unsigned)((total + 255) / 256);
-    MBU_DISPATCH_V(v, hipLaunchKernelGGL(upsample_kernel<V>, dim3(blocks), dim3(256), 0, s,
+    MBU_DISPATCH_V(v, MBU_LAUNCH(upsample_kernel<V>, dim3(blocks), dim3(256), 0, s,
                                          (const V *)in, total, Wo, Ho, Cv, (V *)out));
     return check_launch("upsample2x_bits");
 }
@@ -124,7 +124,7 @@ int launch_concat(const uint32_t *a, int Caw, const uint32_t *b, int Cbw, long p
     long total = pixels * ((Caw + Cbw) / v);
     if (total == 0) return MBU_OK;
     unsigned blocks = (unsigned)((total + 255) / 256);
-    MBU_DISPATCH_V(v, hipLaunchKernelGGL(concat_kernel<V>, dim3(blocks), dim3(256), 0, s,
+    MBU_DISPATCH_V(v, MBU_LAUNCH(concat_kernel<V>, dim3(blocks), dim3(256), 0, s,
                                          (const V *)a, Caw / v, (const V *)b, Cbw / v, total,
                                          (V *)out));
     return check_launch("concat_bits");
@@ -137,7 +137,7 @@ int launch_upcat(const uint32_t *skip, int Csw, const uint32_t *low, int Clw, in
     long total = (long)N * H * W * ((Csw + Clw) / v);
     if (total == 0) return MBU_OK;
     unsigned blocks = (unsigned)((total + 255) / 256);
-    MBU_DISPATCH_V(v, hipLaunchKernelGGL(upcat_kernel<V>, dim3(blocks), dim3(256), 0, s,
+    MBU_DISPATCH_V(v, MBU_LAUNCH(upcat_kernel<V>, dim3(blocks), dim3(256), 0, s,
                                          (const V *)skip, Csw / v, (const V *)low, Clw / v, total,
                                          W, H, (V *)out));
     return check_launch("upsample_concat");

@@ -375,9 +375,10 @@ int mbu_event_record(void *event, void *stream)
 int mbu_event_elapsed_ms(void *start, void *stop, float *ms)
 {
     if (!start || !stop || !ms) return fail(MBU_ERR_NULL, "mbu_event_elapsed_ms: NULL argument");
-    if (hipEventSynchronize((hipEvent_t)stop) != hipSuccess) return fail(MBU_ERR_HIP, "hipEventSynchronize failed");
-    if (hipEventElapsedTime(ms, (hipEvent_t)start, (hipEvent_t)stop) != hipSuccess)
-        return fail(MBU_ERR_HIP, "hipEventElapsedTime failed");
+    hipError_t e = hipEventSynchronize((hipEvent_t)stop);
+    if (e != hipSuccess) return fail(MBU_ERR_HIP, "hipEventSynchronize: %s", hipGetErrorString(e));
+    e = hipEventElapsedTime(ms, (hipEvent_t)start, (hipEvent_t)stop);
+    if (e != hipSuccess) return fail(MBU_ERR_HIP, "hipEventElapsedTime: %s", hipGetErrorString(e));
     return MBU_OK;
 }
 

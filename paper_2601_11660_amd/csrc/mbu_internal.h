@@ -11,6 +11,13 @@ namespace mbu {
 int fail(int code, const char *fmt, ...);
 // Turn the HIP error state after a launch into a status.
 int check_launch(const char *what);
+// Launch wrapper: drops any stale error left by earlier, unrelated runtime calls so that
+// check_launch() reports this launch only.
+#define MBU_LAUNCH(kernel, grid, block, shmem, stream, ...)                         \
+    do {                                                                            \
+        (void)hipGetLastError();                                                    \
+        hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);        \
+    } while (0)
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline int ceil_div(int a, int b) { return (a + b - 1) / b; }

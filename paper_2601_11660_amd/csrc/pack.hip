@@ -57,10 +57,10 @@ int launch_pack_act(const void *src, int dtype, long pixels, int C, uint32_t *ds
     if (total == 0) return MBU_OK;
     unsigned blocks = (unsigned)((total + 255) / 256);
     if (dtype == 0)
-        hipLaunchKernelGGL(pack_act_kernel<int8_t>, dim3(blocks), dim3(256), 0, s,
+        MBU_LAUNCH(pack_act_kernel<int8_t>, dim3(blocks), dim3(256), 0, s,
                            (const int8_t *)src, pixels, C, Cw, dst);
     else
-        hipLaunchKernelGGL(pack_act_kernel<float>, dim3(blocks), dim3(256), 0, s,
+        MBU_LAUNCH(pack_act_kernel<float>, dim3(blocks), dim3(256), 0, s,
                            (const float *)src, pixels, C, Cw, dst);
     return check_launch("pack_act");
 }
@@ -150,10 +150,10 @@ int launch_pack_weights(const int8_t *w, const BlobLayout &L, void *blob, hipStr
 {
     long total = (long)L.cout_pad64 * 9 * 2 * L.ksteps;
     unsigned blocks = (unsigned)((total + 255) / 256);
-    hipLaunchKernelGGL(pack_weights_kernel, dim3(blocks), dim3(256), 0, s, w, L, (uint8_t *)blob);
+    MBU_LAUNCH(pack_weights_kernel, dim3(blocks), dim3(256), 0, s, w, L, (uint8_t *)blob);
     int rc = check_launch("pack_weights");
     if (rc) return rc;
-    hipLaunchKernelGGL(count_kept_kernel, dim3(ceil_div(L.cout_pad64, 256)), dim3(256), 0, s, L,
+    MBU_LAUNCH(count_kept_kernel, dim3(ceil_div(L.cout_pad64, 256)), dim3(256), 0, s, L,
                        (uint8_t *)blob);
     return check_launch("count_kept");
 }
