@@ -27,8 +27,9 @@ inline size_t round_up(size_t v, size_t m) { return (v + m - 1) / m * m; }
 // Section V (vector-ALU path): two bit planes, each uint32 [9][cin_words][cout_pad64]
 // (tap-major, output channel fastest so 64 lanes read 64 consecutive words), and the
 // kept-weight counts int32 [10][cout_pad64]: rows 0..8 per tap, row 9 the total.
-// Section M (matrix-core path): 4-bit codes, uint4 [cout_tiles32][9][ksteps][64 lanes],
-// one 16-byte fragment per lane and (32 output channels, tap, 64 input channels).
+// Section M (matrix-core path): 4-bit codes, uint4 [cout_pad64/64][ksteps][9 taps][2][64 lanes],
+// one 16-byte fragment per lane and (32 output channels, tap, 64 input channels); the 18
+// fragments one wave needs for a 64-channel step are contiguous (18 KB).
 struct BlobLayout {
     int cout, cin;
     int cin_words;     // ceil(cin/32)

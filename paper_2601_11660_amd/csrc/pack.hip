@@ -115,12 +115,12 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const int8_t *__restr
             }
             d[dd] = v;
         }
-        int tile = o >> 5;
+        int tile64 = o >> 6, m = (o >> 5) & 1;
         int row = tile_channel_to_row(o & 31);
         int kstep = k >> 1, half = k & 1;
         int lane = half * 32 + row;
         uint4 *F = reinterpret_cast<uint4 *>(blob + L.off_f4);
-        size_t at = (((size_t)tile * 9 + tap) * L.ksteps + kstep) * 64 + lane;
+        size_t at = ((((size_t)tile64 * L.ksteps + kstep) * 9 + tap) * 2 + m) * 64 + lane;
         F[at] = make_uint4(d[0], d[1], d[2], d[3]);
     }
 }
