@@ -85,7 +85,7 @@ static int build_plan(const mbu_unet_desc *d, int N, int H, int W, std::vector<S
     if (d->levels < 1 || d->levels > 6) return fail(MBU_ERR_SHAPE, "%s: levels must be 1..6", fn);
     if (d->base <= 0 || d->base % 32) return fail(MBU_ERR_SHAPE, "%s: base must be a positive multiple of 32", fn);
     if (d->in_channels != 1 && d->in_channels != 3) return fail(MBU_ERR_SHAPE, "%s: in_channels must be 1 or 3", fn);
-    if (d->n_classes <= 0 || d->n_classes > 64) return fail(MBU_ERR_SHAPE, "%s: n_classes must be 1..64", fn);
+    if (d->n_classes <= 0 || d->n_classes > 32) return fail(MBU_ERR_SHAPE, "%s: n_classes must be 1..32", fn);
     if (d->base != 32 && d->base != 64 && d->base != 128)
         return fail(MBU_ERR_SHAPE, "%s: base must be 32, 64 or 128 (classifier width)", fn);
     if (!d->convs) return fail(MBU_ERR_NULL, "%s: convs is NULL", fn);
