@@ -64,6 +64,13 @@ const char *mbu_last_error(void);
 int mbu_set_conv_path(int path);
 int mbu_get_conv_path(void);
 
+/* Benchmarking hook: force the kernel variant of the matrix-path convolution process-wide.
+ * kernel 0 = let the library choose per layer (default); 1 = block-cooperative kernel
+ * (four waves share a staged window, 4 rows x 64 channels per wave); 3 = persistent
+ * wave-private kernel with 3 rows x 64 channels per wave; 6 = the same with 6 rows x 32
+ * channels.  `reserved` must be 0.  Results never depend on it.  MBU_ERR_ARG otherwise. */
+int mbu_set_conv_tuning(int kernel, int reserved);
+
 /* Bit-packing of activations (Sec. 1: many binary values are grouped into one word
  * so one instruction handles them; Algorithm 1 consumes such fragments).
  *   src       NHWC [N][H][W][C]; src_dtype 0: int8 values, bit = (v > 0);

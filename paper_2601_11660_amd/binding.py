@@ -19,7 +19,7 @@ MBU_ERR_NULL, MBU_ERR_SHAPE, MBU_ERR_ALIGN, MBU_ERR_WORKSPACE, MBU_ERR_HIP, MBU_
 PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
 
 EXPORTS = [
-    "mbu_last_error", "mbu_set_conv_path", "mbu_get_conv_path", "mbu_pack_act",
+    "mbu_last_error", "mbu_set_conv_path", "mbu_get_conv_path", "mbu_set_conv_tuning", "mbu_pack_act",
     "mbu_packed_weights_bytes", "mbu_pack_weights", "mbu_conv3x3_masked_binary",
     "mbu_maxpool2x2_bits", "mbu_upsample2x_bits", "mbu_concat_bits", "mbu_unet_num_steps",
     "mbu_unet_step_info", "mbu_unet_workspace_bytes", "mbu_unet_forward",
@@ -112,6 +112,11 @@ def set_conv_path(path: int) -> None:
 
 def get_conv_path() -> int:
     return lib().mbu_get_conv_path()
+
+
+def set_conv_tuning(kernel: int = 0) -> None:
+    """mbu_set_conv_tuning: 0 automatic, 1 block-cooperative, 3 / 6 wave-private variants."""
+    check(lib().mbu_set_conv_tuning(kernel, 0))
 
 
 # Packed words are stored in int32 tensors (same bits as the ABI's uint32).

@@ -53,29 +53,32 @@ constexpr int HALO_W = TW + 2;
 // ---------------------------------------------------------------------------------
 // Fast kernel (packed bits only).
 //
-// Block = 4 waves arranged WM x WN: WM groups of RW image rows, WN groups of 64 output
-// channels; block tile = (RW*WM) rows x 32 pixels x (64*WN) channels.  A wave owns
-// RW x 2 accumulator tiles (RW = 4: 128 registers).
+// Every wave works alone: no barrier and no data shared between the waves of a block.
+// A wave owns one 64-channel output tile for its whole life and walks over pixel tiles
+// of RW image rows x 32 pixels (RW x 2 accumulator tiles, RW = 4: 128 registers).  Its
+// work is the flat sequence of steps (pixel tile, 64-channel input step ks).
 //
-// K loop over 64-channel steps ks; inside a step three "groups", one per kernel column
-// kx.  A group needs the 3 x 2 weight fragments of taps (ky, kx) (24 registers) and
-// RW+2 activation fragments (LDS rows rho = r + ky), each feeding every (r, ky) pair
-// with r + ky = rho: 6*RW matrix instructions per RW+2 LDS reads.  All 18 fragments of
-// a step stay in registers; as soon as a group has issued its matrix instructions its
-// registers are refilled with the same group's fragments of step ks+1, so weights
-// arrive a whole step (three groups) ahead of their use.
+// Step = three "groups", one per kernel column kx.  A group needs the 3 x 2 weight
+// fragments of taps (ky, kx) (24 registers) and RW+2 activation fragments (LDS rows
+// rho = r + ky), each feeding every (r, ky) pair with r + ky = rho: 6*RW matrix
+// instructions per RW+2 LDS reads.  All 18 weight fragments of a step stay in
+// registers; as soon as a group has issued its matrix instructions its registers are
+// refilled with the same group's fragments of the next step, so weights arrive a whole
+// step ahead of their use (with a single input step they simply stay).
 //
-// The halo window of step ks+1 is fetched from global memory at the start of step ks,
-// expanded and written to the other LDS buffer at its end; one barrier per step.  The
-// loop body has no branches: halo pixels outside the image are loaded from a clamped
-// address and expanded with zero masks, the last step refetches itself.
+// The (RW+2) x 34 pixel halo window of the NEXT step - which may belong to the next
+// pixel tile - is fetched from global memory at the start of a step, expanded from bits
+// to nibbles and written to the wave's other LDS buffer at its end, so the matrix
+// pipeline never waits for staging, also across tile boundaries.  The step body has no
+// branches: halo pixels outside the image are loaded from a clamped address and
+// expanded with zero masks; after its last step a wave re-stages its last window.
 //
-// Epilogue: accumulators start at -theta (exact in fp32 after clamping theta to
-// +-2^22, which cannot change any comparison because |R| <= 9*Cin < 2^20), so the
+// Epilogue per tile: accumulators start at -theta (exact in fp32 after clamping theta
+// to +-2^22, which cannot change any comparison because |R| <= 9*Cin < 2^20), so the
 // output bit is the complement of the accumulator's sign bit: one funnel shift per
 // register collects 16 channel bits, one cross-half exchange completes the word.
-template <int RW>
-__device__ __forceinline__ void group_mma(v16f (&acc)[RW][2], const v4i (&Wg)[3][2],
+template <int RW, int MT>
+__device__ __forceinline__ void group_mma(v16f (&acc)[RW][MT], const v4i (&Wg)[3][MT],
                                           const uint4 *tb)
 {
 #pragma unroll
@@ -86,41 +89,240 @@ __device__ __forceinline__ void group_mma(v16f (&acc)[RW][2], const v4i (&Wg)[3]
         for (int ky = 0; ky < 3; ++ky) {
             const int r = rho - ky;
             if (r >= 0 && r < RW) {
-                acc[r][0] = mfma_f4(Wg[ky][0], B, acc[r][0]);
-                acc[r][1] = mfma_f4(Wg[ky][1], B, acc[r][1]);
+#pragma unroll
+                for (int m = 0; m < MT; ++m) acc[r][m] = mfma_f4(Wg[ky][m], B, acc[r][m]);
             }
         }
     }
 }
 
-// fragments of taps (ky, kx), ky = 0..2, both 32-channel halves of the wave's 64 channels;
-// wk points at [tap 0][m 0][lane] of one 64-channel step of this wave's channel tile
-__device__ __forceinline__ void load_group(v4i (&Wg)[3][2], const uint4 *wk, int kx)
+// fragments of taps (ky, kx), ky = 0..2, of the wave's MT 32-channel tiles; wk points at
+// [tap 0][this wave's first 32-channel tile][lane] of one 64-channel input step
+template <int MT>
+__device__ __forceinline__ void load_group(v4i (&Wg)[3][MT], const uint4 *wk, int kx)
 {
 #pragma unroll
     for (int ky = 0; ky < 3; ++ky)
 #pragma unroll
-        for (int m = 0; m < 2; ++m) {
+        for (int m = 0; m < MT; ++m) {
             const uint4 a = wk[((ky * 3 + kx) * 2 + m) * 64];
             Wg[ky][m] = (v4i){(int)a.x, (int)a.y, (int)a.z, (int)a.w};
         }
 }
 
-template <int RW, int WM, int WN, bool CW_EVEN>
+// RW image rows x 32 pixels x (32*MT) output channels per wave: (RW, MT) = (4, 2) or (8, 1)
+// both give 128 accumulator registers; MT = 1 halves the weight registers and doubles
+// the reuse of every weight fragment at the price of more activation reads.
+template <int RW, int MT, bool CW_EVEN, bool ONE_STEP>
 __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
+    const uint32_t *__restrict__ act, int N, int H, int W, int Cw, int ksteps,
+    const uint4 *__restrict__ wfrag, int Cout, int ctiles, int slots, int ptiles,
+    const int32_t *__restrict__ thresh, uint32_t *__restrict__ out_bits)
+{
+    constexpr int HR = RW + 2;
+    constexpr int NPIX = HR * HALO_W;            // halo pixels per step
+    constexpr int NLD = (NPIX + 63) / 64;        // staged pixels per lane
+    constexpr int TILE = HR * 2 * HALO_W;        // uint4 entries per buffer, [row][half][col]
+    __shared__ uint4 lds[4][2][TILE];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int gw = blockIdx.x * 4 + wave;
+    if (gw >= slots * ctiles) return;             // whole wave leaves; nothing is shared
+    const int ct = gw % ctiles;                   // (32*MT)-channel output tile, fixed for the wave
+    const int slot = gw / ctiles;
+    const int col = lane & 31, half = lane >> 5;
+    const int tiles_x = (W + TW - 1) / TW;
+    const int tiles_y = (H + RW - 1) / RW;
+    uint4(*tile)[TILE] = lds[wave];
+
+    // ---- -theta for the MT x 16 channels of this lane
+    float init[MT][16];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        const int cbase = (ct * MT + m) * 32 + 16 * half;  // 16 consecutive channels per lane
+        int th[16];
+        if (cbase < Cout) {                                 // Cout % 32 == 0: all 16 or none
+            const int4 *tp = reinterpret_cast<const int4 *>(thresh + cbase);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int4 t = tp[q];
+                th[4 * q] = t.x; th[4 * q + 1] = t.y; th[4 * q + 2] = t.z; th[4 * q + 3] = t.w;
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) th[i] = 0;
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            init[m][i] = 0.0f - (float)max(-(1 << 22), min(1 << 22, th[i]));
+    }
+
+    // ---- staging plan for the window of a pixel tile: lane handles halo pixels lane + 64*j
+    uint32_t src[NLD];            // word offset of the (clamped) pixel from `act`
+    uint32_t m8[NLD];             // 0x88888888 inside the image, 0 outside
+    auto plan = [&](int pt) {
+        const int tx = pt % tiles_x;
+        const int q = pt / tiles_x;
+        const int ty = q % tiles_y;
+        const int n = q / tiles_y;
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+            int p = lane + 64 * j;
+            p = p < NPIX ? p : 0;     // surplus lanes duplicate pixel 0 (same data, same slot)
+            const int r = p / HALO_W, c = p - r * HALO_W;
+            const int yy = ty * RW + r - 1, xx = tx * TW + c - 1;
+            const bool in = yy >= 0 && yy < H && xx >= 0 && xx < W;
+            const int yc = min(max(yy, 0), H - 1), xc = min(max(xx, 0), W - 1);
+            src[j] = (uint32_t)((((size_t)n * H + yc) * W + xc) * Cw);
+            m8[j] = in ? 0x88888888u : 0u;
+        }
+    };
+    uint2 gq[NLD];
+    auto stage_issue = [&](int ks) {
+        const uint32_t *base = act + 2 * ks;
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+            if (CW_EVEN) {
+                gq[j] = *reinterpret_cast<const uint2 *>(base + src[j]);
+            } else {
+                gq[j].x = base[src[j]];
+                gq[j].y = act[src[j] + min(2 * ks + 1, Cw - 1)];
+            }
+        }
+    };
+    auto stage_commit = [&](int ks, uint4 *buf) {
+        const bool second = CW_EVEN || (2 * ks + 1 < Cw);
+#pragma unroll
+        for (int j = 0; j < NLD; ++j) {
+            int p = lane + 64 * j;
+            p = p < NPIX ? p : 0;
+            const int r = p / HALO_W, c = p - r * HALO_W;
+            uint4 *d = buf + (r * 2) * HALO_W + c;
+            const uint32_t a = gq[j].x, b = gq[j].y;
+            const uint32_t k8 = m8[j], k2 = k8 >> 2;
+            const uint32_t l8 = second ? k8 : 0u, l2 = l8 >> 2;
+            uint4 e0, e1;
+            e0.x = ((a << 3) & k8) | k2; e0.y = ((a << 2) & k8) | k2;
+            e0.z = ((a << 1) & k8) | k2; e0.w = (a & k8) | k2;
+            e1.x = ((b << 3) & l8) | l2; e1.y = ((b << 2) & l8) | l2;
+            e1.z = ((b << 1) & l8) | l2; e1.w = (b & l8) | l2;
+            d[0] = e0;
+            d[HALO_W] = e1;
+        }
+    };
+
+    // ---- weight fragments: [tile64][kstep][tap][m][lane], 18 KB per step and 64 channels
+    const int t64 = (ct * MT) >> 1, mfirst = (ct * MT) & 1;
+    const uint4 *wk = wfrag + ((size_t)t64 * ksteps * 18 + mfirst) * 64 + lane;
+    v4i Wg[3][3][MT];   // [kx][ky][m]
+    plan(slot);
+    stage_issue(0);
+#pragma unroll
+    for (int kx = 0; kx < 3; ++kx) load_group<MT>(Wg[kx], wk, kx);
+    stage_commit(0, tile[0]);
+
+    const int tb_off = half * HALO_W + col;
+    const int Cow = Cout >> 5;
+    int buf = 0;
+    for (int pt = slot; pt < ptiles; pt += slots) {
+        v16f acc[RW][MT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+#pragma unroll
+                for (int r = 0; r < RW; ++r) acc[r][m][i] = init[m][i];
+
+        for (int ks = 0; ks < ksteps; ++ks) {
+            // the step after this one: next input step of this tile, or step 0 of the wave's
+            // next tile (its own last window again when there is none)
+            const bool last = ks + 1 == ksteps;
+            const int kn = last ? 0 : ks + 1;
+            if (last) plan(pt + slots < ptiles ? pt + slots : pt);
+            const uint4 *tb = tile[buf] + tb_off;
+            // The scheduling fences keep every fetch where it is written: issued as early as
+            // its destination registers are free, a whole step ahead of its use.
+            stage_issue(kn);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int kx = 0; kx < 3; ++kx) {
+                group_mma<RW, MT>(acc, Wg[kx], tb + kx);
+                if (!ONE_STEP) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_group<MT>(Wg[kx], wk + (size_t)kn * (18 * 64), kx);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            buf ^= 1;
+            stage_commit(kn, tile[buf]);
+            // LDS instructions of one wave execute in order, so the fragment reads of the
+            // next step see these writes; the fence only stops the compiler from moving them.
+            __builtin_amdgcn_wave_barrier();
+        }
+
+        // ---- epilogue of this pixel tile
+        const int tx = pt % tiles_x;
+        const int q = pt / tiles_x;
+        const int ty = q % tiles_y;
+        const int n = q / tiles_y;
+        const int x = tx * TW + col;
+#pragma unroll
+        for (int r = 0; r < RW; ++r) {
+            const int y = ty * RW + r;
+            uint32_t s[MT];
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                s[m] = 0;
+#pragma unroll
+                for (int i = 15; i >= 0; --i)
+                    s[m] = __builtin_amdgcn_alignbit(s[m], __float_as_uint(acc[r][m][i]), 31);
+            }
+            // s = sign bits (1 = below threshold) of channels 16*half + i of tile m
+            uint32_t word;
+            int widx;
+            if (MT == 2) {
+                const uint32_t mine = (~s[0] & 0xffffu) | (~s[MT - 1] << 16);
+                const uint32_t other = (uint32_t)__shfl_xor((int)mine, 32);
+                word = half == 0 ? ((mine & 0xffffu) | (other << 16))
+                                 : ((other >> 16) | (mine & 0xffff0000u));
+                widx = ct * 2 + half;       // half 0 stores the first word, half 1 the second
+            } else {
+                const uint32_t mine = ~s[0] & 0xffffu;
+                const uint32_t other = (uint32_t)__shfl_xor((int)mine, 32);
+                word = half == 0 ? (mine | (other << 16)) : (other | (mine << 16));
+                widx = (half == (r & 1)) ? ct : Cow;   // alternate the storing half per row
+            }
+            if (widx < Cow && y < H && x < W)
+                out_bits[(((size_t)n * H + y) * W + x) * Cow + widx] = word;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Block-cooperative variant for layers with several input steps: the four waves of a
+// block share one staged halo window ((RW*WM+2) x 34 pixels, double buffered, one
+// barrier per step) and are arranged WM x WN over image rows x 64-channel output tiles.
+// Less staging work per wave than the wave-private kernel above; used when the K loop
+// is long enough to amortise the per-tile prologue and epilogue.
+template <int RW, int WM, int WN, bool CW_EVEN>
+__global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
     const uint32_t *__restrict__ act, int N, int H, int W, int Cw, int ksteps,
     const uint4 *__restrict__ wfrag, int Cout, int tiles64, const int32_t *__restrict__ thresh,
     uint32_t *__restrict__ out_bits)
 {
+    static_assert(WM * WN == 4, "four waves per block");
+    constexpr int NT = 256;
     constexpr int TH = RW * WM;
     constexpr int HR = TH + 2;
     constexpr int NPIX = HR * HALO_W;            // halo pixels per step
-    constexpr int NLD = (NPIX + 255) / 256;      // staged pixels per thread
+    constexpr int NLD = (NPIX + NT - 1) / NT;      // staged pixels per thread
     constexpr int TILE = HR * 2 * HALO_W;        // uint4 entries per buffer, [row][half][col]
     __shared__ uint4 tile[2][TILE];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int tid = threadIdx.x;
     const int wm = wave % WM, wn = wave / WM;
     const int col = lane & 31, half = lane >> 5;
     const int tiles_x = (W + TW - 1) / TW;
@@ -161,13 +363,13 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
         }
     }
 
-    // ---- staging plan of this thread: halo pixels p = tid + 256*j
+    // ---- staging plan of this thread: halo pixels p = tid + NT*j
     const uint32_t *src[NLD];     // first word of the (clamped) pixel
     uint32_t m8[NLD], m2[NLD];    // expansion masks, zero for pixels outside the image
     int dst[NLD];                 // LDS entry of (row, half 0, col)
 #pragma unroll
     for (int j = 0; j < NLD; ++j) {
-        int p = threadIdx.x + 256 * j;
+        int p = tid + NT * j;
         p = p < NPIX ? p : 0;     // surplus threads duplicate pixel 0 (same data, same slot)
         const int r = p / HALO_W, c = p - r * HALO_W;
         const int yy = y0 + r - 1, xx = x0 + c - 1;
@@ -212,7 +414,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
     v4i Wg[3][3][2];   // [kx][ky][m]
     stage_issue(0);
 #pragma unroll
-    for (int kx = 0; kx < 3; ++kx) load_group(Wg[kx], wk, kx);
+    for (int kx = 0; kx < 3; ++kx) load_group<2>(Wg[kx], wk, kx);
     stage_commit(0, tile[0]);
     __syncthreads();
 
@@ -227,9 +429,9 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int kx = 0; kx < 3; ++kx) {
-            group_mma<RW>(acc, Wg[kx], tb + kx);
+            group_mma<RW, 2>(acc, Wg[kx], tb + kx);
             __builtin_amdgcn_sched_barrier(0);
-            load_group(Wg[kx], wn_ptr, kx);
+            load_group<2>(Wg[kx], wn_ptr, kx);
             __builtin_amdgcn_sched_barrier(0);
         }
         stage_commit(kn, tile[(ks + 1) & 1]);
@@ -366,26 +568,57 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(
     }
 }
 
-template <int RW, int WM, int WN, bool CW_EVEN>
+int g_tune_rw = 0, g_tune_wm = 0;   // 0 = automatic
+
+template <int RW, int MT, bool CW_EVEN, bool ONE_STEP>
 static int launch_bits_t(const uint32_t *act, int N, int H, int W, const BlobLayout &L,
-                       const uint4 *wfrag, const int32_t *thresh, uint32_t *out_bits, hipStream_t s)
+                         const uint4 *wfrag, const int32_t *thresh, uint32_t *out_bits,
+                         hipStream_t s)
+{
+    const int ctiles = L.cout_pad64 / (32 * MT);
+    const long ptiles = (long)N * ceil_div(H, RW) * ceil_div(W, TW);
+    if (ptiles > 0x7fffffffL) return fail(MBU_ERR_SHAPE, "too many tiles for one launch");
+    // two waves per SIMD over the whole chip; every wave keeps one output-channel tile
+    // and strides over the pixel tiles
+    const int max_waves = 2 * 4 * 256;
+    if (ctiles > max_waves) return fail(MBU_ERR_SHAPE, "too many output channels");
+    const int slots = (int)min(ptiles, (long)(max_waves / ctiles));
+    const int waves = slots * ctiles;
+    MBU_LAUNCH((conv_mfma_bits_kernel<RW, MT, CW_EVEN, ONE_STEP>), dim3(ceil_div(waves, 4)),
+               dim3(256), 0, s, act, N, H, W, L.cin_words, L.ksteps, wfrag, L.cout, ctiles, slots,
+               (int)ptiles, thresh, out_bits);
+    return check_launch("conv_mfma_bits");
+}
+
+template <int RW, int WM, int WN>
+static int launch_block(const uint32_t *act, int N, int H, int W, const BlobLayout &L,
+                        const uint4 *wfrag, const int32_t *thresh, uint32_t *out_bits, hipStream_t s)
 {
     const int tiles64 = L.cout_pad64 / 64;
     long tiles = (long)N * ceil_div(H, RW * WM) * ceil_div(W, TW);
     if (tiles > 0x7fffffffL) return fail(MBU_ERR_SHAPE, "too many tiles for one launch");
     dim3 grid((unsigned)tiles, (unsigned)ceil_div(tiles64, WN));
-    MBU_LAUNCH((conv_mfma_bits_kernel<RW, WM, WN, CW_EVEN>), grid, dim3(256), 0, s, act, N, H, W,
-               L.cin_words, L.ksteps, wfrag, L.cout, tiles64, thresh, out_bits);
-    return check_launch("conv_mfma_bits");
+    if (L.cin_words % 2 == 0)
+        MBU_LAUNCH((conv_mfma_block_kernel<RW, WM, WN, true>), grid, dim3(256), 0, s, act, N, H, W,
+                   L.cin_words, L.ksteps, wfrag, L.cout, tiles64, thresh, out_bits);
+    else
+        MBU_LAUNCH((conv_mfma_block_kernel<RW, WM, WN, false>), grid, dim3(256), 0, s, act, N, H, W,
+                   L.cin_words, L.ksteps, wfrag, L.cout, tiles64, thresh, out_bits);
+    return check_launch("conv_mfma_block");
 }
 
-template <int RW, int WM, int WN>
+template <int RW, int MT>
 static int launch_bits(const uint32_t *act, int N, int H, int W, const BlobLayout &L,
                        const uint4 *wfrag, const int32_t *thresh, uint32_t *out_bits, hipStream_t s)
 {
+    if (L.ksteps == 1) {
+        if (L.cin_words % 2 == 0)
+            return launch_bits_t<RW, MT, true, true>(act, N, H, W, L, wfrag, thresh, out_bits, s);
+        return launch_bits_t<RW, MT, false, true>(act, N, H, W, L, wfrag, thresh, out_bits, s);
+    }
     if (L.cin_words % 2 == 0)
-        return launch_bits_t<RW, WM, WN, true>(act, N, H, W, L, wfrag, thresh, out_bits, s);
-    return launch_bits_t<RW, WM, WN, false>(act, N, H, W, L, wfrag, thresh, out_bits, s);
+        return launch_bits_t<RW, MT, true, false>(act, N, H, W, L, wfrag, thresh, out_bits, s);
+    return launch_bits_t<RW, MT, false, false>(act, N, H, W, L, wfrag, thresh, out_bits, s);
 }
 
 int launch_conv_mfma(const uint32_t *act, int N, int H, int W, const BlobLayout &L,
@@ -402,20 +635,21 @@ int launch_conv_mfma(const uint32_t *act, int N, int H, int W, const BlobLayout 
                    L.ksteps, wfrag, L.cout, thresh, out_bits, out_acc);
         return check_launch("conv_mfma_acc");
     }
-    // Shape of the block: spread the four waves over output channels when there are
-    // enough of them, over image rows otherwise; halve the rows per wave when the
-    // launch would not give every SIMD two waves.
+    // Kernel choice (measured on MI355X): with a single 64-channel input step the per-tile
+    // prologue and epilogue dominate and the persistent wave-private kernel wins (3 rows x 64
+    // channels per wave fit the register file together with the resident weights); with
+    // several steps the block-cooperative kernel stages less per wave and wins.
     const int tiles64 = L.cout_pad64 / 64;
-    const int WN = (tiles64 % 4 == 0) ? 4 : (tiles64 % 2 == 0) ? 2 : 1;
-    const int WM = 4 / WN;
-    const long blocks4 = (long)N * ceil_div(H, 4 * WM) * ceil_div(W, TW) * ceil_div(tiles64, WN);
-    const bool small = blocks4 < 2 * 256;
-#define MBU_GO(RW_, WM_, WN_) return launch_bits<RW_, WM_, WN_>(act, N, H, W, L, wfrag, thresh, out_bits, s)
-    if (WN == 4) { if (small) MBU_GO(2, 1, 4); else MBU_GO(4, 1, 4); }
-    if (WN == 2) { if (small) MBU_GO(2, 2, 2); else MBU_GO(4, 2, 2); }
-    if (small) MBU_GO(2, 4, 1);
-    MBU_GO(4, 4, 1);
-#undef MBU_GO
+    const int mode = g_tune_rw;   // 0 = automatic; see mbu_set_conv_tuning
+    const bool want_block = mode == 1 || (mode == 0 && L.ksteps > 1);
+    if (want_block) {
+        // waves of a block over output-channel tiles when there are enough of them
+        if (tiles64 % 4 == 0) return launch_block<4, 1, 4>(act, N, H, W, L, wfrag, thresh, out_bits, s);
+        if (tiles64 % 2 == 0) return launch_block<4, 2, 2>(act, N, H, W, L, wfrag, thresh, out_bits, s);
+        return launch_block<4, 4, 1>(act, N, H, W, L, wfrag, thresh, out_bits, s);
+    }
+    if (mode == 6) return launch_bits<6, 1>(act, N, H, W, L, wfrag, thresh, out_bits, s);
+    return launch_bits<3, 2>(act, N, H, W, L, wfrag, thresh, out_bits, s);
 }
 
 }  // namespace mbu

@@ -171,6 +171,15 @@ int mbu_set_conv_path(int path)
 
 int mbu_get_conv_path(void) { return g_conv_path; }
 
+int mbu_set_conv_tuning(int rows_per_wave, int reserved)
+{
+    if ((rows_per_wave != 0 && rows_per_wave != 1 && rows_per_wave != 3 && rows_per_wave != 6) || reserved != 0)
+        return fail(MBU_ERR_ARG, "mbu_set_conv_tuning: kernel in {0,1,3,6}, second argument 0");
+    g_tune_rw = rows_per_wave;
+    g_tune_wm = 0;
+    return MBU_OK;
+}
+
 int mbu_pack_act(const void *src, int src_dtype, int N, int H, int W, int C, uint32_t *dst,
                  void *stream)
 {

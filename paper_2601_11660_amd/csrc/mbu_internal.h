@@ -53,6 +53,9 @@ __host__ __device__ inline int tile_channel_to_row(int c) {
     return 8 * g + 4 * h + j;
 }
 
+// block-shape override of the matrix-path convolution (0 = automatic)
+extern int g_tune_rw, g_tune_wm;
+
 // ---- kernel launchers (arguments already validated) ----
 int launch_pack_act(const void *src, int dtype, long pixels, int C, uint32_t *dst, hipStream_t s);
 int launch_pack_weights(const int8_t *w, const BlobLayout &L, void *blob, hipStream_t s);

@@ -20,7 +20,7 @@ def header_symbols():
 def test_library_exports_every_declared_symbol():
     L = B.lib()
     syms = header_symbols()
-    assert len(syms) >= 18
+    assert len(syms) >= 19
     for s in syms:
         assert hasattr(L, s), s
     assert sorted(B.EXPORTS) == syms
@@ -61,6 +61,9 @@ def test_packed_weight_size_and_path_switch():
     n = ctypes.c_size_t()
     assert B.lib().mbu_packed_weights_bytes(64, 64, None) == B.MBU_ERR_NULL
     assert B.lib().mbu_set_conv_path(9) == B.MBU_ERR_ARG
+    assert B.lib().mbu_set_conv_tuning(5, 0) == B.MBU_ERR_ARG
+    assert B.lib().mbu_set_conv_tuning(3, 1) == B.MBU_ERR_ARG
+    assert B.lib().mbu_set_conv_tuning(0, 0) == 0
     B.set_conv_path(B.PATH_VALU)
     assert B.get_conv_path() == B.PATH_VALU
     B.set_conv_path(B.PATH_AUTO)

@@ -20,6 +20,7 @@ PATHS = [(B.PATH_VALU, "valu"), (B.PATH_MFMA, "mfma")]
 def _auto_path():
     yield
     B.set_conv_path(B.PATH_AUTO)
+    B.set_conv_tuning(0)
     torch.cuda.synchronize()
 
 
@@ -127,6 +128,20 @@ def test_conv_degenerate_masks_and_ties(path, pname):
         th = np.full(64, v, np.int32)
         bits, _ = run_layer(synth.ConvCase(case.a, case.w, th, 0.6), path)
         assert np.array_equal(bits, bitref.pack_pm1(O.threshold(acc_ref, th)))
+
+
+@pytest.mark.parametrize("kernel", [1, 3, 6])
+@pytest.mark.parametrize("shape", SMALL_SHAPES + [(1, 100, 100, 128, 128, 0.6), (2, 31, 67, 64, 192, 0.5)])
+def test_every_matrix_kernel_variant_matches_oracle(shape, kernel):
+    """The library picks a kernel variant per layer shape; each variant must be exact on
+    every shape (single and multiple input steps, ragged tiles, odd word counts)."""
+    N, H, W, Cin, Cout, keep = shape
+    say(f"conv mfma kernel={kernel} N={N} H={H} W={W} Cin={Cin} Cout={Cout}")
+    case = synth.conv_case(8, 0, N, H, W, Cin, Cout, keep)
+    _, out_ref = O.masked_binary_layer(case.a, case.w, case.theta)
+    B.set_conv_tuning(kernel)
+    bits, _ = run_layer(case, B.PATH_MFMA, want_acc=False)
+    assert np.array_equal(bits, bitref.pack_pm1(out_ref))
 
 
 def test_paths_agree_and_are_deterministic():
