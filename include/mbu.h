@@ -113,6 +113,25 @@ int mbu_conv3x3_masked_binary(const uint32_t *act, int N, int H, int W, int Cin,
                               const void *packed_w, int Cout, const int32_t *thresh,
                               uint32_t *out_bits, int32_t *out_acc, void *stream);
 
+/* The same layer with the U-Net glue around it fused in (matrix path only, whatever
+ * mbu_set_conv_path says): the skip concatenation and the 2x up-sampling that feed a
+ * decoder layer (Sec. 2.1) are read in place instead of being materialised, and the 2x2
+ * pooling that follows an encoder layer (Sec. 3.2.2) is written as a second output.
+ *   act       packed [N][H][W][Ca/32]; Ca % 32 == 0 when `low` is given
+ *   low       packed [N][H/2][W/2][ceil(Clow/32)] or NULL (then Clow must be 0); the layer's
+ *             input is the channel concatenation [act | low up-sampled 2x nearest], i.e.
+ *             input pixel (y, x) takes its last Clow channels from low[y/2][x/2]
+ *   packed_w  blob packed for (Cout, Cin = Ca + Clow)
+ *   out_bits  packed [N][H][W][Cout/32], or NULL
+ *   out_pool  packed [N][H/2][W/2][Cout/32] = bitwise OR of each 2x2 window of the layer's
+ *             output, or NULL
+ * H and W must be even when `low` or `out_pool` is given; at least one output non-NULL.
+ * Errors as for mbu_conv3x3_masked_binary. */
+int mbu_conv3x3_masked_binary_fused(const uint32_t *act, int Ca, const uint32_t *low, int Clow,
+                                    int N, int H, int W, const void *packed_w, int Cout,
+                                    const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool,
+                                    void *stream);
+
 /* 2x2 stride-2 max pooling on +-1 values = bitwise OR of the four packed words
  * (Sec. 3.2.2 lists pooling as trivial).  H and W must be even.
  *   in [N][H][W][Cw] -> out [N][H/2][W/2][Cw], Cw = ceil(C/32). */
@@ -160,6 +179,13 @@ typedef struct mbu_unet_desc {
                                        hipEvent_t: event i is recorded on the stream
                                        before step i, the last one after the final
                                        step.  NULL = no events.                   */
+    int fuse;                       /* 0: one kernel per step, every step's output is
+                                       written to the workspace.  1: on the matrix path
+                                       the "cat" steps are folded into the layer that
+                                       reads them (their workspace region stays unwritten)
+                                       and pooling is folded into the layer before it
+                                       where that layer runs the block kernel; such
+                                       steps then take no time of their own.        */
 } mbu_unet_desc;
 
 /* Number of kernel steps the forward pass runs (stem, each conv, pool, up-sample +

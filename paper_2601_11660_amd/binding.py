@@ -21,6 +21,7 @@ PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
 EXPORTS = [
     "mbu_last_error", "mbu_set_conv_path", "mbu_get_conv_path", "mbu_set_conv_tuning", "mbu_pack_act",
     "mbu_packed_weights_bytes", "mbu_pack_weights", "mbu_conv3x3_masked_binary",
+    "mbu_conv3x3_masked_binary_fused",
     "mbu_maxpool2x2_bits", "mbu_upsample2x_bits", "mbu_concat_bits", "mbu_unet_num_steps",
     "mbu_unet_step_info", "mbu_unet_workspace_bytes", "mbu_unet_forward",
     "mbu_event_create", "mbu_event_destroy", "mbu_event_record", "mbu_event_elapsed_ms",
@@ -43,7 +44,7 @@ class UNetDesc(ctypes.Structure):
                 ("in_channels", ctypes.c_int), ("n_classes", ctypes.c_int),
                 ("stem_w", ctypes.c_void_p), ("convs", ctypes.POINTER(ConvLayer)),
                 ("cls_w", ctypes.c_void_p), ("cls_b", ctypes.c_void_p),
-                ("step_events", ctypes.POINTER(ctypes.c_void_p))]
+                ("step_events", ctypes.POINTER(ctypes.c_void_p)), ("fuse", ctypes.c_int)]
 
 
 _lib = None
@@ -63,6 +64,7 @@ def lib() -> ctypes.CDLL:
         L.mbu_packed_weights_bytes.argtypes = [ci, ci, ctypes.POINTER(ctypes.c_size_t)]
         L.mbu_pack_weights.argtypes = [vp, ci, ci, vp, vp]
         L.mbu_conv3x3_masked_binary.argtypes = [vp, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp]
+        L.mbu_conv3x3_masked_binary_fused.argtypes = [vp, ci, vp, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp]
         L.mbu_maxpool2x2_bits.argtypes = [vp, ci, ci, ci, ci, vp, vp]
         L.mbu_upsample2x_bits.argtypes = [vp, ci, ci, ci, ci, vp, vp]
         L.mbu_concat_bits.argtypes = [vp, ci, vp, ci, ci, ci, ci, vp, vp]
@@ -164,6 +166,24 @@ def conv3x3_masked_binary(act: torch.Tensor, cin: int, packed_w: torch.Tensor, c
     return out_bits, out_acc
 
 
+def conv3x3_masked_binary_fused(act: torch.Tensor, ca: int, low: Optional[torch.Tensor], clow: int,
+                                packed_w: torch.Tensor, cout: int, thresh: torch.Tensor,
+                                want_bits: bool = True, want_pool: bool = False
+                                ) -> Tuple[Optional[torch.Tensor], Optional[torch.Tensor]]:
+    """mbu_conv3x3_masked_binary_fused -> (packed bits or None, 2x2-pooled packed bits or None)."""
+    N, H, W, _ = act.shape
+    out_bits = (torch.empty((N, H, W, cout // 32), dtype=torch.int32, device=act.device)
+                if want_bits else None)
+    out_pool = (torch.empty((N, H // 2, W // 2, cout // 32), dtype=torch.int32, device=act.device)
+                if want_pool else None)
+    check(lib().mbu_conv3x3_masked_binary_fused(
+        _dev(act, (torch.int32,)), ca, _dev(low, (torch.int32,)) if low is not None else None, clow,
+        N, H, W, _dev(packed_w, (torch.uint8,)), cout, _dev(thresh, (torch.int32,)),
+        out_bits.data_ptr() if out_bits is not None else None,
+        out_pool.data_ptr() if out_pool is not None else None, _stream()))
+    return out_bits, out_pool
+
+
 def maxpool2x2_bits(x: torch.Tensor, c: int) -> torch.Tensor:
     N, H, W, Cw = x.shape
     out = torch.empty((N, H // 2, W // 2, Cw), dtype=torch.int32, device=x.device)
@@ -221,7 +241,7 @@ class UNet:
     """Owner of the device tensors and the host descriptor for mbu_unet_forward."""
 
     def __init__(self, stem_w: torch.Tensor, convs: Sequence[Tuple[torch.Tensor, torch.Tensor]],
-                 cls_w: torch.Tensor, cls_b: torch.Tensor, levels: int = 4):
+                 cls_w: torch.Tensor, cls_b: torch.Tensor, levels: int = 4, fuse: bool = True):
         """stem_w float32 [base,3,3,Ci]; convs: (w int8 OHWI, theta int32) device tensors in
         execution order; cls_w float32 [K,base]; cls_b float32 [K]."""
         self.levels = levels
@@ -247,7 +267,8 @@ class UNet:
         self.desc = UNetDesc(levels=levels, base=self.base, in_channels=self.in_channels,
                              n_classes=self.n_classes, stem_w=self.stem_w.data_ptr(),
                              convs=self._layers, cls_w=self.cls_w.data_ptr(),
-                             cls_b=self.cls_b.data_ptr(), step_events=None)
+                             cls_b=self.cls_b.data_ptr(), step_events=None,
+                             fuse=1 if fuse else 0)
         self.num_steps = lib().mbu_unet_num_steps(ctypes.byref(self.desc))
         if self.num_steps < 0:
             check(self.num_steps)

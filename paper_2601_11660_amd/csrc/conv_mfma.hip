@@ -305,18 +305,29 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
 // barrier per step) and are arranged WM x WN over image rows x 64-channel output tiles.
 // Less staging work per wave than the wave-private kernel above; used when the K loop
 // is long enough to amortise the per-tile prologue and epilogue.
-template <int RW, int WM, int WN, bool CW_EVEN>
+//
+// Two fusions of the decoder / encoder glue (Sec. 2.1) live here, because they only touch
+// the staging and the epilogue:
+//  TWO_SRC  the input is the channel concatenation [act | 2x-up-sampled low]: word k of a
+//           halo pixel (y, x) comes from act[y][x][k] for k < Cwa and from
+//           low[y/2][x/2][k - Cwa] otherwise - the skip concatenation and the nearest
+//           up-sampling are never materialised;
+//  POOL     besides its own output the layer writes the 2x2 OR-pooled output (max pooling
+//           of +-1 values): rows pair up inside a lane, columns with the neighbouring lane.
+template <int RW, int WM, int WN, bool CW_EVEN, bool TWO_SRC, bool POOL>
 __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
-    const uint32_t *__restrict__ act, int N, int H, int W, int Cw, int ksteps,
-    const uint4 *__restrict__ wfrag, int Cout, int tiles64, const int32_t *__restrict__ thresh,
-    uint32_t *__restrict__ out_bits)
+    const uint32_t *__restrict__ act, const uint32_t *__restrict__ low, int N, int H, int W,
+    int Cwa, int Cwb, int ksteps, const uint4 *__restrict__ wfrag, int Cout, int tiles64,
+    const int32_t *__restrict__ thresh, uint32_t *__restrict__ out_bits,
+    uint32_t *__restrict__ out_pool)
 {
     static_assert(WM * WN == 4, "four waves per block");
+    static_assert(!POOL || (RW % 2 == 0), "pooling pairs rows inside a wave");
     constexpr int NT = 256;
     constexpr int TH = RW * WM;
     constexpr int HR = TH + 2;
     constexpr int NPIX = HR * HALO_W;            // halo pixels per step
-    constexpr int NLD = (NPIX + NT - 1) / NT;      // staged pixels per thread
+    constexpr int NLD = (NPIX + NT - 1) / NT;    // staged pixels per thread
     constexpr int TILE = HR * 2 * HALO_W;        // uint4 entries per buffer, [row][half][col]
     __shared__ uint4 tile[2][TILE];
 
@@ -325,6 +336,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
     const int tid = threadIdx.x;
     const int wm = wave % WM, wn = wave / WM;
     const int col = lane & 31, half = lane >> 5;
+    const int Cw = Cwa + (TWO_SRC ? Cwb : 0);     // words per pixel of the (virtual) input
     const int tiles_x = (W + TW - 1) / TW;
     const int tiles_y = (H + TH - 1) / TH;
     int bid = blockIdx.x;
@@ -364,9 +376,10 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
     }
 
     // ---- staging plan of this thread: halo pixels p = tid + NT*j
-    const uint32_t *src[NLD];     // first word of the (clamped) pixel
-    uint32_t m8[NLD], m2[NLD];    // expansion masks, zero for pixels outside the image
-    int dst[NLD];                 // LDS entry of (row, half 0, col)
+    uint32_t offa[NLD];                  // word offset of the (clamped) pixel in act
+    uint32_t offb[TWO_SRC ? NLD : 1];    // ... of the pixel (y/2, x/2) in low
+    uint32_t m8[NLD];                    // 0x88888888 inside the image, 0 outside
+    const int Hl = H >> 1, Wl = W >> 1;
 #pragma unroll
     for (int j = 0; j < NLD; ++j) {
         int p = tid + NT * j;
@@ -375,20 +388,34 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
         const int yy = y0 + r - 1, xx = x0 + c - 1;
         const bool in = yy >= 0 && yy < H && xx >= 0 && xx < W;
         const int yc = min(max(yy, 0), H - 1), xc = min(max(xx, 0), W - 1);
-        src[j] = act + (((size_t)n * H + yc) * W + xc) * Cw;
+        offa[j] = (uint32_t)((((size_t)n * H + yc) * W + xc) * Cwa);
+        if (TWO_SRC) offb[j] = (uint32_t)((((size_t)n * Hl + (yc >> 1)) * Wl + (xc >> 1)) * Cwb);
         m8[j] = in ? 0x88888888u : 0u;
-        m2[j] = in ? 0x22222222u : 0u;
-        dst[j] = (r * 2) * HALO_W + c;
     }
+    // word k (wave-uniform) of staged pixel j of the virtual input
+    auto word = [&](int j, int k) -> uint32_t {
+        if (TWO_SRC && k >= Cwa) return low[offb[j] + (k - Cwa)];
+        return act[offa[j] + k];
+    };
     uint2 gq[NLD];
     auto stage_issue = [&](int ks) {
+        const int k0 = 2 * ks;
+        if (CW_EVEN) {   // both sources have an even word count: one aligned 8-byte load
+            if (TWO_SRC && k0 >= Cwa) {
 #pragma unroll
-        for (int j = 0; j < NLD; ++j) {
-            if (CW_EVEN) {
-                gq[j] = *reinterpret_cast<const uint2 *>(src[j] + 2 * ks);
+                for (int j = 0; j < NLD; ++j)
+                    gq[j] = *reinterpret_cast<const uint2 *>(low + offb[j] + (k0 - Cwa));
             } else {
-                gq[j].x = src[j][2 * ks];
-                gq[j].y = src[j][min(2 * ks + 1, Cw - 1)];
+#pragma unroll
+                for (int j = 0; j < NLD; ++j)
+                    gq[j] = *reinterpret_cast<const uint2 *>(act + offa[j] + k0);
+            }
+        } else {
+            const int k1 = min(k0 + 1, Cw - 1);
+#pragma unroll
+            for (int j = 0; j < NLD; ++j) {
+                gq[j].x = word(j, k0);
+                gq[j].y = word(j, k1);
             }
         }
     };
@@ -396,16 +423,20 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
         const bool second = CW_EVEN || (2 * ks + 1 < Cw);
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
+            int p = tid + NT * j;
+            p = p < NPIX ? p : 0;
+            const int r = p / HALO_W, c = p - r * HALO_W;
+            uint4 *d = buf + (r * 2) * HALO_W + c;
             const uint32_t a = gq[j].x, b = gq[j].y;
-            const uint32_t k8 = m8[j], k2 = m2[j];
-            const uint32_t l8 = second ? k8 : 0u, l2 = second ? k2 : 0u;
+            const uint32_t k8 = m8[j], k2 = k8 >> 2;
+            const uint32_t l8 = second ? k8 : 0u, l2 = l8 >> 2;
             uint4 e0, e1;
             e0.x = ((a << 3) & k8) | k2; e0.y = ((a << 2) & k8) | k2;
             e0.z = ((a << 1) & k8) | k2; e0.w = (a & k8) | k2;
             e1.x = ((b << 3) & l8) | l2; e1.y = ((b << 2) & l8) | l2;
             e1.z = ((b << 1) & l8) | l2; e1.w = (b & l8) | l2;
-            buf[dst[j]] = e0;
-            buf[dst[j] + HALO_W] = e1;
+            d[0] = e0;
+            d[HALO_W] = e1;
         }
     };
 
@@ -442,6 +473,8 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
     const int Cow = Cout >> 5;
     const int x = x0 + col;
     const int widx = ct * 2 + half;
+    const bool ok = has_ct && x < W && widx < Cow;
+    uint32_t words[RW];
 #pragma unroll
     for (int r = 0; r < RW; ++r) {
         const int y = y0 + wm * RW + r;
@@ -454,10 +487,22 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
         // s = sign bits (1 = below threshold) of channels 16*half + i
         const uint32_t mine = (~s0 & 0xffffu) | (~s1 << 16);
         const uint32_t other = (uint32_t)__shfl_xor((int)mine, 32);
-        const uint32_t word = half == 0 ? ((mine & 0xffffu) | (other << 16))
-                                        : ((other >> 16) | (mine & 0xffff0000u));
-        if (has_ct && y < H && x < W && widx < Cow)
-            out_bits[(((size_t)n * H + y) * W + x) * Cow + widx] = word;
+        words[r] = half == 0 ? ((mine & 0xffffu) | (other << 16))
+                             : ((other >> 16) | (mine & 0xffff0000u));
+        if (ok && y < H && out_bits)
+            out_bits[(((size_t)n * H + y) * W + x) * Cow + widx] = words[r];
+    }
+    if (POOL) {
+        // H, W even and the tile origin even: every 2x2 window lies inside one wave's rows
+        // and inside one lane pair
+#pragma unroll
+        for (int r = 0; r < RW; r += 2) {
+            const int y = y0 + wm * RW + r;
+            uint32_t v = words[r] | words[r + 1];
+            v |= (uint32_t)__shfl_xor((int)v, 1);
+            if (ok && y < H && (col & 1) == 0)
+                out_pool[(((size_t)n * Hl + (y >> 1)) * Wl + (x >> 1)) * Cow + widx] = v;
+        }
     }
 }
 
@@ -590,21 +635,44 @@ static int launch_bits_t(const uint32_t *act, int N, int H, int W, const BlobLay
     return check_launch("conv_mfma_bits");
 }
 
-template <int RW, int WM, int WN>
-static int launch_block(const uint32_t *act, int N, int H, int W, const BlobLayout &L,
-                        const uint4 *wfrag, const int32_t *thresh, uint32_t *out_bits, hipStream_t s)
+// what a matrix-path launch works on: plain input, or the virtual concatenation
+// [act | up-sampled low]; optional pooled second output
+struct ConvIO {
+    const uint32_t *act;
+    const uint32_t *low;     // NULL = single source
+    int cwa, cwb;            // words per pixel of act / low
+    uint32_t *out_bits;      // may be NULL when out_pool is set
+    uint32_t *out_pool;      // NULL = no pooled output
+};
+
+template <int RW, int WM, int WN, bool TWO_SRC, bool POOL>
+static int launch_block_t(const ConvIO &io, int N, int H, int W, const BlobLayout &L,
+                          const uint4 *wfrag, const int32_t *thresh, hipStream_t s)
 {
     const int tiles64 = L.cout_pad64 / 64;
     long tiles = (long)N * ceil_div(H, RW * WM) * ceil_div(W, TW);
     if (tiles > 0x7fffffffL) return fail(MBU_ERR_SHAPE, "too many tiles for one launch");
     dim3 grid((unsigned)tiles, (unsigned)ceil_div(tiles64, WN));
-    if (L.cin_words % 2 == 0)
-        MBU_LAUNCH((conv_mfma_block_kernel<RW, WM, WN, true>), grid, dim3(256), 0, s, act, N, H, W,
-                   L.cin_words, L.ksteps, wfrag, L.cout, tiles64, thresh, out_bits);
+    const bool even = (io.cwa % 2 == 0) && (!TWO_SRC || io.cwb % 2 == 0);
+    if (even)
+        MBU_LAUNCH((conv_mfma_block_kernel<RW, WM, WN, true, TWO_SRC, POOL>), grid, dim3(256), 0, s,
+                   io.act, io.low, N, H, W, io.cwa, io.cwb, L.ksteps, wfrag, L.cout, tiles64, thresh,
+                   io.out_bits, io.out_pool);
     else
-        MBU_LAUNCH((conv_mfma_block_kernel<RW, WM, WN, false>), grid, dim3(256), 0, s, act, N, H, W,
-                   L.cin_words, L.ksteps, wfrag, L.cout, tiles64, thresh, out_bits);
+        MBU_LAUNCH((conv_mfma_block_kernel<RW, WM, WN, false, TWO_SRC, POOL>), grid, dim3(256), 0, s,
+                   io.act, io.low, N, H, W, io.cwa, io.cwb, L.ksteps, wfrag, L.cout, tiles64, thresh,
+                   io.out_bits, io.out_pool);
     return check_launch("conv_mfma_block");
+}
+
+template <int RW, int WM, int WN>
+static int launch_block(const ConvIO &io, int N, int H, int W, const BlobLayout &L,
+                        const uint4 *wfrag, const int32_t *thresh, hipStream_t s)
+{
+    if (io.low && io.out_pool) return launch_block_t<RW, WM, WN, true, true>(io, N, H, W, L, wfrag, thresh, s);
+    if (io.low) return launch_block_t<RW, WM, WN, true, false>(io, N, H, W, L, wfrag, thresh, s);
+    if (io.out_pool) return launch_block_t<RW, WM, WN, false, true>(io, N, H, W, L, wfrag, thresh, s);
+    return launch_block_t<RW, WM, WN, false, false>(io, N, H, W, L, wfrag, thresh, s);
 }
 
 template <int RW, int MT>
@@ -619,6 +687,16 @@ static int launch_bits(const uint32_t *act, int N, int H, int W, const BlobLayou
     if (L.cin_words % 2 == 0)
         return launch_bits_t<RW, MT, true, false>(act, N, H, W, L, wfrag, thresh, out_bits, s);
     return launch_bits_t<RW, MT, false, false>(act, N, H, W, L, wfrag, thresh, out_bits, s);
+}
+
+static int launch_block_auto(const ConvIO &io, int N, int H, int W, const BlobLayout &L,
+                             const uint4 *wfrag, const int32_t *thresh, hipStream_t s)
+{
+    // waves of a block over output-channel tiles when there are enough of them
+    const int tiles64 = L.cout_pad64 / 64;
+    if (tiles64 % 4 == 0) return launch_block<4, 1, 4>(io, N, H, W, L, wfrag, thresh, s);
+    if (tiles64 % 2 == 0) return launch_block<4, 2, 2>(io, N, H, W, L, wfrag, thresh, s);
+    return launch_block<4, 4, 1>(io, N, H, W, L, wfrag, thresh, s);
 }
 
 int launch_conv_mfma(const uint32_t *act, int N, int H, int W, const BlobLayout &L,
@@ -639,17 +717,25 @@ int launch_conv_mfma(const uint32_t *act, int N, int H, int W, const BlobLayout 
     // prologue and epilogue dominate and the persistent wave-private kernel wins (3 rows x 64
     // channels per wave fit the register file together with the resident weights); with
     // several steps the block-cooperative kernel stages less per wave and wins.
-    const int tiles64 = L.cout_pad64 / 64;
     const int mode = g_tune_rw;   // 0 = automatic; see mbu_set_conv_tuning
     const bool want_block = mode == 1 || (mode == 0 && L.ksteps > 1);
     if (want_block) {
-        // waves of a block over output-channel tiles when there are enough of them
-        if (tiles64 % 4 == 0) return launch_block<4, 1, 4>(act, N, H, W, L, wfrag, thresh, out_bits, s);
-        if (tiles64 % 2 == 0) return launch_block<4, 2, 2>(act, N, H, W, L, wfrag, thresh, out_bits, s);
-        return launch_block<4, 4, 1>(act, N, H, W, L, wfrag, thresh, out_bits, s);
+        ConvIO io{act, nullptr, L.cin_words, 0, out_bits, nullptr};
+        return launch_block_auto(io, N, H, W, L, wfrag, thresh, s);
     }
     if (mode == 6) return launch_bits<6, 1>(act, N, H, W, L, wfrag, thresh, out_bits, s);
     return launch_bits<3, 2>(act, N, H, W, L, wfrag, thresh, out_bits, s);
+}
+
+// Fused form: input = [act (Ca channels) | 2x-up-sampled low (Clow channels)] when low is
+// given, plus an optional 2x2-pooled second output.  Always the block-cooperative kernel.
+int launch_conv_mfma_fused(const uint32_t *act, int Ca, const uint32_t *low, int Clow, int N, int H,
+                           int W, const BlobLayout &L, const void *blob, const int32_t *thresh,
+                           uint32_t *out_bits, uint32_t *out_pool, hipStream_t s)
+{
+    const uint4 *wfrag = (const uint4 *)((const uint8_t *)blob + L.off_f4);
+    ConvIO io{act, low, ceil_div(Ca, 32), low ? ceil_div(Clow, 32) : 0, out_bits, out_pool};
+    return launch_block_auto(io, N, H, W, L, wfrag, thresh, s);
 }
 
 }  // namespace mbu

@@ -235,6 +235,41 @@ int mbu_conv3x3_masked_binary(const uint32_t *act, int N, int H, int W, int Cin,
     return run_conv(act, N, H, W, Cin, packed_w, Cout, thresh, out_bits, out_acc, (hipStream_t)stream);
 }
 
+int mbu_conv3x3_masked_binary_fused(const uint32_t *act, int Ca, const uint32_t *low, int Clow,
+                                    int N, int H, int W, const void *packed_w, int Cout,
+                                    const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool,
+                                    void *stream)
+{
+    const char *fn = "mbu_conv3x3_masked_binary_fused";
+    MBU_REQ_PTR(fn, act);
+    MBU_REQ_PTR(fn, packed_w);
+    MBU_REQ_PTR(fn, thresh);
+    if (!out_bits && !out_pool) return fail(MBU_ERR_NULL, "%s: out_bits and out_pool are both NULL", fn);
+    if (out_bits && !aligned16(out_bits)) return fail(MBU_ERR_ALIGN, "%s: out_bits is not 16-byte aligned", fn);
+    if (out_pool && !aligned16(out_pool)) return fail(MBU_ERR_ALIGN, "%s: out_pool is not 16-byte aligned", fn);
+    if (low && !aligned16(low)) return fail(MBU_ERR_ALIGN, "%s: low is not 16-byte aligned", fn);
+    if ((const void *)out_bits == (const void *)act || (const void *)out_pool == (const void *)act ||
+        (low && ((const void *)out_bits == (const void *)low || (const void *)out_pool == (const void *)low)))
+        return fail(MBU_ERR_ARG, "%s: outputs must not alias an input", fn);
+    int rc = check_dims4(fn, N, H, W, Ca);
+    if (rc) return rc;
+    if ((low != nullptr) != (Clow > 0) || Clow < 0)
+        return fail(MBU_ERR_SHAPE, "%s: Clow must be positive exactly when low is given (Clow=%d)", fn, Clow);
+    if (low && Ca % 32) return fail(MBU_ERR_SHAPE, "%s: Ca must be a multiple of 32 when low is given, got %d", fn, Ca);
+    if ((low || out_pool) && ((H & 1) || (W & 1)))
+        return fail(MBU_ERR_SHAPE, "%s: H and W must be even with low / out_pool (H=%d W=%d)", fn, H, W);
+    if (Cout <= 0 || Cout % 32) return fail(MBU_ERR_SHAPE, "%s: Cout must be a positive multiple of 32, got %d", fn, Cout);
+    if (Cout > 65536 || Ca + Clow > 65536) return fail(MBU_ERR_SHAPE, "%s: channel count too large", fn);
+    rc = check_dims4(fn, N, H, W, Cout);
+    if (rc) return rc;
+    rc = check_dims4(fn, N, H, W, Ca + Clow);
+    if (rc) return rc;
+    // the matrix-path blob stores whole 32-channel words of each source one after the other
+    const int cin_blob = Ca + Clow;
+    return launch_conv_mfma_fused(act, Ca, low, Clow, N, H, W, blob_layout(Cout, cin_blob), packed_w,
+                                  thresh, out_bits, out_pool, (hipStream_t)stream);
+}
+
 int mbu_maxpool2x2_bits(const uint32_t *in, int N, int H, int W, int C, uint32_t *out, void *stream)
 {
     const char *fn = "mbu_maxpool2x2_bits";
@@ -326,6 +361,7 @@ int mbu_unet_forward(const mbu_unet_desc *d, const float *image_nchw, int N, int
     hipStream_t s = (hipStream_t)stream;
     uint8_t *ws = (uint8_t *)workspace;
     auto buf = [&](int step) { return (uint32_t *)(ws + steps[step].off); };
+    const bool fuse = d->fuse != 0 && g_conv_path != MBU_PATH_VALU;
     for (size_t i = 0; i < steps.size(); ++i) {
         const Step &st = steps[i];
         if (d->step_events && hipEventRecord((hipEvent_t)d->step_events[i], s) != hipSuccess)
@@ -336,16 +372,37 @@ int mbu_unet_forward(const mbu_unet_desc *d, const float *image_nchw, int N, int
             break;
         case Step::CONV: {
             const mbu_conv_layer &L = d->convs[st.conv];
-            rc = run_conv(buf(st.in), N, st.h, st.w, L.cin, L.packed_w, L.cout, L.thresh,
-                          buf((int)i), nullptr, s);
+            const Step &in = steps[st.in];
+            // fused forms: read [skip | up(low)] in place; write the pooled output as well
+            const bool from_cat = fuse && in.kind == Step::UPCAT;
+            const bool next_pool = fuse && i + 1 < steps.size() && steps[i + 1].kind == Step::POOL &&
+                                   blob_layout(L.cout, L.cin).ksteps > 1;
+            if (from_cat || next_pool) {
+                const uint32_t *a = from_cat ? buf(in.in) : buf(st.in);
+                const int ca = from_cat ? steps[in.in].c : L.cin;
+                const uint32_t *lo = from_cat ? buf(in.in2) : nullptr;
+                const int clo = from_cat ? steps[in.in2].c : 0;
+                rc = launch_conv_mfma_fused(a, ca, lo, clo, N, st.h, st.w, blob_layout(L.cout, L.cin),
+                                            L.packed_w, L.thresh, buf((int)i),
+                                            next_pool ? buf((int)i + 1) : nullptr, s);
+            } else {
+                rc = run_conv(buf(st.in), N, st.h, st.w, L.cin, L.packed_w, L.cout, L.thresh,
+                              buf((int)i), nullptr, s);
+            }
             break;
         }
-        case Step::POOL:
-            rc = launch_maxpool(buf(st.in), N, st.h * 2, st.w * 2, st.c / 32, buf((int)i), s);
+        case Step::POOL: {
+            const Step &in = steps[st.in];
+            const bool done = fuse && in.kind == Step::CONV &&
+                              blob_layout(d->convs[in.conv].cout, d->convs[in.conv].cin).ksteps > 1;
+            if (!done)
+                rc = launch_maxpool(buf(st.in), N, st.h * 2, st.w * 2, st.c / 32, buf((int)i), s);
             break;
+        }
         case Step::UPCAT:
-            rc = launch_upcat(buf(st.in), steps[st.in].c / 32, buf(st.in2), steps[st.in2].c / 32, N,
-                              st.h, st.w, buf((int)i), s);
+            if (!fuse)
+                rc = launch_upcat(buf(st.in), steps[st.in].c / 32, buf(st.in2), steps[st.in2].c / 32,
+                                  N, st.h, st.w, buf((int)i), s);
             break;
         case Step::CLS:
             rc = launch_classifier(buf(st.in), N, st.h, st.w, steps[st.in].c, d->cls_w, d->cls_b,

@@ -65,6 +65,9 @@ int launch_conv_valu(const uint32_t *act, int N, int H, int W, const BlobLayout 
 int launch_conv_mfma(const uint32_t *act, int N, int H, int W, const BlobLayout &L,
                      const void *blob, const int32_t *thresh, uint32_t *out_bits,
                      int32_t *out_acc, hipStream_t s);
+int launch_conv_mfma_fused(const uint32_t *act, int Ca, const uint32_t *low, int Clow, int N, int H,
+                           int W, const BlobLayout &L, const void *blob, const int32_t *thresh,
+                           uint32_t *out_bits, uint32_t *out_pool, hipStream_t s);
 int launch_maxpool(const uint32_t *in, int N, int H, int W, int Cw, uint32_t *out, hipStream_t s);
 int launch_upsample(const uint32_t *in, int N, int H, int W, int Cw, uint32_t *out, hipStream_t s);
 int launch_concat(const uint32_t *a, int Caw, const uint32_t *b, int Cbw, long pixels,

@@ -20,7 +20,7 @@ def header_symbols():
 def test_library_exports_every_declared_symbol():
     L = B.lib()
     syms = header_symbols()
-    assert len(syms) >= 19
+    assert len(syms) >= 20
     for s in syms:
         assert hasattr(L, s), s
     assert sorted(B.EXPORTS) == syms
@@ -52,6 +52,20 @@ def test_conv_argument_validation():
     assert f(a, 1, 8, 8, 64, w, 64, t, a, None, None) == B.MBU_ERR_ARG
     assert f(a, 1, 8, 8, 64, w, 64, t + 8, o, None, None) == B.MBU_ERR_ALIGN
     assert f(None, 1, 8, 8, 64, w, 64, t, o, None, None) == B.MBU_ERR_NULL
+
+
+def test_fused_conv_argument_validation():
+    L = B.lib()
+    a, lo, w, t, o, p = 0x10000, 0x20000, 0x30000, 0x40000, 0x50000, 0x60000
+    f = L.mbu_conv3x3_masked_binary_fused
+    assert f(a, 64, lo, 128, 1, 8, 8, w, 64, t, None, None, None) == B.MBU_ERR_NULL
+    assert f(a, 64, None, 128, 1, 8, 8, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
+    assert f(a, 64, lo, 0, 1, 8, 8, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
+    assert f(a, 48, lo, 128, 1, 8, 8, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
+    assert f(a, 64, lo, 128, 1, 7, 8, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
+    assert f(a, 64, None, 0, 1, 8, 9, w, 64, t, o, p, None) == B.MBU_ERR_SHAPE
+    assert f(a, 64, lo, 128, 1, 8, 8, w, 64, t, lo, None, None) == B.MBU_ERR_ARG
+    assert f(a, 64, lo + 4, 128, 1, 8, 8, w, 64, t, o, None, None) == B.MBU_ERR_ALIGN
 
 
 def test_packed_weight_size_and_path_switch():

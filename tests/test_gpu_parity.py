@@ -144,6 +144,48 @@ def test_every_matrix_kernel_variant_matches_oracle(shape, kernel):
     assert np.array_equal(bits, bitref.pack_pm1(out_ref))
 
 
+FUSED_SHAPES = [
+    # N, H, W, Ca, Clow, Cout
+    (1, 16, 64, 64, 128, 64),      # decoder level 1 shape in miniature
+    (2, 12, 38, 96, 160, 96),      # odd word counts on both sides, ragged tiles
+    (1, 8, 34, 32, 32, 64),        # one word each: a step straddles the two sources
+    (1, 20, 40, 128, 256, 256),
+    (1, 6, 10, 64, 40, 32),        # low channels not a multiple of 32
+    (1, 4, 4, 512, 1024, 128),
+]
+
+
+@pytest.mark.parametrize("shape", FUSED_SHAPES)
+def test_fused_concat_upsample_pool(shape):
+    """mbu_conv3x3_masked_binary_fused against the oracle's separate up-sample, concat,
+    layer and pooling."""
+    N, H, W, Ca, Clow, Cout = shape
+    say(f"conv fused N={N} H={H} W={W} Ca={Ca} Clow={Clow} Cout={Cout}")
+    rng = np.random.default_rng(Ca + Clow)
+    skip = synth.pm1_bits(rng, (N, H, W, Ca))
+    low = synth.pm1_bits(rng, (N, H // 2, W // 2, Clow))
+    w = synth.ternary_weights(9, 0, 0, Cout, Ca + Clow, 0.6)
+    th = synth.thresholds(9, 0, 0, Cout, (9 * (Ca + Clow)) // 16)
+    x = O.concat(skip, O.upsample2x(low))
+    _, out_ref = O.masked_binary_layer(x, w, th)
+    pool_ref = O.maxpool2x2(out_ref)
+    blob = B.pack_weights(dev(w))
+    pa, pl = B.pack_act(dev(skip)), B.pack_act(dev(low))
+    bits, pool = B.conv3x3_masked_binary_fused(pa, Ca, pl, Clow, blob, Cout, dev(th), True, True)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_u32(bits), bitref.pack_pm1(out_ref))
+    assert np.array_equal(host_u32(pool), bitref.pack_pm1(pool_ref))
+    # pooled output alone; plain input with pooled output
+    _, pool2 = B.conv3x3_masked_binary_fused(pa, Ca, pl, Clow, blob, Cout, dev(th), False, True)
+    assert np.array_equal(host_u32(pool2), bitref.pack_pm1(pool_ref))
+    w1 = synth.ternary_weights(9, 1, 0, Cout, Ca, 0.6)
+    _, o1 = O.masked_binary_layer(skip, w1, th)
+    b1, p1 = B.conv3x3_masked_binary_fused(pa, Ca, None, 0, B.pack_weights(dev(w1)), Cout, dev(th),
+                                           True, True)
+    assert np.array_equal(host_u32(b1), bitref.pack_pm1(o1))
+    assert np.array_equal(host_u32(p1), bitref.pack_pm1(O.maxpool2x2(o1)))
+
+
 def test_paths_agree_and_are_deterministic():
     say("conv paths agree")
     case = synth.conv_case(7, 3, 2, 40, 72, 128, 128, 0.5)
@@ -193,16 +235,17 @@ def test_pool_upsample_concat(C):
 
 
 # ------------------------------------------------------------------------ network
-def build_unet(case):
+def build_unet(case, fuse=True):
     return B.UNet(dev(case.stem_w), [(dev(w), dev(t)) for w, t in case.convs],
-                  dev(case.cls_w), dev(case.cls_b), levels=case.levels)
+                  dev(case.cls_w), dev(case.cls_b), levels=case.levels, fuse=fuse)
 
 
 TAP_OF_STEP = {"stem": "stem", "classifier": None}
 
 
-def compare_unet_all_taps(case, N, H, W):
-    net = build_unet(case)
+def compare_unet_all_taps(case, N, H, W, fuse=True):
+    net = build_unet(case, fuse)
+    fused_away = fuse and B.get_conv_path() != B.PATH_VALU
     logits = net.forward(dev(case.image))
     torch.cuda.synchronize()
     ref_logits, taps = O.unet_forward(case.image, case.stem_w, case.convs, case.cls_w,
@@ -213,6 +256,8 @@ def compare_unet_all_taps(case, N, H, W):
         name, _, h, w, c = net.step_info(N, H, W, s)
         ref = taps[rename.get(name, name)]
         assert ref.shape == (N, h, w, c), name
+        if fused_away and name.startswith("cat"):
+            continue      # folded into the layer that reads it; never written
         got = host_u32(net.step_output(N, H, W, s))
         bad = int((got != bitref.pack_pm1(ref)).sum())
         assert bad == 0, f"step {s} ({name}): {bad} packed words differ"
@@ -221,28 +266,32 @@ def compare_unet_all_taps(case, N, H, W):
     assert (err <= 1e-4 * np.maximum(1.0, np.abs(ref_logits))).all(), float(err.max())
 
 
+@pytest.mark.parametrize("fuse", [True, False])
 @pytest.mark.parametrize("path,pname", PATHS)
-def test_unet_small_all_layers(path, pname):
-    say(f"unet small {pname}")
+def test_unet_small_all_layers(path, pname, fuse):
+    say(f"unet small {pname} fuse={fuse}")
     B.set_conv_path(path)
     case = synth.unet_case(2, 1, 2, 32, 48, base=32, levels=2, n_classes=5)
-    compare_unet_all_taps(case, 2, 32, 48)
+    compare_unet_all_taps(case, 2, 32, 48, fuse)
+    case = synth.unet_case(2, 2, 1, 64, 96, base=64, levels=3, n_classes=19)
+    compare_unet_all_taps(case, 1, 64, 96, fuse)
 
 
-def test_unet_512_all_layers():
+@pytest.mark.parametrize("fuse", [True, False])
+def test_unet_512_all_layers(fuse):
     """Full U-Net forward at 1x3x512x512, per-layer keep probability in [0.4,0.8]:
     every layer's packed bits exactly, logits within 1e-4 relative."""
-    say("unet 512x512 all layers")
+    say(f"unet 512x512 all layers fuse={fuse}")
     case = synth.unet_case(2, 0, 1, 512, 512)
-    compare_unet_all_taps(case, 1, 512, 512)
+    compare_unet_all_taps(case, 1, 512, 512, fuse)
 
 
-def check_unet_by_induction(case, N, H, W, rows_per_layer=3):
+def check_unet_by_induction(case, N, H, W, rows_per_layer=3, fuse=True):
     """Full-size check without running the whole oracle: every step's GPU output is
     checked against the oracle applied to that step's GPU *input* (sampled row strips
     for the convolutions, everything for the cheap steps), so the chain is exact by
     induction from the image."""
-    net = build_unet(case)
+    net = build_unet(case, fuse)
     logits = net.forward(dev(case.image))
     torch.cuda.synchronize()
     outs = {}
@@ -276,7 +325,11 @@ def check_unet_by_induction(case, N, H, W, rows_per_layer=3):
             l = int(name[3:])
             sk, lo = outs[skips[l]], outs[prev]
             up = np.repeat(np.repeat(lo, 2, axis=1), 2, axis=2)
-            assert np.array_equal(np.concatenate([sk, up], -1), outs[name]), name
+            cat = np.concatenate([sk, up], -1)
+            if fuse:
+                outs[name] = cat      # never materialised on the GPU: the next layer reads
+            else:                     # skip and low in place, so check it against this
+                assert np.array_equal(cat, outs[name]), name
         else:
             wgt, th = case.convs[ci]
             ci += 1
@@ -299,11 +352,12 @@ def check_unet_by_induction(case, N, H, W, rows_per_layer=3):
             assert (np.abs(g - ref) <= 1e-4 * np.maximum(1.0, np.abs(ref))).all(), "classifier"
 
 
-def test_unet_1024x2048_by_induction():
+@pytest.mark.parametrize("fuse", [True, False])
+def test_unet_1024x2048_by_induction(fuse):
     """The high-resolution shape the benchmark times: batch 1, 3x1024x2048, keep 0.6."""
-    say("unet 1024x2048 induction")
+    say(f"unet 1024x2048 induction fuse={fuse}")
     case = synth.unet_case(3, 0, 1, 1024, 2048, keep=0.6)
-    check_unet_by_induction(case, 1, 1024, 2048)
+    check_unet_by_induction(case, 1, 1024, 2048, fuse=fuse)
 
 
 @pytest.mark.parametrize("mean_zero", [0.2, 0.6, 0.8])
