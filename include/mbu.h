@@ -177,8 +177,9 @@ typedef struct mbu_unet_desc {
     const float *cls_b;             /* device [n_classes]                        */
     void **step_events;             /* optional host array of mbu_unet_num_steps()+1
                                        hipEvent_t: event i is recorded on the stream
-                                       before step i, the last one after the final
-                                       step.  NULL = no events.                   */
+                                       before step i if that step launches a kernel
+                                       (mbu_unet_step_launches), the last one after
+                                       the final step.  NULL = no events.          */
     int fuse;                       /* 0: one kernel per step, every step's output is
                                        written to the workspace.  1: on the matrix path
                                        the "cat" steps are folded into the layer that
@@ -198,6 +199,11 @@ int mbu_unet_num_steps(const mbu_unet_desc *d);
  * All out-pointers are host pointers and may be NULL. */
 int mbu_unet_step_info(const mbu_unet_desc *d, int N, int H, int W, int step,
                        const char **name, size_t *ws_offset, int *h, int *w, int *c);
+
+/* 1 if step `step` launches a kernel of its own under the descriptor's `fuse` setting and the
+ * current convolution path, 0 if it is folded into a neighbouring layer (then its event in
+ * step_events is not recorded), negative status on error. */
+int mbu_unet_step_launches(const mbu_unet_desc *d, int N, int H, int W, int step);
 
 /* Workspace size (bytes) mbu_unet_forward needs for this shape. */
 int mbu_unet_workspace_bytes(const mbu_unet_desc *d, int N, int H, int W, size_t *bytes);

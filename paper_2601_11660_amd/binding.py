@@ -23,7 +23,7 @@ EXPORTS = [
     "mbu_packed_weights_bytes", "mbu_pack_weights", "mbu_conv3x3_masked_binary",
     "mbu_conv3x3_masked_binary_fused",
     "mbu_maxpool2x2_bits", "mbu_upsample2x_bits", "mbu_concat_bits", "mbu_unet_num_steps",
-    "mbu_unet_step_info", "mbu_unet_workspace_bytes", "mbu_unet_forward",
+    "mbu_unet_step_info", "mbu_unet_step_launches", "mbu_unet_workspace_bytes", "mbu_unet_forward",
     "mbu_event_create", "mbu_event_destroy", "mbu_event_record", "mbu_event_elapsed_ms",
 ]
 
@@ -73,6 +73,7 @@ def lib() -> ctypes.CDLL:
                                          ctypes.POINTER(ctypes.c_char_p),
                                          ctypes.POINTER(ctypes.c_size_t),
                                          ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ci)]
+        L.mbu_unet_step_launches.argtypes = [ctypes.POINTER(UNetDesc), ci, ci, ci, ci]
         L.mbu_unet_workspace_bytes.argtypes = [ctypes.POINTER(UNetDesc), ci, ci, ci,
                                                ctypes.POINTER(ctypes.c_size_t)]
         L.mbu_unet_forward.argtypes = [ctypes.POINTER(UNetDesc), vp, ci, ci, ci, vp, vp,
@@ -294,10 +295,22 @@ class UNet:
     def enable_step_events(self, on: bool = True) -> None:
         self.use_event_set(self.new_event_set() if on else None)
 
-    def step_times_ms(self, es: Optional["EventSet"] = None) -> List[float]:
+    def step_launches(self, N: int, H: int, W: int, step: int) -> bool:
+        rc = lib().mbu_unet_step_launches(ctypes.byref(self.desc), N, H, W, step)
+        if rc < 0:
+            check(rc)
+        return rc == 1
+
+    def step_times_ms(self, N: int, H: int, W: int, es: Optional["EventSet"] = None) -> List[float]:
+        """Per-step durations of the last forward pass recorded into `es`; steps folded into
+        a neighbouring layer report 0."""
         es = es if es is not None else self._events
         assert es is not None
-        return [es.events[i].elapsed_ms(es.events[i + 1]) for i in range(self.num_steps)]
+        live = [i for i in range(self.num_steps) if self.step_launches(N, H, W, i)]
+        out = [0.0] * self.num_steps
+        for a, b in zip(live, live[1:] + [self.num_steps]):
+            out[a] = es.events[a].elapsed_ms(es.events[b])
+        return out
 
     def step_info(self, N: int, H: int, W: int, step: int):
         name = ctypes.c_char_p()

@@ -141,6 +141,21 @@ static int build_plan(const mbu_unet_desc *d, int N, int H, int W, std::vector<S
     return MBU_OK;
 }
 
+// Does step i launch a kernel of its own under the descriptor's fusion setting?
+static bool step_launches(const mbu_unet_desc *d, const std::vector<Step> &steps, size_t i)
+{
+    const bool fuse = d->fuse != 0 && g_conv_path != MBU_PATH_VALU;
+    if (!fuse) return true;
+    const Step &st = steps[i];
+    if (st.kind == Step::UPCAT) return false;
+    if (st.kind == Step::POOL) {
+        const Step &in = steps[st.in];
+        return !(in.kind == Step::CONV &&
+                 blob_layout(d->convs[in.conv].cout, d->convs[in.conv].cin).ksteps > 1);
+    }
+    return true;
+}
+
 static int run_conv(const uint32_t *act, int N, int H, int W, int Cin, const void *packed_w,
                     int Cout, const int32_t *thresh, uint32_t *out_bits, int32_t *out_acc,
                     hipStream_t s)
@@ -330,6 +345,15 @@ int mbu_unet_step_info(const mbu_unet_desc *d, int N, int H, int W, int step, co
     return MBU_OK;
 }
 
+int mbu_unet_step_launches(const mbu_unet_desc *d, int N, int H, int W, int step)
+{
+    std::vector<Step> steps;
+    int rc = build_plan(d, N, H, W, steps, nullptr);
+    if (rc) return rc;
+    if (step < 0 || step >= (int)steps.size()) return fail(MBU_ERR_ARG, "mbu_unet_step_launches: step %d out of range", step);
+    return step_launches(d, steps, (size_t)step) ? 1 : 0;
+}
+
 int mbu_unet_workspace_bytes(const mbu_unet_desc *d, int N, int H, int W, size_t *bytes)
 {
     if (!bytes) return fail(MBU_ERR_NULL, "mbu_unet_workspace_bytes: bytes is NULL");
@@ -364,7 +388,8 @@ int mbu_unet_forward(const mbu_unet_desc *d, const float *image_nchw, int N, int
     const bool fuse = d->fuse != 0 && g_conv_path != MBU_PATH_VALU;
     for (size_t i = 0; i < steps.size(); ++i) {
         const Step &st = steps[i];
-        if (d->step_events && hipEventRecord((hipEvent_t)d->step_events[i], s) != hipSuccess)
+        if (d->step_events && step_launches(d, steps, i) &&
+            hipEventRecord((hipEvent_t)d->step_events[i], s) != hipSuccess)
             return fail(MBU_ERR_HIP, "%s: hipEventRecord failed", fn);
         switch (st.kind) {
         case Step::STEM:

@@ -20,7 +20,7 @@ def header_symbols():
 def test_library_exports_every_declared_symbol():
     L = B.lib()
     syms = header_symbols()
-    assert len(syms) >= 20
+    assert len(syms) >= 21
     for s in syms:
         assert hasattr(L, s), s
     assert sorted(B.EXPORTS) == syms
