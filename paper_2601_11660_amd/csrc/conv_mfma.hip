@@ -318,7 +318,7 @@ template <int RW, int WM, int WN, bool CW_EVEN, bool TWO_SRC, bool POOL>
 __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
     const uint32_t *__restrict__ act, const uint32_t *__restrict__ low, int N, int H, int W,
     int Cwa, int Cwb, int ksteps, const uint4 *__restrict__ wfrag, int Cout, int tiles64,
-    const int32_t *__restrict__ thresh, uint32_t *__restrict__ out_bits,
+    int ptiles, const int32_t *__restrict__ thresh, uint32_t *__restrict__ out_bits,
     uint32_t *__restrict__ out_pool)
 {
     static_assert(WM * WN == 4, "four waves per block");
@@ -330,6 +330,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
     constexpr int NLD = (NPIX + NT - 1) / NT;    // staged pixels per thread
     constexpr int TILE = HR * 2 * HALO_W;        // uint4 entries per buffer, [row][half][col]
     __shared__ uint4 tile[2][TILE];
+    __shared__ float4 init_tab[4][2][2][4];      // [wave][half][m][4 x 4 channels]: -theta
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -339,63 +340,51 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
     const int Cw = Cwa + (TWO_SRC ? Cwb : 0);     // words per pixel of the (virtual) input
     const int tiles_x = (W + TW - 1) / TW;
     const int tiles_y = (H + TH - 1) / TH;
-    int bid = blockIdx.x;
-    const int tx = bid % tiles_x;
-    bid /= tiles_x;
-    const int ty = bid % tiles_y;
-    const int n = bid / tiles_y;
-    const int x0 = tx * TW, y0 = ty * TH;
+    const int Hl = H >> 1, Wl = W >> 1;
     const int ct_raw = blockIdx.y * WN + wn;      // 64-channel output tile of this wave
     const bool has_ct = ct_raw < tiles64;
     const int ct = has_ct ? ct_raw : tiles64 - 1;
 
-    // ---- accumulators start at -theta
-    v16f acc[RW][2];
-#pragma unroll
-    for (int m = 0; m < 2; ++m) {
-        const int cbase = ct * 64 + m * 32 + 16 * half;   // 16 consecutive channels per lane
-        int th[16];
-        if (cbase < Cout) {                                // Cout % 32 == 0: all 16 or none
-            const int4 *tp = reinterpret_cast<const int4 *>(thresh + cbase);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int4 t = tp[q];
-                th[4 * q] = t.x; th[4 * q + 1] = t.y; th[4 * q + 2] = t.z; th[4 * q + 3] = t.w;
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) th[i] = 0;
-        }
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int t = max(-(1 << 22), min(1 << 22, th[i]));
-            const float init = 0.0f - (float)t;
-#pragma unroll
-            for (int r = 0; r < RW; ++r) acc[r][m][i] = init;
-        }
+    // ---- -theta of this wave's 64 channels, kept in LDS and reloaded at every pixel tile
+    // (exact in fp32 after clamping theta to +-2^22; see the epilogue)
+    if (col < 8) {   // lanes (half, col < 8) write float4 number col of their half
+        const int m = col >> 2, q = col & 3;
+        const int cbase = ct * 64 + m * 32 + 16 * half + 4 * q;
+        int4 t = make_int4(0, 0, 0, 0);
+        if (cbase < Cout) t = *reinterpret_cast<const int4 *>(thresh + cbase);
+        float4 f;
+        f.x = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.x));
+        f.y = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.y));
+        f.z = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.z));
+        f.w = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.w));
+        init_tab[wave][half][m][q] = f;
     }
 
-    // ---- staging plan of this thread: halo pixels p = tid + NT*j
+    // ---- staging plan of this thread for one pixel tile: halo pixels p = tid + NT*j
+    // bit 31 of offa = "pixel lies inside the image" (tensors are limited to 2^31 words)
     uint32_t offa[NLD];                  // word offset of the (clamped) pixel in act
     uint32_t offb[TWO_SRC ? NLD : 1];    // ... of the pixel (y/2, x/2) in low
-    uint32_t m8[NLD];                    // 0x88888888 inside the image, 0 outside
-    const int Hl = H >> 1, Wl = W >> 1;
+    auto plan = [&](int pt) {
+        const int tx = pt % tiles_x;
+        const int q = pt / tiles_x;
+        const int ty = q % tiles_y;
+        const int n = q / tiles_y;
 #pragma unroll
-    for (int j = 0; j < NLD; ++j) {
-        int p = tid + NT * j;
-        p = p < NPIX ? p : 0;     // surplus threads duplicate pixel 0 (same data, same slot)
-        const int r = p / HALO_W, c = p - r * HALO_W;
-        const int yy = y0 + r - 1, xx = x0 + c - 1;
-        const bool in = yy >= 0 && yy < H && xx >= 0 && xx < W;
-        const int yc = min(max(yy, 0), H - 1), xc = min(max(xx, 0), W - 1);
-        offa[j] = (uint32_t)((((size_t)n * H + yc) * W + xc) * Cwa);
-        if (TWO_SRC) offb[j] = (uint32_t)((((size_t)n * Hl + (yc >> 1)) * Wl + (xc >> 1)) * Cwb);
-        m8[j] = in ? 0x88888888u : 0u;
-    }
+        for (int j = 0; j < NLD; ++j) {
+            int p = tid + NT * j;
+            p = p < NPIX ? p : 0;     // surplus threads duplicate pixel 0 (same data, same slot)
+            const int r = p / HALO_W, c = p - r * HALO_W;
+            const int yy = ty * TH + r - 1, xx = tx * TW + c - 1;
+            const bool in = yy >= 0 && yy < H && xx >= 0 && xx < W;
+            const int yc = min(max(yy, 0), H - 1), xc = min(max(xx, 0), W - 1);
+            offa[j] = (uint32_t)((((size_t)n * H + yc) * W + xc) * Cwa) | (in ? 0x80000000u : 0u);
+            if (TWO_SRC) offb[j] = (uint32_t)((((size_t)n * Hl + (yc >> 1)) * Wl + (xc >> 1)) * Cwb);
+        }
+    };
     // word k (wave-uniform) of staged pixel j of the virtual input
     auto word = [&](int j, int k) -> uint32_t {
         if (TWO_SRC && k >= Cwa) return low[offb[j] + (k - Cwa)];
-        return act[offa[j] + k];
+        return act[(offa[j] & 0x7fffffffu) + k];
     };
     uint2 gq[NLD];
     auto stage_issue = [&](int ks) {
@@ -408,7 +397,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
             } else {
 #pragma unroll
                 for (int j = 0; j < NLD; ++j)
-                    gq[j] = *reinterpret_cast<const uint2 *>(act + offa[j] + k0);
+                    gq[j] = *reinterpret_cast<const uint2 *>(act + (offa[j] & 0x7fffffffu) + k0);
             }
         } else {
             const int k1 = min(k0 + 1, Cw - 1);
@@ -428,7 +417,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
             const int r = p / HALO_W, c = p - r * HALO_W;
             uint4 *d = buf + (r * 2) * HALO_W + c;
             const uint32_t a = gq[j].x, b = gq[j].y;
-            const uint32_t k8 = m8[j], k2 = k8 >> 2;
+            const uint32_t k8 = (uint32_t)((int)offa[j] >> 31) & 0x88888888u, k2 = k8 >> 2;
             const uint32_t l8 = second ? k8 : 0u, l2 = l8 >> 2;
             uint4 e0, e1;
             e0.x = ((a << 3) & k8) | k2; e0.y = ((a << 2) & k8) | k2;
@@ -443,6 +432,8 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
     // ---- weight fragments: [tile64][kstep][tap][m][lane], 18 KB per step and tile
     const uint4 *wk = wfrag + (size_t)ct * ksteps * (18 * 64) + lane;
     v4i Wg[3][3][2];   // [kx][ky][m]
+    const int stride = gridDim.x;
+    plan(blockIdx.x);
     stage_issue(0);
 #pragma unroll
     for (int kx = 0; kx < 3; ++kx) load_group<2>(Wg[kx], wk, kx);
@@ -450,58 +441,86 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
     __syncthreads();
 
     const int tb_off = (wm * RW * 2 + half) * HALO_W + col;
-    for (int ks = 0; ks < ksteps; ++ks) {
-        const int kn = min(ks + 1, ksteps - 1);
-        const uint4 *wn_ptr = wk + (size_t)kn * (18 * 64);
-        const uint4 *tb = tile[ks & 1] + tb_off;
-        // The scheduling fences keep every fetch where it is written: issued as early as its
-        // destination registers are free, a whole step ahead of its use.
-        stage_issue(kn);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int kx = 0; kx < 3; ++kx) {
-            group_mma<RW, 2>(acc, Wg[kx], tb + kx);
-            __builtin_amdgcn_sched_barrier(0);
-            load_group<2>(Wg[kx], wn_ptr, kx);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        stage_commit(kn, tile[(ks + 1) & 1]);
-        __syncthreads();
-    }
-
-    // ---- epilogue
     const int Cow = Cout >> 5;
-    const int x = x0 + col;
     const int widx = ct * 2 + half;
-    const bool ok = has_ct && x < W && widx < Cow;
-    uint32_t words[RW];
+    int buf = 0;
+    // The block walks over its pixel tiles; the work is the flat sequence of steps
+    // (tile, 64-channel input step).  During a step the window and the weights of the NEXT
+    // step are fetched - at a tile's last step those of the next tile's first - so neither
+    // the matrix pipeline nor a new tile waits for staging.
+    for (int pt = blockIdx.x; pt < ptiles; pt += stride) {
+        v16f acc[RW][2];
 #pragma unroll
-    for (int r = 0; r < RW; ++r) {
-        const int y = y0 + wm * RW + r;
-        uint32_t s0 = 0, s1 = 0;
+        for (int m = 0; m < 2; ++m)
 #pragma unroll
-        for (int i = 15; i >= 0; --i) {
-            s0 = __builtin_amdgcn_alignbit(s0, __float_as_uint(acc[r][0][i]), 31);
-            s1 = __builtin_amdgcn_alignbit(s1, __float_as_uint(acc[r][1][i]), 31);
+            for (int q = 0; q < 4; ++q) {
+                const float4 f = init_tab[wave][half][m][q];
+#pragma unroll
+                for (int r = 0; r < RW; ++r) {
+                    acc[r][m][4 * q] = f.x; acc[r][m][4 * q + 1] = f.y;
+                    acc[r][m][4 * q + 2] = f.z; acc[r][m][4 * q + 3] = f.w;
+                }
+            }
+
+        for (int ks = 0; ks < ksteps; ++ks) {
+            const bool last = ks + 1 == ksteps;
+            const int kn = last ? 0 : ks + 1;
+            if (last) plan(pt + stride < ptiles ? pt + stride : pt);
+            const uint4 *wn_ptr = wk + (size_t)kn * (18 * 64);
+            const uint4 *tb = tile[buf] + tb_off;
+            // The scheduling fences keep every fetch where it is written: issued as early as
+            // its destination registers are free, a whole step ahead of its use.
+            stage_issue(kn);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int kx = 0; kx < 3; ++kx) {
+                group_mma<RW, 2>(acc, Wg[kx], tb + kx);
+                __builtin_amdgcn_sched_barrier(0);
+                load_group<2>(Wg[kx], wn_ptr, kx);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            buf ^= 1;
+            stage_commit(kn, tile[buf]);
+            __syncthreads();
         }
-        // s = sign bits (1 = below threshold) of channels 16*half + i
-        const uint32_t mine = (~s0 & 0xffffu) | (~s1 << 16);
-        const uint32_t other = (uint32_t)__shfl_xor((int)mine, 32);
-        words[r] = half == 0 ? ((mine & 0xffffu) | (other << 16))
-                             : ((other >> 16) | (mine & 0xffff0000u));
-        if (ok && y < H && out_bits)
-            out_bits[(((size_t)n * H + y) * W + x) * Cow + widx] = words[r];
-    }
-    if (POOL) {
-        // H, W even and the tile origin even: every 2x2 window lies inside one wave's rows
-        // and inside one lane pair
+
+        // ---- epilogue of this pixel tile
+        const int tx = pt % tiles_x;
+        const int q2 = pt / tiles_x;
+        const int ty = q2 % tiles_y;
+        const int n = q2 / tiles_y;
+        const int x = tx * TW + col;
+        const int yb = ty * TH + wm * RW;
+        const bool ok = has_ct && x < W && widx < Cow;
+        uint32_t words[RW];
 #pragma unroll
-        for (int r = 0; r < RW; r += 2) {
-            const int y = y0 + wm * RW + r;
-            uint32_t v = words[r] | words[r + 1];
-            v |= (uint32_t)__shfl_xor((int)v, 1);
-            if (ok && y < H && (col & 1) == 0)
-                out_pool[(((size_t)n * Hl + (y >> 1)) * Wl + (x >> 1)) * Cow + widx] = v;
+        for (int r = 0; r < RW; ++r) {
+            const int y = yb + r;
+            uint32_t s0 = 0, s1 = 0;
+#pragma unroll
+            for (int i = 15; i >= 0; --i) {
+                s0 = __builtin_amdgcn_alignbit(s0, __float_as_uint(acc[r][0][i]), 31);
+                s1 = __builtin_amdgcn_alignbit(s1, __float_as_uint(acc[r][1][i]), 31);
+            }
+            // s = sign bits (1 = below threshold) of channels 16*half + i
+            const uint32_t mine = (~s0 & 0xffffu) | (~s1 << 16);
+            const uint32_t other = (uint32_t)__shfl_xor((int)mine, 32);
+            words[r] = half == 0 ? ((mine & 0xffffu) | (other << 16))
+                                 : ((other >> 16) | (mine & 0xffff0000u));
+            if (ok && y < H && out_bits)
+                out_bits[(((size_t)n * H + y) * W + x) * Cow + widx] = words[r];
+        }
+        if (POOL) {
+            // H, W even and the tile origin even: every 2x2 window lies inside one wave's
+            // rows and inside one lane pair
+#pragma unroll
+            for (int r = 0; r < RW; r += 2) {
+                const int y = yb + r;
+                uint32_t v = words[r] | words[r + 1];
+                v |= (uint32_t)__shfl_xor((int)v, 1);
+                if (ok && y < H && (col & 1) == 0)
+                    out_pool[(((size_t)n * Hl + (y >> 1)) * Wl + (x >> 1)) * Cow + widx] = v;
+            }
         }
     }
 }
@@ -614,6 +633,7 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(
 }
 
 int g_tune_rw = 0, g_tune_wm = 0;   // 0 = automatic
+int g_persistent_blocks = 512;       // resident blocks of the block-cooperative kernel (2 per CU)
 
 template <int RW, int MT, bool CW_EVEN, bool ONE_STEP>
 static int launch_bits_t(const uint32_t *act, int N, int H, int W, const BlobLayout &L,
@@ -652,16 +672,22 @@ static int launch_block_t(const ConvIO &io, int N, int H, int W, const BlobLayou
     const int tiles64 = L.cout_pad64 / 64;
     long tiles = (long)N * ceil_div(H, RW * WM) * ceil_div(W, TW);
     if (tiles > 0x7fffffffL) return fail(MBU_ERR_SHAPE, "too many tiles for one launch");
-    dim3 grid((unsigned)tiles, (unsigned)ceil_div(tiles64, WN));
+    if ((double)N * H * W * io.cwa >= 2147483648.0)
+        return fail(MBU_ERR_SHAPE, "input tensor too large for one launch (2^31 words)");
+    // persistent blocks: two per compute unit in total, spread over the output-channel
+    // groups; each strides over the pixel tiles
+    const int groups = ceil_div(tiles64, WN);
+    const long per_group = max(1, g_persistent_blocks / groups);
+    dim3 grid((unsigned)min(tiles, per_group), (unsigned)groups);
     const bool even = (io.cwa % 2 == 0) && (!TWO_SRC || io.cwb % 2 == 0);
     if (even)
         MBU_LAUNCH((conv_mfma_block_kernel<RW, WM, WN, true, TWO_SRC, POOL>), grid, dim3(256), 0, s,
-                   io.act, io.low, N, H, W, io.cwa, io.cwb, L.ksteps, wfrag, L.cout, tiles64, thresh,
-                   io.out_bits, io.out_pool);
+                   io.act, io.low, N, H, W, io.cwa, io.cwb, L.ksteps, wfrag, L.cout, tiles64,
+                   (int)tiles, thresh, io.out_bits, io.out_pool);
     else
         MBU_LAUNCH((conv_mfma_block_kernel<RW, WM, WN, false, TWO_SRC, POOL>), grid, dim3(256), 0, s,
-                   io.act, io.low, N, H, W, io.cwa, io.cwb, L.ksteps, wfrag, L.cout, tiles64, thresh,
-                   io.out_bits, io.out_pool);
+                   io.act, io.low, N, H, W, io.cwa, io.cwb, L.ksteps, wfrag, L.cout, tiles64,
+                   (int)tiles, thresh, io.out_bits, io.out_pool);
     return check_launch("conv_mfma_block");
 }
 
