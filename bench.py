@@ -41,7 +41,40 @@ def parse():
     ap.add_argument("--width", type=int, default=2048)
     ap.add_argument("--no-sweep", action="store_true", help="skip the single-layer sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (3x) so that a counter pass of "
+                         "this command can scale FETCH_SIZE / WRITE_SIZE by a known transfer")
+    ap.add_argument("--single-layer", default=None, metavar="CIN,COUT,H,W",
+                    help="time one masked-binary 3x3 layer of this shape instead of the network "
+                         "(used for per-kernel counter passes); prints its own JSON line")
     return ap.parse_args()
+
+
+def traffic_from_profile():
+    """HBM bytes per convolution launch measured by the two counter passes recorded in
+    profiles/conv_mfma_unet_1024x2048_hbm_traffic.md (None if that file is absent)."""
+    path = os.path.join(ROOT, "profiles", "conv_mfma_unet_1024x2048_hbm_traffic.md")
+    try:
+        for line in open(path):
+            if line.startswith("conv_traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def single_layer(args, B, torch, synth):
+    cin, cout, h, w = (int(v) for v in args.single_layer.split(","))
+    case = synth.conv_case(1, 0, 1, h, w, cin, cout, 0.6)
+    act = B.pack_act(torch.from_numpy(case.a).cuda())
+    blob = B.pack_weights(torch.from_numpy(case.w).cuda())
+    th = torch.from_numpy(case.theta).cuda()
+    ms = time_layer(B, torch, act, cin, blob, cout, th, iters=args.steps, warm=args.warmup)
+    ops = 2.0 * synth.conv_macs(1, h, w, cin, cout)
+    print(json.dumps({"metric": "masked-binary conv effective GOPS", "value": round(ops / ms / 1e6, 1),
+                      "unit": "GOPS", "ms": round(ms, 4), "steps": args.steps,
+                      "config": {"workload": f"one layer {cin}->{cout} at 1x{h}x{w}, keep 0.6"},
+                      "frac_of_fp4_peak": round(ops / ms / 1e9 / PEAK_FP4_TFLOPS, 4)}))
 
 
 def time_layer(B, torch, act, cin, blob, cout, theta, iters=10, warm=2):
@@ -113,6 +146,9 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     B.set_conv_path({"auto": B.PATH_AUTO, "valu": B.PATH_VALU, "mfma": B.PATH_MFMA}[args.path])
+    if args.single_layer:
+        single_layer(args, B, torch, synth)
+        return
     N, H, W = 1, args.height, args.width
     case = synth.unet_case(3, 0, N, H, W, keep=0.6)
 
@@ -161,7 +197,7 @@ def main():
     step_ms /= K
     net.use_event_set(None)
 
-    per_layer, conv_ms, conv_ops = [], 0.0, 0.0
+    per_layer, conv_ms, conv_ops, conv_bytes = [], 0.0, 0.0, 0.0
     ci = 0
     for (name, _, h, w, c), ms in zip(infos, step_ms):
         row = {"step": name, "ms": round(float(ms), 4)}
@@ -174,6 +210,8 @@ def main():
                         "eff_tops": round(ops / ms / 1e9, 1)})
             conv_ms += ms
             conv_ops += ops
+            # input bits + output bits + the 4-bit weight codes, each once
+            conv_bytes += N * h * w * (cin + cout) / 8.0 + 9.0 * cin * cout / 2.0
         per_layer.append(row)
     n_conv = ci
     path = B.get_conv_path()
@@ -185,7 +223,8 @@ def main():
             "peak": PEAK_FP4_TFLOPS if mfma else PEAK_VALU_BIT_TOPS,
             "unit": "TFLOP/s" if mfma else "TOP/s",
             "frac": round(achieved / (PEAK_FP4_TFLOPS if mfma else PEAK_VALU_BIT_TOPS), 4),
-            "traffic": None,
+            "traffic": traffic_from_profile(),
+            "algorithmic_bytes_per_launch": round(conv_bytes / n_conv),
             "launches_per_step": n_conv,
             "avg_launch_ms": round(conv_ms / n_conv, 4),
             "algorithmic_ops_per_step": conv_ops,
@@ -212,6 +251,13 @@ def main():
     }
     del net, image, logits
     torch.cuda.empty_cache()
+    if args.calibrate_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_sweep:
         out["conv_sweep"] = conv_sweep(B, torch, synth)
     out["cpu_baseline"] = None if args.no_cpu else cpu_baseline(synth)
