@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--width", type=int, default=2048)
     ap.add_argument("--no-sweep", action="store_true", help="skip the single-layer sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--sparsity-sweep", action="store_true",
+                    help="run the batch-8 wide network for all four mean zero fractions "
+                         "(default: 0.6 only)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (3x) so that a counter pass of "
                          "this command can scale FETCH_SIZE / WRITE_SIZE by a known transfer")
@@ -109,6 +112,38 @@ def conv_sweep(B, torch, synth):
             rows.append(row)
             del act, blob, th
     B.set_conv_path(B.PATH_AUTO)
+    return rows
+
+
+def wide_batch(B, torch, synth, mean_zeros):
+    """Sparsity-stress workload: batch 8, 3x1024x1024, channels widened 2x, cost-aware per-layer
+    zero fractions around each mean; images/s of the whole forward pass."""
+    rows = []
+    plan = synth.unet_channel_plan(128, 4)
+    n, h, w = 8, 1024, 1024
+    for z in mean_zeros:
+        zf = synth.cost_aware_zero_fractions(plan, h, w, z)
+        case = synth.unet_case(4, 0, n, h, w, base=128, keeps=[1.0 - v for v in zf])
+        net = B.UNet(torch.from_numpy(case.stem_w).cuda(),
+                     [(torch.from_numpy(wt).cuda(), torch.from_numpy(t).cuda()) for wt, t in case.convs],
+                     torch.from_numpy(case.cls_w).cuda(), torch.from_numpy(case.cls_b).cuda(), levels=4)
+        image = torch.from_numpy(case.image).cuda()
+        logits = torch.empty((n, case.n_classes, h, w), dtype=torch.float32, device="cuda")
+        for _ in range(2):
+            net.forward(image, logits)
+        e0, e1 = B.Event(), B.Event()
+        iters = 5
+        e0.record()
+        for _ in range(iters):
+            net.forward(image, logits)
+        e1.record()
+        ms = e0.elapsed_ms(e1) / iters
+        ops = 2.0 * synth.unet_conv_macs(plan, n, h, w)
+        rows.append({"mean_zero_fraction": z, "ms_per_batch": round(ms, 3),
+                     "images_per_s": round(n * 1e3 / ms, 1),
+                     "conv_eff_tops_incl_other_layers": round(ops / ms / 1e9, 1)})
+        del net, image, logits, case
+        torch.cuda.empty_cache()
     return rows
 
 
@@ -260,6 +295,8 @@ def main():
         del src, dst
     if not args.no_sweep:
         out["conv_sweep"] = conv_sweep(B, torch, synth)
+        out["wide_batch8"] = wide_batch(B, torch, synth,
+                                        (0.2, 0.4, 0.6, 0.8) if args.sparsity_sweep else (0.6,))
     out["cpu_baseline"] = None if args.no_cpu else cpu_baseline(synth)
     out["paper_context"] = ("paper reports 2.04x speed-up and 3.54x lower energy vs FP16 U-Net on "
                             "A100/H100/Jetson Orin Nano/RTX 2080 Ti (1-bit tensor cores); no "

@@ -370,3 +370,14 @@ def test_unet_wide_batch_by_induction(mean_zero):
     zf = synth.cost_aware_zero_fractions(plan, 1024, 1024, mean_zero)
     case = synth.unet_case(4, 0, 2, 256, 256, base=128, keeps=[1.0 - z for z in zf])
     check_unet_by_induction(case, 2, 256, 256)
+
+
+def test_unet_wide_batch8_full_size():
+    """The sparsity-stress workload at its full size: batch 8, 3x1024x1024, channels widened
+    2x (128..2048, decoder inputs 384..3072), cost-aware zero pattern around 60 % zeros.
+    Checked by induction on sampled rows of the first and the last image."""
+    say("unet wide batch 8 at 1024x1024")
+    plan = synth.unet_channel_plan(128, 4)
+    zf = synth.cost_aware_zero_fractions(plan, 1024, 1024, 0.6)
+    case = synth.unet_case(4, 0, 8, 1024, 1024, base=128, keeps=[1.0 - z for z in zf])
+    check_unet_by_induction(case, 8, 1024, 1024, rows_per_layer=2)
