@@ -96,6 +96,29 @@ __device__ __forceinline__ void group_mma(v16f (&acc)[RW][MT], const v4i (&Wg)[3
     }
 }
 
+// First group of a pixel tile: the matrix instruction that opens an accumulator tile
+// (tap row ky = 0 at LDS row rho = r) takes -theta as its addend, so the accumulators are
+// never initialised by separate moves.
+template <int RW, int MT>
+__device__ __forceinline__ void group_mma_first(v16f (&acc)[RW][MT], const v16f (&init)[MT],
+                                                const v4i (&Wg)[3][MT], const uint4 *tb)
+{
+#pragma unroll
+    for (int rho = 0; rho < RW + 2; ++rho) {
+        const uint4 b = tb[rho * 2 * HALO_W];
+        const v4i B = {(int)b.x, (int)b.y, (int)b.z, (int)b.w};
+#pragma unroll
+        for (int ky = 0; ky < 3; ++ky) {
+            const int r = rho - ky;
+            if (r >= 0 && r < RW) {
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+                    acc[r][m] = mfma_f4(Wg[ky][m], B, ky == 0 ? init[m] : acc[r][m]);
+            }
+        }
+    }
+}
+
 // fragments of taps (ky, kx), ky = 0..2, of the wave's MT 32-channel tiles; wk points at
 // [tap 0][this wave's first 32-channel tile][lane] of one 64-channel input step
 template <int MT>
@@ -137,7 +160,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
     uint4(*tile)[TILE] = lds[wave];
 
     // ---- -theta for the MT x 16 channels of this lane
-    float init[MT][16];
+    v16f init[MT];
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
         const int cbase = (ct * MT + m) * 32 + 16 * half;  // 16 consecutive channels per lane
@@ -227,12 +250,12 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
     int buf = 0;
     for (int pt = slot; pt < ptiles; pt += slots) {
         v16f acc[RW][MT];
+        if (!ONE_STEP) {
 #pragma unroll
-        for (int m = 0; m < MT; ++m)
+            for (int m = 0; m < MT; ++m)
 #pragma unroll
-            for (int i = 0; i < 16; ++i)
-#pragma unroll
-                for (int r = 0; r < RW; ++r) acc[r][m][i] = init[m][i];
+                for (int r = 0; r < RW; ++r) acc[r][m] = init[m];
+        }
 
         for (int ks = 0; ks < ksteps; ++ks) {
             // the step after this one: next input step of this tile, or step 0 of the wave's
@@ -247,7 +270,8 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int kx = 0; kx < 3; ++kx) {
-                group_mma<RW, MT>(acc, Wg[kx], tb + kx);
+                if (ONE_STEP && kx == 0) group_mma_first<RW, MT>(acc, init, Wg[kx], tb + kx);
+                else group_mma<RW, MT>(acc, Wg[kx], tb + kx);
                 if (!ONE_STEP) {
                     __builtin_amdgcn_sched_barrier(0);
                     load_group<MT>(Wg[kx], wk + (size_t)kn * (18 * 64), kx);

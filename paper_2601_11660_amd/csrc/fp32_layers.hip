@@ -152,13 +152,21 @@ __global__ __launch_bounds__(256) void classifier_kernel(const uint32_t *__restr
     const long groups = (pixels + 31) / 32;
     const long wave_id = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
     const long n_waves = (long)gridDim.x * 4;
+    // the packed words of the wave's next pixel group are fetched while the current group is
+    // multiplied and stored
+    auto fetch = [&](long g, uint32_t (&wd)[CW]) {
+        const long pix = g * 32 + col;
+        const long pc = pix < pixels ? pix : pixels - 1;
+#pragma unroll
+        for (int k = 0; k < CW; ++k) wd[k] = act[pc * CW + k];
+    };
+    uint32_t words[CW], next[CW];
+    if (wave_id < groups) fetch(wave_id, words);
     for (long g = wave_id; g < groups; g += n_waves) {
+        const long gn = g + n_waves < groups ? g + n_waves : g;
+        fetch(gn, next);
         const long pix = g * 32 + col;
         const bool live = pix < pixels;
-        const long pc = live ? pix : pixels - 1;
-        uint32_t words[CW];
-#pragma unroll
-        for (int k = 0; k < CW; ++k) words[k] = act[pc * CW + k];
         v16f acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = bias[r];
@@ -181,9 +189,12 @@ __global__ __launch_bounds__(256) void classifier_kernel(const uint32_t *__restr
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int cls = 8 * (r >> 2) + 4 * half + (r & 3);
-                if (cls < K) o[(size_t)cls * HW] = acc[r];
+                // written once, never read by this library: keep it out of the caches
+                if (cls < K) __builtin_nontemporal_store(acc[r], o + (size_t)cls * HW);
             }
         }
+#pragma unroll
+        for (int k = 0; k < CW; ++k) words[k] = next[k];
     }
 }
 
