@@ -47,6 +47,30 @@ __device__ inline uint4 expand_word(uint32_t w)
     return r;
 }
 
+// Completes the packed output words of one image row from the per-lane sign collections.
+// s0 / s1: 16 sign bits (1 = below threshold) of channels 16*half + i of the wave's first /
+// second 32-channel tile.  The two lane halves of a pixel are brought together with one
+// v_permlane32_swap (lo = value of the pixel's lower-half lane, hi = of its upper-half lane,
+// in every lane) and one byte permute picks word 0 (channels 0..31) in the lower half and
+// word 1 (channels 32..63) in the upper half.  psel = 0x05040100 for half 0, 0x07060302 for
+// half 1.
+__device__ __forceinline__ uint32_t finish_word64(uint32_t s0, uint32_t s1, uint32_t psel)
+{
+    const uint32_t mine = (~s0 & 0xffffu) | (~s1 << 16);
+    const auto sw = __builtin_amdgcn_permlane32_swap(mine, mine, false, false);
+    // sw[0] = lower-half lane's value, sw[1] = upper-half lane's value
+    return __builtin_amdgcn_perm(sw[1], sw[0], psel);
+}
+
+// Same for a wave that owns a single 32-channel tile: the word is (lo & 0xffff) | (hi << 16)
+// in both halves.
+__device__ __forceinline__ uint32_t finish_word32(uint32_t s0)
+{
+    const uint32_t mine = ~s0 & 0xffffu;
+    const auto sw = __builtin_amdgcn_permlane32_swap(mine, mine, false, false);
+    return sw[0] | (sw[1] << 16);
+}
+
 constexpr int TW = 32;            // pixels per matrix column tile (one image-row segment)
 constexpr int HALO_W = TW + 2;
 
@@ -247,6 +271,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
 
     const int tb_off = half * HALO_W + col;
     const int Cow = Cout >> 5;
+    const uint32_t psel = half ? 0x07060302u : 0x05040100u;
     int buf = 0;
     for (int pt = slot; pt < ptiles; pt += slots) {
         v16f acc[RW][MT];
@@ -291,34 +316,29 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
         const int ty = q % tiles_y;
         const int n = q / tiles_y;
         const int x = tx * TW + col;
+        const int y0 = ty * RW;
+        uint32_t *orow = out_bits + (((size_t)n * H + y0) * W + x) * Cow;
+        const size_t row_stride = (size_t)W * Cow;
 #pragma unroll
         for (int r = 0; r < RW; ++r) {
-            const int y = ty * RW + r;
-            uint32_t s[MT];
+            uint32_t sgn[MT];
 #pragma unroll
             for (int m = 0; m < MT; ++m) {
-                s[m] = 0;
+                sgn[m] = 0;
 #pragma unroll
                 for (int i = 15; i >= 0; --i)
-                    s[m] = __builtin_amdgcn_alignbit(s[m], __float_as_uint(acc[r][m][i]), 31);
+                    sgn[m] = __builtin_amdgcn_alignbit(sgn[m], __float_as_uint(acc[r][m][i]), 31);
             }
-            // s = sign bits (1 = below threshold) of channels 16*half + i of tile m
             uint32_t word;
             int widx;
             if (MT == 2) {
-                const uint32_t mine = (~s[0] & 0xffffu) | (~s[MT - 1] << 16);
-                const uint32_t other = (uint32_t)__shfl_xor((int)mine, 32);
-                word = half == 0 ? ((mine & 0xffffu) | (other << 16))
-                                 : ((other >> 16) | (mine & 0xffff0000u));
+                word = finish_word64(sgn[0], sgn[MT - 1], psel);
                 widx = ct * 2 + half;       // half 0 stores the first word, half 1 the second
             } else {
-                const uint32_t mine = ~s[0] & 0xffffu;
-                const uint32_t other = (uint32_t)__shfl_xor((int)mine, 32);
-                word = half == 0 ? (mine | (other << 16)) : (other | (mine << 16));
+                word = finish_word32(sgn[0]);
                 widx = (half == (r & 1)) ? ct : Cow;   // alternate the storing half per row
             }
-            if (widx < Cow && y < H && x < W)
-                out_bits[(((size_t)n * H + y) * W + x) * Cow + widx] = word;
+            if (widx < Cow && y0 + r < H && x < W) orow[r * row_stride + widx] = word;
         }
     }
 }
@@ -467,6 +487,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
     const int tb_off = (wm * RW * 2 + half) * HALO_W + col;
     const int Cow = Cout >> 5;
     const int widx = ct * 2 + half;
+    const uint32_t psel = half ? 0x07060302u : 0x05040100u;
     int buf = 0;
     // The block walks over its pixel tiles; the work is the flat sequence of steps
     // (tile, 64-channel input step).  During a step the window and the weights of the NEXT
@@ -517,22 +538,18 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
         const int yb = ty * TH + wm * RW;
         const bool ok = has_ct && x < W && widx < Cow;
         uint32_t words[RW];
+        uint32_t *orow = out_bits + (((size_t)n * H + yb) * W + x) * Cow + widx;
+        const size_t row_stride = (size_t)W * Cow;
 #pragma unroll
         for (int r = 0; r < RW; ++r) {
-            const int y = yb + r;
             uint32_t s0 = 0, s1 = 0;
 #pragma unroll
             for (int i = 15; i >= 0; --i) {
                 s0 = __builtin_amdgcn_alignbit(s0, __float_as_uint(acc[r][0][i]), 31);
                 s1 = __builtin_amdgcn_alignbit(s1, __float_as_uint(acc[r][1][i]), 31);
             }
-            // s = sign bits (1 = below threshold) of channels 16*half + i
-            const uint32_t mine = (~s0 & 0xffffu) | (~s1 << 16);
-            const uint32_t other = (uint32_t)__shfl_xor((int)mine, 32);
-            words[r] = half == 0 ? ((mine & 0xffffu) | (other << 16))
-                                 : ((other >> 16) | (mine & 0xffff0000u));
-            if (ok && y < H && out_bits)
-                out_bits[(((size_t)n * H + y) * W + x) * Cow + widx] = words[r];
+            words[r] = finish_word64(s0, s1, psel);
+            if (ok && yb + r < H && out_bits) orow[r * row_stride] = words[r];
         }
         if (POOL) {
             // H, W even and the tile origin even: every 2x2 window lies inside one wave's
@@ -541,7 +558,8 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
             for (int r = 0; r < RW; r += 2) {
                 const int y = yb + r;
                 uint32_t v = words[r] | words[r + 1];
-                v |= (uint32_t)__shfl_xor((int)v, 1);
+                // neighbouring lane (quad permute [1,0,3,2]) holds the next pixel of the row
+                v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, true);
                 if (ok && y < H && (col & 1) == 0)
                     out_pool[(((size_t)n * Hl + (y >> 1)) * Wl + (x >> 1)) * Cow + widx] = v;
             }
