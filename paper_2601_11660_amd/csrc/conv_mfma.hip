@@ -71,6 +71,43 @@ __device__ __forceinline__ uint32_t finish_word32(uint32_t s0)
     return sw[0] | (sw[1] << 16);
 }
 
+// Position of a pixel tile, advanced by a fixed stride without divisions: the stride is
+// split on the host into (dx, dy, dn) = stride mod tiles_x, (stride / tiles_x) mod tiles_y,
+// stride / (tiles_x * tiles_y).
+struct TileStep {
+    int tiles_x, tiles_y, dx, dy, dn;
+};
+struct TilePos {
+    int tx, ty, n;
+    __device__ __forceinline__ void advance(const TileStep &st)
+    {
+        tx += st.dx;
+        if (tx >= st.tiles_x) { tx -= st.tiles_x; ++ty; }
+        ty += st.dy;
+        if (ty >= st.tiles_y) { ty -= st.tiles_y; ++n; }
+        n += st.dn;
+    }
+};
+__host__ __device__ inline TilePos tile_pos(int pt, int tiles_x, int tiles_y)
+{
+    TilePos p;
+    p.tx = pt % tiles_x;
+    const int q = pt / tiles_x;
+    p.ty = q % tiles_y;
+    p.n = q / tiles_y;
+    return p;
+}
+static TileStep tile_step(int stride, int tiles_x, int tiles_y)
+{
+    TileStep st;
+    st.tiles_x = tiles_x;
+    st.tiles_y = tiles_y;
+    st.dx = stride % tiles_x;
+    st.dy = (stride / tiles_x) % tiles_y;
+    st.dn = stride / (tiles_x * tiles_y);
+    return st;
+}
+
 constexpr int TW = 32;            // pixels per matrix column tile (one image-row segment)
 constexpr int HALO_W = TW + 2;
 
@@ -163,7 +200,7 @@ __device__ __forceinline__ void load_group(v4i (&Wg)[3][MT], const uint4 *wk, in
 template <int RW, int MT, bool CW_EVEN, bool ONE_STEP>
 __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
     const uint32_t *__restrict__ act, int N, int H, int W, int Cw, int ksteps,
-    const uint4 *__restrict__ wfrag, int Cout, int ctiles, int slots, int ptiles,
+    const uint4 *__restrict__ wfrag, int Cout, int ctiles, int slots, int ptiles, TileStep tstep,
     const int32_t *__restrict__ thresh, uint32_t *__restrict__ out_bits)
 {
     constexpr int HR = RW + 2;
@@ -179,8 +216,6 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
     const int ct = gw % ctiles;                   // (32*MT)-channel output tile, fixed for the wave
     const int slot = gw / ctiles;
     const int col = lane & 31, half = lane >> 5;
-    const int tiles_x = (W + TW - 1) / TW;
-    const int tiles_y = (H + RW - 1) / RW;
     uint4(*tile)[TILE] = lds[wave];
 
     // ---- -theta for the MT x 16 channels of this lane
@@ -208,11 +243,8 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
     // ---- staging plan for the window of a pixel tile: lane handles halo pixels lane + 64*j
     uint32_t src[NLD];            // word offset of the (clamped) pixel from `act`
     uint32_t m8[NLD];             // 0x88888888 inside the image, 0 outside
-    auto plan = [&](int pt) {
-        const int tx = pt % tiles_x;
-        const int q = pt / tiles_x;
-        const int ty = q % tiles_y;
-        const int n = q / tiles_y;
+    auto plan = [&](const TilePos &tp) {
+        const int tx = tp.tx, ty = tp.ty, n = tp.n;
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
             int p = lane + 64 * j;
@@ -263,7 +295,8 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
     const int t64 = (ct * MT) >> 1, mfirst = (ct * MT) & 1;
     const uint4 *wk = wfrag + ((size_t)t64 * ksteps * 18 + mfirst) * 64 + lane;
     v4i Wg[3][3][MT];   // [kx][ky][m]
-    plan(slot);
+    TilePos cur = tile_pos(slot, tstep.tiles_x, tstep.tiles_y);   // the only divisions
+    plan(cur);
     stage_issue(0);
 #pragma unroll
     for (int kx = 0; kx < 3; ++kx) load_group<MT>(Wg[kx], wk, kx);
@@ -287,7 +320,11 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
             // next tile (its own last window again when there is none)
             const bool last = ks + 1 == ksteps;
             const int kn = last ? 0 : ks + 1;
-            if (last) plan(pt + slots < ptiles ? pt + slots : pt);
+            if (last) {
+                TilePos nxt = cur;
+                if (pt + slots < ptiles) nxt.advance(tstep);
+                plan(nxt);
+            }
             const uint4 *tb = tile[buf] + tb_off;
             // The scheduling fences keep every fetch where it is written: issued as early as
             // its destination registers are free, a whole step ahead of its use.
@@ -311,35 +348,33 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
         }
 
         // ---- epilogue of this pixel tile
-        const int tx = pt % tiles_x;
-        const int q = pt / tiles_x;
-        const int ty = q % tiles_y;
-        const int n = q / tiles_y;
-        const int x = tx * TW + col;
-        const int y0 = ty * RW;
-        uint32_t *orow = out_bits + (((size_t)n * H + y0) * W + x) * Cow;
+        const int x = cur.tx * TW + col;
+        const int y0 = cur.ty * RW;
+        uint32_t *orow = out_bits + (((size_t)cur.n * H + y0) * W + x) * Cow;
         const size_t row_stride = (size_t)W * Cow;
+        // all sign collections first (RW*MT independent dependency chains in one basic block),
+        // then the words, then the stores
+        uint32_t sgn[RW][MT];
+#pragma unroll
+        for (int i = 15; i >= 0; --i)
+#pragma unroll
+            for (int r = 0; r < RW; ++r)
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+                    sgn[r][m] = __builtin_amdgcn_alignbit(i == 15 ? 0u : sgn[r][m],
+                                                          __float_as_uint(acc[r][m][i]), 31);
+        uint32_t word[RW];
+#pragma unroll
+        for (int r = 0; r < RW; ++r)
+            word[r] = MT == 2 ? finish_word64(sgn[r][0], sgn[r][MT - 1], psel) : finish_word32(sgn[r][0]);
 #pragma unroll
         for (int r = 0; r < RW; ++r) {
-            uint32_t sgn[MT];
-#pragma unroll
-            for (int m = 0; m < MT; ++m) {
-                sgn[m] = 0;
-#pragma unroll
-                for (int i = 15; i >= 0; --i)
-                    sgn[m] = __builtin_amdgcn_alignbit(sgn[m], __float_as_uint(acc[r][m][i]), 31);
-            }
-            uint32_t word;
-            int widx;
-            if (MT == 2) {
-                word = finish_word64(sgn[0], sgn[MT - 1], psel);
-                widx = ct * 2 + half;       // half 0 stores the first word, half 1 the second
-            } else {
-                word = finish_word32(sgn[0]);
-                widx = (half == (r & 1)) ? ct : Cow;   // alternate the storing half per row
-            }
-            if (widx < Cow && y0 + r < H && x < W) orow[r * row_stride + widx] = word;
+            // MT == 2: half 0 stores the first word, half 1 the second; MT == 1: the storing
+            // half alternates per row
+            const int widx = MT == 2 ? ct * 2 + half : ((half == (r & 1)) ? ct : Cow);
+            if (widx < Cow && y0 + r < H && x < W) orow[r * row_stride + widx] = word[r];
         }
+        cur.advance(tstep);
     }
 }
 
@@ -362,7 +397,7 @@ template <int RW, int WM, int WN, bool CW_EVEN, bool TWO_SRC, bool POOL>
 __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
     const uint32_t *__restrict__ act, const uint32_t *__restrict__ low, int N, int H, int W,
     int Cwa, int Cwb, int ksteps, const uint4 *__restrict__ wfrag, int Cout, int tiles64,
-    int ptiles, const int32_t *__restrict__ thresh, uint32_t *__restrict__ out_bits,
+    int ptiles, TileStep tstep, const int32_t *__restrict__ thresh, uint32_t *__restrict__ out_bits,
     uint32_t *__restrict__ out_pool)
 {
     static_assert(WM * WN == 4, "four waves per block");
@@ -382,8 +417,6 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
     const int wm = wave % WM, wn = wave / WM;
     const int col = lane & 31, half = lane >> 5;
     const int Cw = Cwa + (TWO_SRC ? Cwb : 0);     // words per pixel of the (virtual) input
-    const int tiles_x = (W + TW - 1) / TW;
-    const int tiles_y = (H + TH - 1) / TH;
     const int Hl = H >> 1, Wl = W >> 1;
     const int ct_raw = blockIdx.y * WN + wn;      // 64-channel output tile of this wave
     const bool has_ct = ct_raw < tiles64;
@@ -408,11 +441,8 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
     // bit 31 of offa = "pixel lies inside the image" (tensors are limited to 2^31 words)
     uint32_t offa[NLD];                  // word offset of the (clamped) pixel in act
     uint32_t offb[TWO_SRC ? NLD : 1];    // ... of the pixel (y/2, x/2) in low
-    auto plan = [&](int pt) {
-        const int tx = pt % tiles_x;
-        const int q = pt / tiles_x;
-        const int ty = q % tiles_y;
-        const int n = q / tiles_y;
+    auto plan = [&](const TilePos &tp) {
+        const int tx = tp.tx, ty = tp.ty, n = tp.n;
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
             int p = tid + NT * j;
@@ -477,7 +507,8 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
     const uint4 *wk = wfrag + (size_t)ct * ksteps * (18 * 64) + lane;
     v4i Wg[3][3][2];   // [kx][ky][m]
     const int stride = gridDim.x;
-    plan(blockIdx.x);
+    TilePos cur = tile_pos(blockIdx.x, tstep.tiles_x, tstep.tiles_y);   // the only divisions
+    plan(cur);
     stage_issue(0);
 #pragma unroll
     for (int kx = 0; kx < 3; ++kx) load_group<2>(Wg[kx], wk, kx);
@@ -510,7 +541,11 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
         for (int ks = 0; ks < ksteps; ++ks) {
             const bool last = ks + 1 == ksteps;
             const int kn = last ? 0 : ks + 1;
-            if (last) plan(pt + stride < ptiles ? pt + stride : pt);
+            if (last) {
+                TilePos nxt = cur;
+                if (pt + stride < ptiles) nxt.advance(tstep);
+                plan(nxt);
+            }
             const uint4 *wn_ptr = wk + (size_t)kn * (18 * 64);
             const uint4 *tb = tile[buf] + tb_off;
             // The scheduling fences keep every fetch where it is written: issued as early as
@@ -530,27 +565,29 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
         }
 
         // ---- epilogue of this pixel tile
-        const int tx = pt % tiles_x;
-        const int q2 = pt / tiles_x;
-        const int ty = q2 % tiles_y;
-        const int n = q2 / tiles_y;
-        const int x = tx * TW + col;
-        const int yb = ty * TH + wm * RW;
+        const int n = cur.n;
+        const int x = cur.tx * TW + col;
+        const int yb = cur.ty * TH + wm * RW;
         const bool ok = has_ct && x < W && widx < Cow;
         uint32_t words[RW];
         uint32_t *orow = out_bits + (((size_t)n * H + yb) * W + x) * Cow + widx;
         const size_t row_stride = (size_t)W * Cow;
+        // all sign collections first (2*RW independent dependency chains in one basic block),
+        // then the words, then the stores
+        uint32_t sgn[RW][2];
 #pragma unroll
-        for (int r = 0; r < RW; ++r) {
-            uint32_t s0 = 0, s1 = 0;
+        for (int i = 15; i >= 0; --i)
 #pragma unroll
-            for (int i = 15; i >= 0; --i) {
-                s0 = __builtin_amdgcn_alignbit(s0, __float_as_uint(acc[r][0][i]), 31);
-                s1 = __builtin_amdgcn_alignbit(s1, __float_as_uint(acc[r][1][i]), 31);
-            }
-            words[r] = finish_word64(s0, s1, psel);
+            for (int r = 0; r < RW; ++r)
+#pragma unroll
+                for (int m = 0; m < 2; ++m)
+                    sgn[r][m] = __builtin_amdgcn_alignbit(i == 15 ? 0u : sgn[r][m],
+                                                          __float_as_uint(acc[r][m][i]), 31);
+#pragma unroll
+        for (int r = 0; r < RW; ++r) words[r] = finish_word64(sgn[r][0], sgn[r][1], psel);
+#pragma unroll
+        for (int r = 0; r < RW; ++r)
             if (ok && yb + r < H && out_bits) orow[r * row_stride] = words[r];
-        }
         if (POOL) {
             // H, W even and the tile origin even: every 2x2 window lies inside one wave's
             // rows and inside one lane pair
@@ -564,6 +601,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
                     out_pool[(((size_t)n * Hl + (y >> 1)) * Wl + (x >> 1)) * Cow + widx] = v;
             }
         }
+        cur.advance(tstep);
     }
 }
 
@@ -691,9 +729,10 @@ static int launch_bits_t(const uint32_t *act, int N, int H, int W, const BlobLay
     if (ctiles > max_waves) return fail(MBU_ERR_SHAPE, "too many output channels");
     const int slots = (int)min(ptiles, (long)(max_waves / ctiles));
     const int waves = slots * ctiles;
+    const TileStep tstep = tile_step(slots, ceil_div(W, TW), ceil_div(H, RW));
     MBU_LAUNCH((conv_mfma_bits_kernel<RW, MT, CW_EVEN, ONE_STEP>), dim3(ceil_div(waves, 4)),
                dim3(256), 0, s, act, N, H, W, L.cin_words, L.ksteps, wfrag, L.cout, ctiles, slots,
-               (int)ptiles, thresh, out_bits);
+               (int)ptiles, tstep, thresh, out_bits);
     return check_launch("conv_mfma_bits");
 }
 
@@ -721,15 +760,16 @@ static int launch_block_t(const ConvIO &io, int N, int H, int W, const BlobLayou
     const int groups = ceil_div(tiles64, WN);
     const long per_group = max(1, g_persistent_blocks / groups);
     dim3 grid((unsigned)min(tiles, per_group), (unsigned)groups);
+    const TileStep tstep = tile_step((int)grid.x, ceil_div(W, TW), ceil_div(H, RW * WM));
     const bool even = (io.cwa % 2 == 0) && (!TWO_SRC || io.cwb % 2 == 0);
     if (even)
         MBU_LAUNCH((conv_mfma_block_kernel<RW, WM, WN, true, TWO_SRC, POOL>), grid, dim3(256), 0, s,
                    io.act, io.low, N, H, W, io.cwa, io.cwb, L.ksteps, wfrag, L.cout, tiles64,
-                   (int)tiles, thresh, io.out_bits, io.out_pool);
+                   (int)tiles, tstep, thresh, io.out_bits, io.out_pool);
     else
         MBU_LAUNCH((conv_mfma_block_kernel<RW, WM, WN, false, TWO_SRC, POOL>), grid, dim3(256), 0, s,
                    io.act, io.low, N, H, W, io.cwa, io.cwb, L.ksteps, wfrag, L.cout, tiles64,
-                   (int)tiles, thresh, io.out_bits, io.out_pool);
+                   (int)tiles, tstep, thresh, io.out_bits, io.out_pool);
     return check_launch("conv_mfma_block");
 }
 
