@@ -74,6 +74,32 @@ void orc_conv3x3_points(const int8_t *a, int N, int H, int W, int Cin,
                             pts[4 * k + 2], pts[4 * k + 3]);
 }
 
+/* Masked transposed convolution, kernel 2x2, stride 2 (the decoder's up-sampling layer,
+ * Sec. 2.1; Sec. 3.2.2 says it is "performed similarly" to the convolution).  With
+ * kernel = stride every output pixel receives exactly one tap:
+ *   acc[n, 2y+dy, 2x+dx, o] = sum_c w[o][dy][dx][c] * a[n, y, x, c].
+ * a is NHWC [N][H][W][Cin], w is [Cout][2][2][Cin], acc is NHWC [N][2H][2W][Cout]. */
+void orc_tconv2x2(const int8_t *a, int N, int H, int W, int Cin,
+                  const int8_t *w, int Cout, int32_t *acc)
+{
+    long rows = (long)N * H;
+#pragma omp parallel for schedule(static)
+    for (long r = 0; r < rows; ++r) {
+        int n = (int)(r / H), y = (int)(r % H);
+        for (int x = 0; x < W; ++x) {
+            const int8_t *ap = a + (((size_t)n * H + y) * W + x) * Cin;
+            for (int dy = 0; dy < 2; ++dy)
+                for (int dx = 0; dx < 2; ++dx)
+                    for (int o = 0; o < Cout; ++o) {
+                        const int8_t *wp = w + (((size_t)o * 2 + dy) * 2 + dx) * Cin;
+                        int32_t s = 0;
+                        for (int c = 0; c < Cin; ++c) s += (int32_t)wp[c] * (int32_t)ap[c];
+                        acc[(((size_t)n * 2 * H + 2 * y + dy) * 2 * W + 2 * x + dx) * Cout + o] = s;
+                    }
+        }
+    }
+}
+
 /* Algorithm 1, threshold step: output is +1 where R >= theta, else -1 (a tie
  * binarises to +1).  total = N*H*W*C values, channel fastest. */
 void orc_threshold(const int32_t *acc, const int32_t *theta, long pixels, int C,

@@ -83,6 +83,27 @@ def masked_binary_layer(a, w, theta):
     return acc, threshold(acc, theta)
 
 
+def tconv2x2(a, w):
+    """Masked transposed convolution, kernel 2x2 stride 2 (up-sampling layer of the decoder,
+    Sec. 2.1): acc[n,2y+dy,2x+dx,o] = sum_c w[o,dy,dx,c] * a[n,y,x,c].  w is [Cout,2,2,Cin]."""
+    a = _chk(a, np.int8, 4)
+    w = _chk(w, np.int8, 4)
+    N, H, W, Cin = a.shape
+    Cout = w.shape[0]
+    assert w.shape == (Cout, 2, 2, Cin)
+    acc = np.empty((N, 2 * H, 2 * W, Cout), np.int32)
+    lib().orc_tconv2x2(_p(a), N, H, W, Cin, _p(w), Cout, _p(acc))
+    return acc
+
+
+def masked_binary_tconv_layer(a, w, theta):
+    """Transposed layer followed by the threshold step (the quantised network adds batch
+    norm + binary activation after the transposed convolution, Appendix A.1; both fold into
+    the integer threshold as in Algorithm 1).  Returns (acc, +-1 output)."""
+    acc = tconv2x2(a, w)
+    return acc, threshold(acc, theta)
+
+
 def maxpool2x2(a):
     a = _chk(a, np.int8, 4)
     N, H, W, C = a.shape
@@ -139,8 +160,12 @@ def classifier(a, w, b):
     return out
 
 
-def unet_forward(image, stem_w, convs, cls_w, cls_b, levels=4):
+def unet_forward(image, stem_w, convs, cls_w, cls_b, levels=4, up_convs=None):
     """Whole network on unpacked values.
+
+    up_convs: None = the decoder up-samples by 2x nearest neighbour.  Otherwise a list of
+    (w [Cout,2,2,Cin], theta) per decoder level, deepest first: the decoder up-samples with a
+    masked transposed convolution + threshold (Sec. 2.1, Appendix A.1) instead.
 
     convs: list of (w, theta) in execution order: two per encoder level (level 1 ..
     `levels`), two for the bottleneck, two per decoder level (`levels` .. 1);
@@ -170,7 +195,11 @@ def unet_forward(image, stem_w, convs, cls_w, cls_b, levels=4):
         taps.append((f"pool{l}", x))
     x = double_conv(x, "mid")
     for l in range(levels, 0, -1):
-        x = upsample2x(x)
+        if up_convs is None:
+            x = upsample2x(x)
+        else:
+            wu, tu = up_convs[levels - l]
+            _, x = masked_binary_tconv_layer(x, wu, tu)
         taps.append((f"up{l}", x))
         x = concat(skips[l - 1], x)
         taps.append((f"cat{l}", x))

@@ -70,13 +70,24 @@ def conv_case(config_id: int, seed: int, n: int, h: int, w: int, cin: int, cout:
                     keep=keep)
 
 
-def unet_channel_plan(base: int = 64, levels: int = 4) -> List[Tuple[str, int, int, int]]:
+def ternary_tconv_weights(config_id: int, seed: int, layer: int, cout: int, cin: int,
+                          keep: float) -> np.ndarray:
+    """[cout,2,2,cin] int8 for the 2x2 stride-2 transposed layer."""
+    sign = pm1_bits(_rng(config_id, seed, layer, _SIGN), (cout, 2, 2, cin))
+    kept = _rng(config_id, seed, layer, _KEEP).random((cout, 2, 2, cin), dtype=np.float32) < keep
+    return (sign * kept).astype(np.int8)
+
+
+def unet_channel_plan(base: int = 64, levels: int = 4,
+                      transposed: bool = False) -> List[Tuple[str, int, int, int]]:
     """(name, cin, cout, level) of every masked-binary 3x3 layer in execution order.
 
     `level` is the resolution level (1 = full resolution, levels+1 = bottleneck).
     Encoder level l: two convs ending at base*2^(l-1) channels.  Bottleneck: doubles
     once more.  Decoder level l: the up-sampled feature keeps its channel count
-    (nearest-neighbour up-sampling), so the first conv sees skip + up channels.
+    (nearest-neighbour up-sampling), so the first conv sees skip + up channels.  With
+    transposed=True the decoder up-samples with a transposed layer that maps 2c -> c
+    channels (not listed here), so the first conv sees c + c channels.
     """
     plan = []
     c_prev = base
@@ -91,6 +102,8 @@ def unet_channel_plan(base: int = 64, levels: int = 4) -> List[Tuple[str, int, i
     c_up = c_mid
     for l in range(levels, 0, -1):
         c = base << (l - 1)
+        if transposed:
+            c_up = c          # the transposed layer halves the channel count (Sec. 2.1)
         plan.append((f"dec{l}a", c + c_up, c, l))
         plan.append((f"dec{l}b", c, c, l))
         c_up = c
@@ -109,6 +122,7 @@ class UNetCase:
     levels: int
     base: int
     n_classes: int
+    up_convs: Optional[List[Tuple[np.ndarray, np.ndarray]]] = None   # transposed decoder
 
 
 def cost_aware_zero_fractions(plan, h: int, w: int, mean_zero: float) -> List[float]:
@@ -130,10 +144,11 @@ def cost_aware_zero_fractions(plan, h: int, w: int, mean_zero: float) -> List[fl
 def unet_case(config_id: int, seed: int, n: int, h: int, w: int, base: int = 64,
               levels: int = 4, n_classes: int = 19,
               keep: Optional[float] = None,
-              keeps: Optional[Sequence[float]] = None) -> UNetCase:
+              keeps: Optional[Sequence[float]] = None,
+              transposed: bool = False) -> UNetCase:
     """Whole-network inputs.  keep=None and keeps=None draws each layer's keep
     probability uniformly in [0.4, 0.8]; thresholds are uniform in +-floor(9*cin/16)."""
-    plan = unet_channel_plan(base, levels)
+    plan = unet_channel_plan(base, levels, transposed)
     image = _rng(config_id, seed, 0, _IMG).standard_normal((n, 3, h, w), dtype=np.float32)
     stem_w = _rng(config_id, seed, 0, _STEMW).standard_normal((base, 3, 3, 3), dtype=np.float32)
     convs, used = [], []
@@ -150,7 +165,15 @@ def unet_case(config_id: int, seed: int, n: int, h: int, w: int, base: int = 64,
     cls_w = (_rng(config_id, seed, 0, _CLSW).standard_normal((n_classes, base), dtype=np.float32)
              / np.float32(8.0))
     cls_b = _rng(config_id, seed, 0, _CLSB).standard_normal((n_classes,), dtype=np.float32)
-    return UNetCase(image=image, stem_w=stem_w, convs=convs, cls_w=cls_w, cls_b=cls_b,
+    up_convs = None
+    if transposed:
+        up_convs = []
+        for j, l in enumerate(range(levels, 0, -1)):
+            c = base << (l - 1)
+            k = float(keep) if keep is not None else 0.6
+            up_convs.append((ternary_tconv_weights(config_id, seed, 100 + j, c, 2 * c, k),
+                             thresholds(config_id, seed, 100 + j, c, (2 * c) // 8)))
+    return UNetCase(up_convs=up_convs, image=image, stem_w=stem_w, convs=convs, cls_w=cls_w, cls_b=cls_b,
                     plan=plan, keeps=used, levels=levels, base=base, n_classes=n_classes)
 
 

@@ -348,3 +348,83 @@ def test_config0_regression_fixture():
     with open(path) as f:
         stored = f.read().splitlines()
     assert stored == config0_summary()
+
+
+# ------------------------------------------------------- transposed layer (decoder)
+def test_tconv_equals_torch_conv_transpose_and_brute_force():
+    rng = np.random.default_rng(21)
+    a = synth.pm1_bits(rng, (2, 5, 7, 40))
+    w = synth.ternary_tconv_weights(99, 0, 0, 24, 40, 0.6)
+    acc = O.tconv2x2(a, w)
+    assert acc.shape == (2, 10, 14, 24)
+    # library special case: ConvTranspose2d weight is [Cin][Cout][kh][kw]
+    wt = torch.from_numpy(w).double().permute(3, 0, 1, 2)
+    ref = F.conv_transpose2d(torch.from_numpy(a).double().permute(0, 3, 1, 2), wt, stride=2)
+    assert np.array_equal(acc.astype(np.float64), ref.permute(0, 2, 3, 1).numpy())
+    # brute force in scatter form on a tiny case
+    a2, w2 = a[:1, :2, :3, :5], w[:3, :, :, :5]
+    out = np.zeros((1, 4, 6, 3), np.int64)
+    for y in range(2):
+        for x in range(3):
+            for dy in range(2):
+                for dx in range(2):
+                    for o in range(3):
+                        out[0, 2 * y + dy, 2 * x + dx, o] = sum(
+                            int(w2[o, dy, dx, c]) * int(a2[0, y, x, c]) for c in range(5))
+    assert np.array_equal(O.tconv2x2(np.ascontiguousarray(a2), np.ascontiguousarray(w2)), out)
+
+
+def test_tconv_single_tap_and_invariants():
+    rng = np.random.default_rng(22)
+    a = synth.pm1_bits(rng, (1, 3, 4, 6))
+    for (o, dy, dx, c, sgn) in [(0, 0, 0, 2, 1), (1, 1, 0, 5, -1), (2, 0, 1, 0, 1), (1, 1, 1, 3, -1)]:
+        w = np.zeros((3, 2, 2, 6), np.int8)
+        w[o, dy, dx, c] = sgn
+        acc = O.tconv2x2(a, w)
+        exp = np.zeros((6, 8), np.int32)
+        exp[dy::2, dx::2] = sgn * a[0, :, :, c]
+        assert np.array_equal(acc[0, :, :, o], exp)
+        assert not acc[0][:, :, [k for k in range(3) if k != o]].any()
+    w = synth.ternary_tconv_weights(99, 1, 0, 4, 6, 0.5)
+    acc = O.tconv2x2(a, w)
+    assert np.array_equal(O.tconv2x2(-a, w), -acc)
+    kept = O.tconv2x2(np.ones_like(a), np.abs(w).astype(np.int8))
+    assert (np.abs(acc) <= kept).all() and ((acc - kept) % 2 == 0).all()
+    assert not O.tconv2x2(a, np.zeros_like(w)).any()
+
+
+def test_unet_with_transposed_decoder_matches_torch():
+    case = synth.unet_case(5, 0, 1, 16, 32, base=32, levels=2, n_classes=3, transposed=True)
+    pre, _ = O.stem(case.image, case.stem_w)
+    assert np.abs(pre).min() > 2e-5
+    logits, taps = O.unet_forward(case.image, case.stem_w, case.convs, case.cls_w, case.cls_b,
+                                  levels=2, up_convs=case.up_convs)
+
+    def t(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).double()
+    x = F.conv2d(t(case.image), t(case.stem_w).permute(0, 3, 1, 2), padding=1)
+    x = torch.where(x >= 0, 1.0, -1.0).double()
+    it = iter(case.convs)
+
+    def dconv(x):
+        for _ in range(2):
+            w, th = next(it)
+            acc = F.conv2d(x, t(w).permute(0, 3, 1, 2), padding=1)
+            x = torch.where(acc >= t(th)[None, :, None, None], 1.0, -1.0).double()
+        return x
+    skips = []
+    for _ in range(2):
+        x = dconv(x)
+        skips.append(x)
+        x = F.max_pool2d(x, 2)
+    x = dconv(x)
+    for j, l in enumerate((2, 1)):
+        wu, tu = case.up_convs[j]
+        acc = F.conv_transpose2d(x, t(wu).permute(3, 0, 1, 2), stride=2)
+        x = torch.where(acc >= t(tu)[None, :, None, None], 1.0, -1.0).double()
+        x = torch.cat([skips[l - 1], x], 1)
+        x = dconv(x)
+    assert np.array_equal(taps[-1][1], x.permute(0, 2, 3, 1).numpy().astype(np.int8))
+    shapes = {n: v.shape for n, v in taps}
+    assert shapes["up2"] == (1, 8, 16, 64) and shapes["cat2"] == (1, 8, 16, 128)
+    assert shapes["cat1"] == (1, 16, 32, 64)
