@@ -132,6 +132,32 @@ int mbu_conv3x3_masked_binary_fused(const uint32_t *act, int Ca, const uint32_t 
                                     const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool,
                                     void *stream);
 
+/* The 3x3 layer on the plain channel concatenation [a | b] of two tensors of the layer's own
+ * size, read in place (skip connection after a transposed up-sampling layer, Sec. 2.1);
+ * matrix path only.  a [N][H][W][Ca/32] with Ca % 32 == 0, b [N][H][W][ceil(Cb/32)],
+ * packed_w packed for (Cout, Ca + Cb); outputs as for mbu_conv3x3_masked_binary_fused. */
+int mbu_conv3x3_masked_binary_concat(const uint32_t *a, int Ca, const uint32_t *b, int Cb, int N,
+                                     int H, int W, const void *packed_w, int Cout,
+                                     const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool,
+                                     void *stream);
+
+/* Masked-binary transposed convolution, kernel 2x2, stride 2, with the threshold / sign /
+ * bit-pack epilogue: the decoder's up-sampling layer (Sec. 2.1; Sec. 3.2.2 notes it is
+ * performed like the convolution; the quantised network follows it with batch norm and a
+ * binary activation, Appendix A.1, which fold into the integer threshold as in Algorithm 1).
+ *   acc[n, 2y+dy, 2x+dx, o] = sum_c w[o,dy,dx,c] * a[n,y,x,c],  bit = (acc >= thresh[o]).
+ * Weights: device int8 [Cout][2][2][Cin] in {-1,0,+1}, packed once into a blob of
+ * mbu_packed_tconv_weights_bytes(Cout, Cin) bytes (layout private; matrix path only).
+ *   act       packed [N][H][W][ceil(Cin/32)]
+ *   out_bits  packed [N][2H][2W][Cout/32], or NULL
+ *   out_acc   int32 NHWC [N][2H][2W][Cout], or NULL (parity / debugging)
+ * Errors as for mbu_conv3x3_masked_binary. */
+int mbu_packed_tconv_weights_bytes(int Cout, int Cin, size_t *bytes);
+int mbu_pack_tconv_weights(const int8_t *w, int Cout, int Cin, void *packed, void *stream);
+int mbu_tconv2x2_masked_binary(const uint32_t *act, int N, int H, int W, int Cin,
+                               const void *packed_w, int Cout, const int32_t *thresh,
+                               uint32_t *out_bits, int32_t *out_acc, void *stream);
+
 /* 2x2 stride-2 max pooling on +-1 values = bitwise OR of the four packed words
  * (Sec. 3.2.2 lists pooling as trivial).  H and W must be even.
  *   in [N][H][W][Cw] -> out [N][H/2][W/2][Cw], Cw = ceil(C/32). */
@@ -187,9 +213,16 @@ typedef struct mbu_unet_desc {
                                        and pooling is folded into the layer before it
                                        where that layer runs the block kernel; such
                                        steps then take no time of their own.        */
+    const mbu_conv_layer *up_convs; /* NULL: the decoder up-samples 2x nearest neighbour.
+                                       Otherwise a host array of `levels` transposed 2x2
+                                       stride-2 layers, deepest first (packed_w from
+                                       mbu_pack_tconv_weights, cin = channels below,
+                                       cout = channels of the level): the decoder is
+                                       [transposed layer, concatenation skip-then-up, two
+                                       3x3 layers] per level, as in Sec. 2.1.          */
 } mbu_unet_desc;
 
-/* Number of kernel steps the forward pass runs (stem, each conv, pool, up-sample +
+/* Number of steps the forward pass consists of (stem, each conv, pool, [transposed layer,]
  * concatenation, classifier) for this descriptor. */
 int mbu_unet_num_steps(const mbu_unet_desc *d);
 

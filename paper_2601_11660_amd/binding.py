@@ -21,7 +21,8 @@ PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
 EXPORTS = [
     "mbu_last_error", "mbu_set_conv_path", "mbu_get_conv_path", "mbu_set_conv_tuning", "mbu_pack_act",
     "mbu_packed_weights_bytes", "mbu_pack_weights", "mbu_conv3x3_masked_binary",
-    "mbu_conv3x3_masked_binary_fused",
+    "mbu_conv3x3_masked_binary_fused", "mbu_conv3x3_masked_binary_concat",
+    "mbu_packed_tconv_weights_bytes", "mbu_pack_tconv_weights", "mbu_tconv2x2_masked_binary",
     "mbu_maxpool2x2_bits", "mbu_upsample2x_bits", "mbu_concat_bits", "mbu_unet_num_steps",
     "mbu_unet_step_info", "mbu_unet_step_launches", "mbu_unet_workspace_bytes", "mbu_unet_forward",
     "mbu_event_create", "mbu_event_destroy", "mbu_event_record", "mbu_event_elapsed_ms",
@@ -44,7 +45,8 @@ class UNetDesc(ctypes.Structure):
                 ("in_channels", ctypes.c_int), ("n_classes", ctypes.c_int),
                 ("stem_w", ctypes.c_void_p), ("convs", ctypes.POINTER(ConvLayer)),
                 ("cls_w", ctypes.c_void_p), ("cls_b", ctypes.c_void_p),
-                ("step_events", ctypes.POINTER(ctypes.c_void_p)), ("fuse", ctypes.c_int)]
+                ("step_events", ctypes.POINTER(ctypes.c_void_p)), ("fuse", ctypes.c_int),
+                ("up_convs", ctypes.POINTER(ConvLayer))]
 
 
 _lib = None
@@ -65,6 +67,10 @@ def lib() -> ctypes.CDLL:
         L.mbu_pack_weights.argtypes = [vp, ci, ci, vp, vp]
         L.mbu_conv3x3_masked_binary.argtypes = [vp, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp]
         L.mbu_conv3x3_masked_binary_fused.argtypes = [vp, ci, vp, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp]
+        L.mbu_conv3x3_masked_binary_concat.argtypes = [vp, ci, vp, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp]
+        L.mbu_packed_tconv_weights_bytes.argtypes = [ci, ci, ctypes.POINTER(ctypes.c_size_t)]
+        L.mbu_pack_tconv_weights.argtypes = [vp, ci, ci, vp, vp]
+        L.mbu_tconv2x2_masked_binary.argtypes = [vp, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp]
         L.mbu_maxpool2x2_bits.argtypes = [vp, ci, ci, ci, ci, vp, vp]
         L.mbu_upsample2x_bits.argtypes = [vp, ci, ci, ci, ci, vp, vp]
         L.mbu_concat_bits.argtypes = [vp, ci, vp, ci, ci, ci, ci, vp, vp]
@@ -185,6 +191,47 @@ def conv3x3_masked_binary_fused(act: torch.Tensor, ca: int, low: Optional[torch.
     return out_bits, out_pool
 
 
+def conv3x3_masked_binary_concat(a: torch.Tensor, ca: int, b: torch.Tensor, cb: int,
+                                 packed_w: torch.Tensor, cout: int, thresh: torch.Tensor,
+                                 want_pool: bool = False):
+    """mbu_conv3x3_masked_binary_concat -> (packed bits, pooled packed bits or None)."""
+    N, H, W, _ = a.shape
+    out_bits = torch.empty((N, H, W, cout // 32), dtype=torch.int32, device=a.device)
+    out_pool = (torch.empty((N, H // 2, W // 2, cout // 32), dtype=torch.int32, device=a.device)
+                if want_pool else None)
+    check(lib().mbu_conv3x3_masked_binary_concat(
+        _dev(a, (torch.int32,)), ca, _dev(b, (torch.int32,)), cb, N, H, W,
+        _dev(packed_w, (torch.uint8,)), cout, _dev(thresh, (torch.int32,)), out_bits.data_ptr(),
+        out_pool.data_ptr() if out_pool is not None else None, _stream()))
+    return out_bits, out_pool
+
+
+def pack_tconv_weights(w: torch.Tensor) -> torch.Tensor:
+    """mbu_pack_tconv_weights: device int8 [Cout,2,2,Cin] -> opaque blob (uint8 tensor)."""
+    cout, kh, kw, cin = w.shape
+    assert kh == 2 and kw == 2
+    n = ctypes.c_size_t(0)
+    check(lib().mbu_packed_tconv_weights_bytes(cout, cin, ctypes.byref(n)))
+    blob = torch.empty(n.value, dtype=torch.uint8, device=w.device)
+    check(lib().mbu_pack_tconv_weights(_dev(w, (torch.int8,)), cout, cin, blob.data_ptr(), _stream()))
+    return blob
+
+
+def tconv2x2_masked_binary(act: torch.Tensor, cin: int, packed_w: torch.Tensor, cout: int,
+                           thresh: torch.Tensor, want_bits: bool = True, want_acc: bool = False):
+    """mbu_tconv2x2_masked_binary -> (packed bits [N,2H,2W,Cout/32] or None, int32 acc or None)."""
+    N, H, W, _ = act.shape
+    out_bits = (torch.empty((N, 2 * H, 2 * W, cout // 32), dtype=torch.int32, device=act.device)
+                if want_bits else None)
+    out_acc = (torch.empty((N, 2 * H, 2 * W, cout), dtype=torch.int32, device=act.device)
+               if want_acc else None)
+    check(lib().mbu_tconv2x2_masked_binary(
+        _dev(act, (torch.int32,)), N, H, W, cin, _dev(packed_w, (torch.uint8,)), cout,
+        _dev(thresh, (torch.int32,)), out_bits.data_ptr() if out_bits is not None else None,
+        out_acc.data_ptr() if out_acc is not None else None, _stream()))
+    return out_bits, out_acc
+
+
 def maxpool2x2_bits(x: torch.Tensor, c: int) -> torch.Tensor:
     N, H, W, Cw = x.shape
     out = torch.empty((N, H // 2, W // 2, Cw), dtype=torch.int32, device=x.device)
@@ -242,7 +289,8 @@ class UNet:
     """Owner of the device tensors and the host descriptor for mbu_unet_forward."""
 
     def __init__(self, stem_w: torch.Tensor, convs: Sequence[Tuple[torch.Tensor, torch.Tensor]],
-                 cls_w: torch.Tensor, cls_b: torch.Tensor, levels: int = 4, fuse: bool = True):
+                 cls_w: torch.Tensor, cls_b: torch.Tensor, levels: int = 4, fuse: bool = True,
+                 up_convs: Optional[Sequence[Tuple[torch.Tensor, torch.Tensor]]] = None):
         """stem_w float32 [base,3,3,Ci]; convs: (w int8 OHWI, theta int32) device tensors in
         execution order; cls_w float32 [K,base]; cls_b float32 [K]."""
         self.levels = levels
@@ -265,11 +313,24 @@ class UNet:
             self._layers[i].packed_w = self.blobs[i].data_ptr()
             self._layers[i].thresh = self.thetas[i].data_ptr()
             self._layers[i].cin, self._layers[i].cout = self.shapes[i]
+        self._up_layers = None
+        self.up_blobs: List[torch.Tensor] = []
+        self.up_thetas: List[torch.Tensor] = []
+        if up_convs is not None:
+            # transposed decoder: (w int8 [Cout,2,2,Cin], theta int32) per level, deepest first
+            assert len(up_convs) == levels
+            self._up_layers = (ConvLayer * levels)()
+            for i, (w, th) in enumerate(up_convs):
+                self.up_blobs.append(pack_tconv_weights(w.contiguous()))
+                self.up_thetas.append(th.contiguous())
+                self._up_layers[i].packed_w = self.up_blobs[i].data_ptr()
+                self._up_layers[i].thresh = self.up_thetas[i].data_ptr()
+                self._up_layers[i].cin, self._up_layers[i].cout = w.shape[3], w.shape[0]
         self.desc = UNetDesc(levels=levels, base=self.base, in_channels=self.in_channels,
                              n_classes=self.n_classes, stem_w=self.stem_w.data_ptr(),
                              convs=self._layers, cls_w=self.cls_w.data_ptr(),
                              cls_b=self.cls_b.data_ptr(), step_events=None,
-                             fuse=1 if fuse else 0)
+                             fuse=1 if fuse else 0, up_convs=self._up_layers)
         self.num_steps = lib().mbu_unet_num_steps(ctypes.byref(self.desc))
         if self.num_steps < 0:
             check(self.num_steps)

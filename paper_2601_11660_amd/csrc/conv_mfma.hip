@@ -19,57 +19,9 @@
 // its (TH+2) x 34 pixel window of the current 64-channel step into LDS; the nine taps
 // then read shifted windows of that tile.
 #include "mbu_internal.h"
+#include "mfma_common.h"
 
 namespace mbu {
-
-typedef int v4i __attribute__((ext_vector_type(4)));
-typedef int v8i __attribute__((ext_vector_type(8)));
-typedef float v16f __attribute__((ext_vector_type(16)));
-
-__device__ inline v16f mfma_f4(v4i a, v4i b, v16f c)
-{
-    // The builtin takes 8-dword operands for every format; E2M1 (format code 4) uses the
-    // low 4 dwords.  Zero scale arguments select the unscaled instruction.
-    v8i a8 = {a.x, a.y, a.z, a.w, 0, 0, 0, 0};
-    v8i b8 = {b.x, b.y, b.z, b.w, 0, 0, 0, 0};
-    return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 4, 4, 0, 0, 0, 0);
-}
-
-// bits of one packed word -> 32 E2M1 codes of the NEGATED activation (bit 1 -> 0xA = -1.0,
-// bit 0 -> 0x2 = +1.0); nibble q of dword d carries channel 4q + d.
-__device__ inline uint4 expand_word(uint32_t w)
-{
-    uint4 r;
-    r.x = ((w << 3) & 0x88888888u) | 0x22222222u;
-    r.y = ((w << 2) & 0x88888888u) | 0x22222222u;
-    r.z = ((w << 1) & 0x88888888u) | 0x22222222u;
-    r.w = (w & 0x88888888u) | 0x22222222u;
-    return r;
-}
-
-// Completes the packed output words of one image row from the per-lane sign collections.
-// s0 / s1: 16 sign bits (1 = below threshold) of channels 16*half + i of the wave's first /
-// second 32-channel tile.  The two lane halves of a pixel are brought together with one
-// v_permlane32_swap (lo = value of the pixel's lower-half lane, hi = of its upper-half lane,
-// in every lane) and one byte permute picks word 0 (channels 0..31) in the lower half and
-// word 1 (channels 32..63) in the upper half.  psel = 0x05040100 for half 0, 0x07060302 for
-// half 1.
-__device__ __forceinline__ uint32_t finish_word64(uint32_t s0, uint32_t s1, uint32_t psel)
-{
-    const uint32_t mine = (~s0 & 0xffffu) | (~s1 << 16);
-    const auto sw = __builtin_amdgcn_permlane32_swap(mine, mine, false, false);
-    // sw[0] = lower-half lane's value, sw[1] = upper-half lane's value
-    return __builtin_amdgcn_perm(sw[1], sw[0], psel);
-}
-
-// Same for a wave that owns a single 32-channel tile: the word is (lo & 0xffff) | (hi << 16)
-// in both halves.
-__device__ __forceinline__ uint32_t finish_word32(uint32_t s0)
-{
-    const uint32_t mine = ~s0 & 0xffffu;
-    const auto sw = __builtin_amdgcn_permlane32_swap(mine, mine, false, false);
-    return sw[0] | (sw[1] << 16);
-}
 
 // Position of a pixel tile, advanced by a fixed stride without divisions: the stride is
 // split on the host into (dx, dy, dn) = stride mod tiles_x, (stride / tiles_x) mod tiles_y,
@@ -387,17 +339,18 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
 //
 // Two fusions of the decoder / encoder glue (Sec. 2.1) live here, because they only touch
 // the staging and the epilogue:
-//  TWO_SRC  the input is the channel concatenation [act | 2x-up-sampled low]: word k of a
-//           halo pixel (y, x) comes from act[y][x][k] for k < Cwa and from
-//           low[y/2][x/2][k - Cwa] otherwise - the skip concatenation and the nearest
-//           up-sampling are never materialised;
+//  TWO_SRC  the input is the channel concatenation [act | low]: word k of a halo pixel (y, x)
+//           comes from act[y][x][k] for k < Cwa and from the second tensor otherwise - at
+//           low[y/2][x/2][k - Cwa] when it is half size (nearest up-sampling, low_shift = 1)
+//           or at low[y][x][k - Cwa] (low_shift = 0); neither the skip concatenation nor
+//           the up-sampling is ever materialised;
 //  POOL     besides its own output the layer writes the 2x2 OR-pooled output (max pooling
 //           of +-1 values): rows pair up inside a lane, columns with the neighbouring lane.
 template <int RW, int WM, int WN, bool CW_EVEN, bool TWO_SRC, bool POOL>
 __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
     const uint32_t *__restrict__ act, const uint32_t *__restrict__ low, int N, int H, int W,
-    int Cwa, int Cwb, int ksteps, const uint4 *__restrict__ wfrag, int Cout, int tiles64,
-    int ptiles, TileStep tstep, const int32_t *__restrict__ thresh, uint32_t *__restrict__ out_bits,
+    int Cwa, int Cwb, int low_shift, int ksteps, const uint4 *__restrict__ wfrag, int Cout,
+    int tiles64, int ptiles, TileStep tstep, const int32_t *__restrict__ thresh, uint32_t *__restrict__ out_bits,
     uint32_t *__restrict__ out_pool)
 {
     static_assert(WM * WN == 4, "four waves per block");
@@ -452,7 +405,9 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
             const bool in = yy >= 0 && yy < H && xx >= 0 && xx < W;
             const int yc = min(max(yy, 0), H - 1), xc = min(max(xx, 0), W - 1);
             offa[j] = (uint32_t)((((size_t)n * H + yc) * W + xc) * Cwa) | (in ? 0x80000000u : 0u);
-            if (TWO_SRC) offb[j] = (uint32_t)((((size_t)n * Hl + (yc >> 1)) * Wl + (xc >> 1)) * Cwb);
+            if (TWO_SRC)   // second source: same pixel, or pixel (y/2, x/2) of a half-size tensor
+                offb[j] = (uint32_t)((((size_t)n * (H >> low_shift) + (yc >> low_shift)) * (W >> low_shift) +
+                                      (xc >> low_shift)) * Cwb);
         }
     };
     // word k (wave-uniform) of staged pixel j of the virtual input
@@ -741,6 +696,7 @@ static int launch_bits_t(const uint32_t *act, int N, int H, int W, const BlobLay
 struct ConvIO {
     const uint32_t *act;
     const uint32_t *low;     // NULL = single source
+    int low_shift;           // 1: low is half size (read up-sampled), 0: same size as act
     int cwa, cwb;            // words per pixel of act / low
     uint32_t *out_bits;      // may be NULL when out_pool is set
     uint32_t *out_pool;      // NULL = no pooled output
@@ -764,11 +720,11 @@ static int launch_block_t(const ConvIO &io, int N, int H, int W, const BlobLayou
     const bool even = (io.cwa % 2 == 0) && (!TWO_SRC || io.cwb % 2 == 0);
     if (even)
         MBU_LAUNCH((conv_mfma_block_kernel<RW, WM, WN, true, TWO_SRC, POOL>), grid, dim3(256), 0, s,
-                   io.act, io.low, N, H, W, io.cwa, io.cwb, L.ksteps, wfrag, L.cout, tiles64,
+                   io.act, io.low, N, H, W, io.cwa, io.cwb, io.low_shift, L.ksteps, wfrag, L.cout, tiles64,
                    (int)tiles, tstep, thresh, io.out_bits, io.out_pool);
     else
         MBU_LAUNCH((conv_mfma_block_kernel<RW, WM, WN, false, TWO_SRC, POOL>), grid, dim3(256), 0, s,
-                   io.act, io.low, N, H, W, io.cwa, io.cwb, L.ksteps, wfrag, L.cout, tiles64,
+                   io.act, io.low, N, H, W, io.cwa, io.cwb, io.low_shift, L.ksteps, wfrag, L.cout, tiles64,
                    (int)tiles, tstep, thresh, io.out_bits, io.out_pool);
     return check_launch("conv_mfma_block");
 }
@@ -828,22 +784,31 @@ int launch_conv_mfma(const uint32_t *act, int N, int H, int W, const BlobLayout 
     const int mode = g_tune_rw;   // 0 = automatic; see mbu_set_conv_tuning
     const bool want_block = mode == 1 || (mode == 0 && L.ksteps > 1);
     if (want_block) {
-        ConvIO io{act, nullptr, L.cin_words, 0, out_bits, nullptr};
+        ConvIO io{act, nullptr, 0, L.cin_words, 0, out_bits, nullptr};
         return launch_block_auto(io, N, H, W, L, wfrag, thresh, s);
     }
     if (mode == 6) return launch_bits<6, 1>(act, N, H, W, L, wfrag, thresh, out_bits, s);
     return launch_bits<3, 2>(act, N, H, W, L, wfrag, thresh, out_bits, s);
 }
 
-// Fused form: input = [act (Ca channels) | 2x-up-sampled low (Clow channels)] when low is
-// given, plus an optional 2x2-pooled second output.  Always the block-cooperative kernel.
+// Fused form: input = [act (Ca channels) | low (Clow channels)] when low is given - read
+// up-sampled 2x when low_shift = 1 - plus an optional 2x2-pooled second output.  Always the
+// block-cooperative kernel.
+int launch_conv_mfma_two(const uint32_t *act, int Ca, const uint32_t *low, int Clow, int low_shift,
+                         int N, int H, int W, const BlobLayout &L, const void *blob,
+                         const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, hipStream_t s)
+{
+    const uint4 *wfrag = (const uint4 *)((const uint8_t *)blob + L.off_f4);
+    ConvIO io{act, low, low ? low_shift : 0, ceil_div(Ca, 32), low ? ceil_div(Clow, 32) : 0,
+              out_bits, out_pool};
+    return launch_block_auto(io, N, H, W, L, wfrag, thresh, s);
+}
+
 int launch_conv_mfma_fused(const uint32_t *act, int Ca, const uint32_t *low, int Clow, int N, int H,
                            int W, const BlobLayout &L, const void *blob, const int32_t *thresh,
                            uint32_t *out_bits, uint32_t *out_pool, hipStream_t s)
 {
-    const uint4 *wfrag = (const uint4 *)((const uint8_t *)blob + L.off_f4);
-    ConvIO io{act, low, ceil_div(Ca, 32), low ? ceil_div(Clow, 32) : 0, out_bits, out_pool};
-    return launch_block_auto(io, N, H, W, L, wfrag, thresh, s);
+    return launch_conv_mfma_two(act, Ca, low, Clow, 1, N, H, W, L, blob, thresh, out_bits, out_pool, s);
 }
 
 }  // namespace mbu

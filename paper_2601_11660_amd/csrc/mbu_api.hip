@@ -62,10 +62,11 @@ static int check_dims4(const char *fn, int N, int H, int W, int C)
 
 // ------------------------------------------------------------------ network plan
 struct Step {
-    enum Kind { STEM, CONV, POOL, UPCAT, CLS } kind;
+    enum Kind { STEM, CONV, POOL, UPCAT, TCONV, CAT, CLS } kind;
     const char *name;
     int conv;        // index into d->convs for CONV
-    int in, in2;     // producing steps of the inputs (-1 = image); in2 = low-res input of UPCAT
+    int in, in2;     // producing steps of the inputs (-1 = image); in2 = second input of UPCAT / CAT
+                     // (conv = index into d->up_convs for TCONV)
     int h, w, c;     // output shape
     size_t off;      // workspace offset of the output
 };
@@ -75,6 +76,7 @@ static const char *kConvNames[] = {"enc1a", "enc1b", "enc2a", "enc2b", "enc3a", 
 static const char *kDecNames[] = {"dec1a", "dec1b", "dec2a", "dec2b", "dec3a", "dec3b", "dec4a",
                                   "dec4b", "dec5a", "dec5b", "dec6a", "dec6b"};
 static const char *kPoolNames[] = {"pool1", "pool2", "pool3", "pool4", "pool5", "pool6"};
+static const char *kUpNames[] = {"up1", "up2", "up3", "up4", "up5", "up6"};
 static const char *kCatNames[] = {"cat1", "cat2", "cat3", "cat4", "cat5", "cat6"};
 
 static int build_plan(const mbu_unet_desc *d, int N, int H, int W, std::vector<Step> &steps,
@@ -128,7 +130,16 @@ static int build_plan(const mbu_unet_desc *d, int N, int H, int W, std::vector<S
     for (int l = d->levels - 1; l >= 0; --l) {
         h *= 2; w *= 2;
         int sk = skips[l];
-        cur = push(Step::UPCAT, kCatNames[l], -1, sk, cur, h, w, steps[sk].c + steps[cur].c);
+        if (d->up_convs) {
+            // transposed decoder: masked transposed layer 2x2 stride 2, then plain concatenation
+            const mbu_conv_layer &U = d->up_convs[d->levels - 1 - l];
+            if (U.cin != steps[cur].c || U.cout <= 0 || U.cout % 32)
+                return fail(MBU_ERR_SHAPE, "%s: transposed layer %d has inconsistent channels", fn, d->levels - 1 - l);
+            cur = push(Step::TCONV, kUpNames[l], d->levels - 1 - l, cur, -1, h, w, U.cout);
+            cur = push(Step::CAT, kCatNames[l], -1, sk, cur, h, w, steps[sk].c + steps[cur].c);
+        } else {
+            cur = push(Step::UPCAT, kCatNames[l], -1, sk, cur, h, w, steps[sk].c + steps[cur].c);
+        }
         for (int j = 0; j < 2; ++j) {
             cur = conv(kDecNames[2 * l + j], cur, h, w, steps[cur].c);
             if (cur < 0) return fail(MBU_ERR_SHAPE, "%s: conv layer %d has inconsistent channels", fn, -1 - cur);
@@ -147,7 +158,7 @@ static bool step_launches(const mbu_unet_desc *d, const std::vector<Step> &steps
     const bool fuse = d->fuse != 0 && g_conv_path != MBU_PATH_VALU;
     if (!fuse) return true;
     const Step &st = steps[i];
-    if (st.kind == Step::UPCAT) return false;
+    if (st.kind == Step::UPCAT || st.kind == Step::CAT) return false;
     if (st.kind == Step::POOL) {
         const Step &in = steps[st.in];
         return !(in.kind == Step::CONV &&
@@ -285,6 +296,81 @@ int mbu_conv3x3_masked_binary_fused(const uint32_t *act, int Ca, const uint32_t 
                                   thresh, out_bits, out_pool, (hipStream_t)stream);
 }
 
+int mbu_conv3x3_masked_binary_concat(const uint32_t *a, int Ca, const uint32_t *b, int Cb, int N,
+                                     int H, int W, const void *packed_w, int Cout,
+                                     const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool,
+                                     void *stream)
+{
+    const char *fn = "mbu_conv3x3_masked_binary_concat";
+    MBU_REQ_PTR(fn, a);
+    MBU_REQ_PTR(fn, b);
+    MBU_REQ_PTR(fn, packed_w);
+    MBU_REQ_PTR(fn, thresh);
+    if (!out_bits && !out_pool) return fail(MBU_ERR_NULL, "%s: out_bits and out_pool are both NULL", fn);
+    if (out_bits && !aligned16(out_bits)) return fail(MBU_ERR_ALIGN, "%s: out_bits is not 16-byte aligned", fn);
+    if (out_pool && !aligned16(out_pool)) return fail(MBU_ERR_ALIGN, "%s: out_pool is not 16-byte aligned", fn);
+    if ((const void *)out_bits == (const void *)a || (const void *)out_bits == (const void *)b ||
+        (const void *)out_pool == (const void *)a || (const void *)out_pool == (const void *)b)
+        return fail(MBU_ERR_ARG, "%s: outputs must not alias an input", fn);
+    int rc = check_dims4(fn, N, H, W, Ca);
+    if (rc) return rc;
+    if (Cb <= 0) return fail(MBU_ERR_SHAPE, "%s: Cb must be positive, got %d", fn, Cb);
+    if (Ca % 32) return fail(MBU_ERR_SHAPE, "%s: Ca must be a multiple of 32, got %d", fn, Ca);
+    if (out_pool && ((H & 1) || (W & 1)))
+        return fail(MBU_ERR_SHAPE, "%s: H and W must be even with out_pool (H=%d W=%d)", fn, H, W);
+    if (Cout <= 0 || Cout % 32) return fail(MBU_ERR_SHAPE, "%s: Cout must be a positive multiple of 32, got %d", fn, Cout);
+    if (Cout > 65536 || Ca + Cb > 65536) return fail(MBU_ERR_SHAPE, "%s: channel count too large", fn);
+    rc = check_dims4(fn, N, H, W, Cout);
+    if (rc) return rc;
+    rc = check_dims4(fn, N, H, W, Ca + Cb);
+    if (rc) return rc;
+    return launch_conv_mfma_two(a, Ca, b, Cb, 0, N, H, W, blob_layout(Cout, Ca + Cb), packed_w, thresh,
+                                out_bits, out_pool, (hipStream_t)stream);
+}
+
+int mbu_packed_tconv_weights_bytes(int Cout, int Cin, size_t *bytes)
+{
+    const char *fn = "mbu_packed_tconv_weights_bytes";
+    if (!bytes) return fail(MBU_ERR_NULL, "%s: bytes is NULL", fn);
+    if (Cout <= 0 || Cin <= 0 || Cout % 32) return fail(MBU_ERR_SHAPE, "%s: need Cin > 0 and Cout a positive multiple of 32 (Cout=%d Cin=%d)", fn, Cout, Cin);
+    if (Cout > 65536 || Cin > 65536) return fail(MBU_ERR_SHAPE, "%s: channel count too large", fn);
+    *bytes = tconv_layout(Cout, Cin).total;
+    return MBU_OK;
+}
+
+int mbu_pack_tconv_weights(const int8_t *w, int Cout, int Cin, void *packed, void *stream)
+{
+    const char *fn = "mbu_pack_tconv_weights";
+    MBU_REQ_PTR(fn, w);
+    MBU_REQ_PTR(fn, packed);
+    size_t bytes;
+    int rc = mbu_packed_tconv_weights_bytes(Cout, Cin, &bytes);
+    if (rc) return rc;
+    return launch_pack_tconv(w, tconv_layout(Cout, Cin), packed, (hipStream_t)stream);
+}
+
+int mbu_tconv2x2_masked_binary(const uint32_t *act, int N, int H, int W, int Cin,
+                               const void *packed_w, int Cout, const int32_t *thresh,
+                               uint32_t *out_bits, int32_t *out_acc, void *stream)
+{
+    const char *fn = "mbu_tconv2x2_masked_binary";
+    MBU_REQ_PTR(fn, act);
+    MBU_REQ_PTR(fn, packed_w);
+    MBU_REQ_PTR(fn, thresh);
+    if (!out_bits && !out_acc) return fail(MBU_ERR_NULL, "%s: out_bits and out_acc are both NULL", fn);
+    if (out_bits && !aligned16(out_bits)) return fail(MBU_ERR_ALIGN, "%s: out_bits is not 16-byte aligned", fn);
+    if (out_acc && !aligned16(out_acc)) return fail(MBU_ERR_ALIGN, "%s: out_acc is not 16-byte aligned", fn);
+    if ((const void *)out_bits == (const void *)act || (const void *)out_acc == (const void *)act)
+        return fail(MBU_ERR_ARG, "%s: outputs must not alias the input", fn);
+    int rc = check_dims4(fn, N, H, W, Cin);
+    if (rc) return rc;
+    if (Cout <= 0 || Cout % 32) return fail(MBU_ERR_SHAPE, "%s: Cout must be a positive multiple of 32, got %d", fn, Cout);
+    if (Cout > 65536 || Cin > 65536) return fail(MBU_ERR_SHAPE, "%s: channel count too large", fn);
+    if ((double)N * H * W * 4.0 * (Cout / 32) > 4.0e9) return fail(MBU_ERR_SHAPE, "%s: output too large", fn);
+    return launch_tconv_mfma(act, N, H, W, tconv_layout(Cout, Cin), packed_w, thresh, out_bits, out_acc,
+                             (hipStream_t)stream);
+}
+
 int mbu_maxpool2x2_bits(const uint32_t *in, int N, int H, int W, int C, uint32_t *out, void *stream)
 {
     const char *fn = "mbu_maxpool2x2_bits";
@@ -326,7 +412,7 @@ int mbu_unet_num_steps(const mbu_unet_desc *d)
 {
     if (!d) return fail(MBU_ERR_NULL, "mbu_unet_num_steps: descriptor is NULL");
     if (d->levels < 1 || d->levels > 6) return fail(MBU_ERR_SHAPE, "mbu_unet_num_steps: levels must be 1..6");
-    return 1 + 3 * d->levels + 2 + 3 * d->levels + 1;
+    return 1 + 3 * d->levels + 2 + (d->up_convs ? 4 : 3) * d->levels + 1;
 }
 
 int mbu_unet_step_info(const mbu_unet_desc *d, int N, int H, int W, int step, const char **name,
@@ -382,6 +468,10 @@ int mbu_unet_forward(const mbu_unet_desc *d, const float *image_nchw, int N, int
         MBU_REQ_PTR(fn, d->convs[i].packed_w);
         MBU_REQ_PTR(fn, d->convs[i].thresh);
     }
+    for (int i = 0; d->up_convs && i < d->levels; ++i) {
+        MBU_REQ_PTR(fn, d->up_convs[i].packed_w);
+        MBU_REQ_PTR(fn, d->up_convs[i].thresh);
+    }
     hipStream_t s = (hipStream_t)stream;
     uint8_t *ws = (uint8_t *)workspace;
     auto buf = [&](int step) { return (uint32_t *)(ws + steps[step].off); };
@@ -399,7 +489,7 @@ int mbu_unet_forward(const mbu_unet_desc *d, const float *image_nchw, int N, int
             const mbu_conv_layer &L = d->convs[st.conv];
             const Step &in = steps[st.in];
             // fused forms: read [skip | up(low)] in place; write the pooled output as well
-            const bool from_cat = fuse && in.kind == Step::UPCAT;
+            const bool from_cat = fuse && (in.kind == Step::UPCAT || in.kind == Step::CAT);
             const bool next_pool = fuse && i + 1 < steps.size() && steps[i + 1].kind == Step::POOL &&
                                    blob_layout(L.cout, L.cin).ksteps > 1;
             if (from_cat || next_pool) {
@@ -407,9 +497,9 @@ int mbu_unet_forward(const mbu_unet_desc *d, const float *image_nchw, int N, int
                 const int ca = from_cat ? steps[in.in].c : L.cin;
                 const uint32_t *lo = from_cat ? buf(in.in2) : nullptr;
                 const int clo = from_cat ? steps[in.in2].c : 0;
-                rc = launch_conv_mfma_fused(a, ca, lo, clo, N, st.h, st.w, blob_layout(L.cout, L.cin),
-                                            L.packed_w, L.thresh, buf((int)i),
-                                            next_pool ? buf((int)i + 1) : nullptr, s);
+                rc = launch_conv_mfma_two(a, ca, lo, clo, in.kind == Step::UPCAT ? 1 : 0, N, st.h, st.w,
+                                          blob_layout(L.cout, L.cin), L.packed_w, L.thresh,
+                                          buf((int)i), next_pool ? buf((int)i + 1) : nullptr, s);
             } else {
                 rc = run_conv(buf(st.in), N, st.h, st.w, L.cin, L.packed_w, L.cout, L.thresh,
                               buf((int)i), nullptr, s);
@@ -428,6 +518,17 @@ int mbu_unet_forward(const mbu_unet_desc *d, const float *image_nchw, int N, int
             if (!fuse)
                 rc = launch_upcat(buf(st.in), steps[st.in].c / 32, buf(st.in2), steps[st.in2].c / 32,
                                   N, st.h, st.w, buf((int)i), s);
+            break;
+        case Step::TCONV: {
+            const mbu_conv_layer &U = d->up_convs[st.conv];
+            rc = launch_tconv_mfma(buf(st.in), N, st.h / 2, st.w / 2, tconv_layout(U.cout, U.cin),
+                                   U.packed_w, U.thresh, buf((int)i), nullptr, s);
+            break;
+        }
+        case Step::CAT:
+            if (!fuse)
+                rc = launch_concat(buf(st.in), steps[st.in].c / 32, buf(st.in2), steps[st.in2].c / 32,
+                                   (long)N * st.h * st.w, buf((int)i), s);
             break;
         case Step::CLS:
             rc = launch_classifier(buf(st.in), N, st.h, st.w, steps[st.in].c, d->cls_w, d->cls_b,

@@ -40,6 +40,14 @@ struct BlobLayout {
 };
 BlobLayout blob_layout(int cout, int cin);
 
+// ---- packed blob of the transposed 2x2 stride-2 layer: 4-bit codes only,
+// uint4 [cout_pad64/64][ksteps][4 positions][2][64 lanes] after 256 bytes of header room
+struct TconvLayout {
+    int cout, cin, cin_words, cout_pad64, ksteps;
+    size_t off_f4, total;
+};
+TconvLayout tconv_layout(int cout, int cin);
+
 // Row order of output channels inside one 32-channel matrix tile: tile row i holds
 // output channel tile_row_to_channel(i) of the tile, chosen so that the sixteen
 // accumulator registers of a lane map to sixteen consecutive output-channel bits.
@@ -68,6 +76,15 @@ int launch_conv_mfma(const uint32_t *act, int N, int H, int W, const BlobLayout 
 int launch_conv_mfma_fused(const uint32_t *act, int Ca, const uint32_t *low, int Clow, int N, int H,
                            int W, const BlobLayout &L, const void *blob, const int32_t *thresh,
                            uint32_t *out_bits, uint32_t *out_pool, hipStream_t s);
+// low_shift = 1: `low` is half resolution and is read up-sampled; 0: `low` has the layer's own
+// resolution (plain channel concatenation of two tensors)
+int launch_conv_mfma_two(const uint32_t *act, int Ca, const uint32_t *low, int Clow, int low_shift,
+                         int N, int H, int W, const BlobLayout &L, const void *blob,
+                         const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, hipStream_t s);
+int launch_pack_tconv(const int8_t *w, const TconvLayout &L, void *blob, hipStream_t s);
+int launch_tconv_mfma(const uint32_t *act, int N, int H, int W, const TconvLayout &L,
+                      const void *blob, const int32_t *thresh, uint32_t *out_bits, int32_t *out_acc,
+                      hipStream_t s);
 int launch_maxpool(const uint32_t *in, int N, int H, int W, int Cw, uint32_t *out, hipStream_t s);
 int launch_upsample(const uint32_t *in, int N, int H, int W, int Cw, uint32_t *out, hipStream_t s);
 int launch_concat(const uint32_t *a, int Caw, const uint32_t *b, int Cbw, long pixels,

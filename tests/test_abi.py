@@ -20,7 +20,7 @@ def header_symbols():
 def test_library_exports_every_declared_symbol():
     L = B.lib()
     syms = header_symbols()
-    assert len(syms) >= 21
+    assert len(syms) >= 25
     for s in syms:
         assert hasattr(L, s), s
     assert sorted(B.EXPORTS) == syms
@@ -66,6 +66,51 @@ def test_fused_conv_argument_validation():
     assert f(a, 64, None, 0, 1, 8, 9, w, 64, t, o, p, None) == B.MBU_ERR_SHAPE
     assert f(a, 64, lo, 128, 1, 8, 8, w, 64, t, lo, None, None) == B.MBU_ERR_ARG
     assert f(a, 64, lo + 4, 128, 1, 8, 8, w, 64, t, o, None, None) == B.MBU_ERR_ALIGN
+
+
+def test_tconv_and_concat_argument_validation():
+    L = B.lib()
+    a, b, w, t, o = 0x10000, 0x20000, 0x30000, 0x40000, 0x50000
+    f = L.mbu_tconv2x2_masked_binary
+    assert f(a, 1, 4, 4, 64, w, 64, t, None, None, None) == B.MBU_ERR_NULL
+    assert f(a, 1, 4, 4, 64, w, 48, t, o, None, None) == B.MBU_ERR_SHAPE
+    assert f(a, 1, 0, 4, 64, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
+    assert f(a, 1, 4, 4, 64, w, 64, t, a, None, None) == B.MBU_ERR_ARG
+    assert f(a, 1, 4, 4, 64, w + 2, 64, t, o, None, None) == B.MBU_ERR_ALIGN
+    n = ctypes.c_size_t()
+    assert L.mbu_packed_tconv_weights_bytes(64, 128, ctypes.byref(n)) == 0
+    assert n.value >= 4 * 64 * 128 // 2
+    assert L.mbu_packed_tconv_weights_bytes(40, 128, ctypes.byref(n)) == B.MBU_ERR_SHAPE
+    assert L.mbu_pack_tconv_weights(None, 64, 64, o, None) == B.MBU_ERR_NULL
+    g = L.mbu_conv3x3_masked_binary_concat
+    assert g(a, 64, None, 64, 1, 8, 8, w, 64, t, o, None, None) == B.MBU_ERR_NULL
+    assert g(a, 48, b, 64, 1, 8, 8, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
+    assert g(a, 64, b, 64, 1, 8, 8, w, 64, t, b, None, None) == B.MBU_ERR_ARG
+    assert g(a, 64, b, 0, 1, 8, 8, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
+
+
+def test_unet_plan_with_transposed_decoder():
+    from paper_2601_11660_amd import synth
+    plan = synth.unet_channel_plan(64, 4, transposed=True)
+    d = _desc(convs=[(ci, co) for _, ci, co, _ in plan])
+    ups = (B.ConvLayer * 4)()
+    for i, c in enumerate((512, 256, 128, 64)):
+        ups[i].cin, ups[i].cout = 2 * c, c
+        ups[i].packed_w, ups[i].thresh = 0x10000, 0x20000
+    d.up_convs = ups
+    L = B.lib()
+    assert L.mbu_unet_num_steps(ctypes.byref(d)) == 32
+    n = ctypes.c_size_t()
+    assert L.mbu_unet_workspace_bytes(ctypes.byref(d), 1, 64, 128, ctypes.byref(n)) == 0
+    names = []
+    for s in range(32):
+        name = ctypes.c_char_p()
+        assert L.mbu_unet_step_info(ctypes.byref(d), 1, 64, 128, s, ctypes.byref(name), None, None,
+                                    None, None) == 0
+        names.append(name.value.decode())
+    assert names[15:19] == ["up4", "cat4", "dec4a", "dec4b"]
+    ups[1].cin = 300
+    assert L.mbu_unet_workspace_bytes(ctypes.byref(d), 1, 64, 128, ctypes.byref(n)) == B.MBU_ERR_SHAPE
 
 
 def test_packed_weight_size_and_path_switch():

@@ -186,6 +186,75 @@ def test_fused_concat_upsample_pool(shape):
     assert np.array_equal(host_u32(p1), bitref.pack_pm1(O.maxpool2x2(o1)))
 
 
+TCONV_SHAPES = [
+    # N, H, W, Cin, Cout
+    (1, 8, 32, 128, 64),
+    (2, 5, 37, 96, 32),       # ragged pixel groups, odd word count, half channel tile
+    (1, 3, 70, 64, 128),
+    (1, 1, 1, 32, 64),
+    (1, 6, 9, 40, 96),        # Cin not a multiple of 32
+    (1, 16, 16, 1024, 512),
+]
+
+
+@pytest.mark.parametrize("shape", TCONV_SHAPES)
+def test_tconv_matches_oracle_elementwise(shape):
+    N, H, W, Cin, Cout = shape
+    say(f"tconv N={N} H={H} W={W} Cin={Cin} Cout={Cout}")
+    rng = np.random.default_rng(Cin + Cout)
+    a = synth.pm1_bits(rng, (N, H, W, Cin))
+    w = synth.ternary_tconv_weights(10, 0, 0, Cout, Cin, 0.6)
+    th = synth.thresholds(10, 0, 0, Cout, max(1, Cin // 8))
+    acc_ref, out_ref = O.masked_binary_tconv_layer(a, w, th)
+    act, blob, thd = B.pack_act(dev(a)), B.pack_tconv_weights(dev(w)), dev(th)
+    bits, _ = B.tconv2x2_masked_binary(act, Cin, blob, Cout, thd, True, False)
+    bits2, acc = B.tconv2x2_masked_binary(act, Cin, blob, Cout, thd, True, True)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(acc), acc_ref)
+    assert np.array_equal(host_u32(bits), bitref.pack_pm1(out_ref))
+    assert np.array_equal(host_u32(bits2), bitref.pack_pm1(out_ref))
+    # ties and a zero mask
+    th2 = acc_ref[0, 0, 0].astype(np.int32).copy()
+    b3, _ = B.tconv2x2_masked_binary(act, Cin, blob, Cout, dev(th2), True, False)
+    assert np.array_equal(host_u32(b3), bitref.pack_pm1(O.threshold(acc_ref, th2)))
+    bz, az = B.tconv2x2_masked_binary(act, Cin, B.pack_tconv_weights(dev(np.zeros_like(w))), Cout,
+                                      thd, True, True)
+    assert not host(az).any()
+
+
+@pytest.mark.parametrize("shape", [(1, 12, 40, 64, 64, 64), (2, 9, 33, 96, 160, 96),
+                                   (1, 8, 34, 32, 40, 64)])
+def test_conv_on_plain_concatenation(shape):
+    N, H, W, Ca, Cb, Cout = shape
+    say(f"conv concat N={N} H={H} W={W} Ca={Ca} Cb={Cb} Cout={Cout}")
+    rng = np.random.default_rng(Ca * 7 + Cb)
+    a = synth.pm1_bits(rng, (N, H, W, Ca))
+    b = synth.pm1_bits(rng, (N, H, W, Cb))
+    w = synth.ternary_weights(11, 0, 0, Cout, Ca + Cb, 0.6)
+    th = synth.thresholds(11, 0, 0, Cout, (9 * (Ca + Cb)) // 16)
+    _, out_ref = O.masked_binary_layer(O.concat(a, b), w, th)
+    bits, _ = B.conv3x3_masked_binary_concat(B.pack_act(dev(a)), Ca, B.pack_act(dev(b)), Cb,
+                                             B.pack_weights(dev(w)), Cout, dev(th))
+    torch.cuda.synchronize()
+    assert np.array_equal(host_u32(bits), bitref.pack_pm1(out_ref))
+
+
+@pytest.mark.parametrize("fuse", [True, False])
+def test_unet_transposed_decoder_small_all_layers(fuse):
+    """The paper-shaped decoder: masked transposed 2x2 layers instead of nearest up-sampling."""
+    say(f"unet transposed small fuse={fuse}")
+    case = synth.unet_case(6, 0, 2, 32, 64, base=32, levels=2, n_classes=5, transposed=True)
+    compare_unet_all_taps(case, 2, 32, 64, fuse)
+    case = synth.unet_case(6, 1, 1, 64, 96, base=64, levels=3, n_classes=19, transposed=True)
+    compare_unet_all_taps(case, 1, 64, 96, fuse)
+
+
+def test_unet_transposed_decoder_1024x2048_by_induction():
+    say("unet transposed 1024x2048 induction")
+    case = synth.unet_case(6, 2, 1, 1024, 2048, keep=0.6, transposed=True)
+    check_unet_by_induction(case, 1, 1024, 2048)
+
+
 def test_paths_agree_and_are_deterministic():
     say("conv paths agree")
     case = synth.conv_case(7, 3, 2, 40, 72, 128, 128, 0.5)
@@ -236,8 +305,9 @@ def test_pool_upsample_concat(C):
 
 # ------------------------------------------------------------------------ network
 def build_unet(case, fuse=True):
+    ups = None if case.up_convs is None else [(dev(w), dev(t)) for w, t in case.up_convs]
     return B.UNet(dev(case.stem_w), [(dev(w), dev(t)) for w, t in case.convs],
-                  dev(case.cls_w), dev(case.cls_b), levels=case.levels, fuse=fuse)
+                  dev(case.cls_w), dev(case.cls_b), levels=case.levels, fuse=fuse, up_convs=ups)
 
 
 TAP_OF_STEP = {"stem": "stem", "classifier": None}
@@ -249,7 +319,7 @@ def compare_unet_all_taps(case, N, H, W, fuse=True):
     logits = net.forward(dev(case.image))
     torch.cuda.synchronize()
     ref_logits, taps = O.unet_forward(case.image, case.stem_w, case.convs, case.cls_w,
-                                      case.cls_b, levels=case.levels)
+                                      case.cls_b, levels=case.levels, up_convs=case.up_convs)
     taps = dict(taps)
     rename = {"mida": "mida", "midb": "midb"}
     for s in range(net.num_steps - 1):
@@ -321,10 +391,21 @@ def check_unet_by_induction(case, N, H, W, rows_per_layer=3, fuse=True):
             a = bitref.unpack_pm1(x[:1, :4], c)
             assert np.array_equal(bitref.pack_pm1(O.maxpool2x2(a)), outs[name][:1, :2]), name
             assert np.array_equal(exp, outs[name]), name
+        elif name.startswith("up"):
+            # transposed layer: sampled input rows -> two output rows each
+            j = case.levels - int(name[2:])
+            wu, tu = case.up_convs[j]
+            xin = outs[prev]
+            hh = xin.shape[1]
+            for n in sorted({0, N - 1}):
+                for r0 in sorted({0, hh // 2, hh - 1}):
+                    a = bitref.unpack_pm1(xin[n:n + 1, r0:r0 + 1], wu.shape[3])
+                    _, o = O.masked_binary_tconv_layer(a, wu, tu)
+                    assert np.array_equal(outs[name][n:n + 1, 2 * r0:2 * r0 + 2], bitref.pack_pm1(o)), name
         elif name.startswith("cat"):
             l = int(name[3:])
             sk, lo = outs[skips[l]], outs[prev]
-            up = np.repeat(np.repeat(lo, 2, axis=1), 2, axis=2)
+            up = lo if case.up_convs is not None else np.repeat(np.repeat(lo, 2, axis=1), 2, axis=2)
             cat = np.concatenate([sk, up], -1)
             if fuse:
                 outs[name] = cat      # never materialised on the GPU: the next layer reads
