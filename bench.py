@@ -147,6 +147,46 @@ def wide_batch(B, torch, synth, mean_zeros):
     return rows
 
 
+def transposed_decoder(B, torch, synth, steps):
+    """The same network with the paper's decoder (masked transposed 2x2 stride-2 layers instead
+    of nearest up-sampling, Sec. 2.1) at 1x3x1024x2048: frames/s and the transposed layers'
+    own times."""
+    n, h, w = 1, 1024, 2048
+    case = synth.unet_case(6, 2, n, h, w, keep=0.6, transposed=True)
+
+    def dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+    net = B.UNet(dev(case.stem_w), [(dev(wt), dev(t)) for wt, t in case.convs], dev(case.cls_w),
+                 dev(case.cls_b), levels=4, up_convs=[(dev(wt), dev(t)) for wt, t in case.up_convs])
+    image = dev(case.image)
+    logits = torch.empty((n, case.n_classes, h, w), dtype=torch.float32, device="cuda")
+    for _ in range(3):
+        net.forward(image, logits)
+    e0, e1 = B.Event(), B.Event()
+    e0.record()
+    for _ in range(steps):
+        net.forward(image, logits)
+    e1.record()
+    ms = e0.elapsed_ms(e1) / steps
+    es = net.new_event_set()
+    net.use_event_set(es)
+    net.forward(image, logits)
+    torch.cuda.synchronize()
+    times = net.step_times_ms(n, h, w, es)
+    net.use_event_set(None)
+    ups = []
+    for s_, t in enumerate(times):
+        name, _, hh, ww, c = net.step_info(n, h, w, s_)
+        if name.startswith("up"):
+            macs = n * hh * ww * (2 * c) * c          # one tap per output pixel
+            ups.append({"step": name, "cin": 2 * c, "cout": c, "hw_out": [hh, ww],
+                        "ms": round(t, 4), "eff_tops": round(2.0 * macs / t / 1e9, 1)})
+    conv_macs = synth.unet_conv_macs(case.plan, n, h, w)
+    return {"frames_per_s": round(1e3 / ms, 1), "ms_per_step": round(ms, 4),
+            "conv3x3_macs_per_frame": conv_macs, "transposed_layers": ups}
+
+
 def cpu_baseline(synth):
     """The oracle as it stands on the host cores, on a quarter-frame (512x1024) of the
     same network; reported as full-frame-equivalent frames/s."""
@@ -295,6 +335,7 @@ def main():
         del src, dst
     if not args.no_sweep:
         out["conv_sweep"] = conv_sweep(B, torch, synth)
+        out["transposed_decoder"] = transposed_decoder(B, torch, synth, K)
         out["wide_batch8"] = wide_batch(B, torch, synth,
                                         (0.2, 0.4, 0.6, 0.8) if args.sparsity_sweep else (0.6,))
     out["cpu_baseline"] = None if args.no_cpu else cpu_baseline(synth)

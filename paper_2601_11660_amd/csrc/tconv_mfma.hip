@@ -8,11 +8,11 @@
 //   D_p[cout][pixel] = sum_c W[cout][p][c] * A[c][pixel].
 // Same FP4 encoding and operand layout as the 3x3 layer (exact integers in fp32).  No halo
 // and no reuse of activations between taps: the activation fragment of a lane is ONE packed
-// word, loaded straight from global memory and expanded in registers (7 vector ops), and it
-// feeds the 4 positions x 2 channel tiles = 8 matrix instructions of a 64-channel step.
-// A wave owns 32 consecutive input pixels of one image row and 64 output channels, i.e.
-// 8 accumulator tiles (128 registers); weights of the next step are fetched while the
-// current step multiplies.
+// word, loaded straight from global memory and expanded in registers (7 vector ops),
+// and it feeds the two channel tiles of one position.  The four waves of a block are the four
+// positions of the same 4 x 32 input pixels and 64 output channels (8 accumulator tiles =
+// 128 registers per wave); weights of the next step are fetched while the current step
+// multiplies.
 #include "mbu_internal.h"
 #include "mfma_common.h"
 
@@ -71,39 +71,53 @@ int launch_pack_tconv(const int8_t *w, const TconvLayout &L, void *blob, hipStre
     return check_launch("pack_tconv_weights");
 }
 
-// weight fragments of one 64-channel step: [position][m]
-__device__ __forceinline__ void load_step(v4i (&Wt)[4][2], const uint4 *wk)
+// weight fragments of one 64-channel step of one position: [m]
+__device__ __forceinline__ void load_step(v4i (&Wt)[2], const uint4 *wk)
 {
 #pragma unroll
-    for (int p = 0; p < 4; ++p)
-#pragma unroll
-        for (int m = 0; m < 2; ++m) {
-            const uint4 a = wk[(p * 2 + m) * 64];
-            Wt[p][m] = (v4i){(int)a.x, (int)a.y, (int)a.z, (int)a.w};
-        }
+    for (int m = 0; m < 2; ++m) {
+        const uint4 a = wk[m * 64];
+        Wt[m] = (v4i){(int)a.x, (int)a.y, (int)a.z, (int)a.w};
+    }
 }
+
+// A wave owns ONE position p = 2*dy + dx, 64 output channels and RG = 4 consecutive image rows
+// x 32 input pixels: 8 accumulator tiles, and every weight fragment it fetches feeds four
+// matrix instructions (one per row).  The four positions of a pixel group are four waves of
+// the same block, which read the same activation words (L1 hits).
+constexpr int RG = 4;
 
 template <bool WRITE_ACC>
 __global__ __launch_bounds__(256, 2) void tconv_mfma_kernel(
     const uint32_t *__restrict__ act, int N, int H, int W, int Cw, int ksteps,
-    const uint4 *__restrict__ wfrag, int Cout, long groups, int groups_x,
+    const uint4 *__restrict__ wfrag, int Cout, long groups, int groups_x, int groups_y,
     const int32_t *__restrict__ thresh, uint32_t *__restrict__ out_bits,
     int32_t *__restrict__ out_acc)
 {
     const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const long g = (long)blockIdx.x * 4 + wave;        // 32-pixel group of input pixels
-    if (g >= groups) return;                           // nothing is shared between waves
-    const int ct = blockIdx.y;                         // 64-channel output tile
+    const int p = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // position of this wave
+    const long g = blockIdx.x;                          // (n, row group, 32-pixel column group)
+    const int ct = blockIdx.y;                          // 64-channel output tile
     const int col = lane & 31, half = lane >> 5;
     const int gx = (int)(g % groups_x);
-    const long row = g / groups_x;                     // n * H + y
+    const long q = g / groups_x;
+    const int gy = (int)(q % groups_y);
+    const long n = q / groups_y;
     const int x = gx * 32 + col;
-    const bool in = x < W;
-    const uint32_t *src = act + ((size_t)row * W + (in ? x : W - 1)) * Cw;
-    const uint32_t k8 = in ? 0x88888888u : 0u, k2 = k8 >> 2;
+    const int y0 = gy * RG;
+    const bool in_x = x < W;
 
-    v16f acc[4][2];
+    const uint32_t *src[RG];
+    uint32_t k8[RG];
+#pragma unroll
+    for (int r = 0; r < RG; ++r) {
+        const bool in = in_x && y0 + r < H;
+        const int yc = min(y0 + r, H - 1), xc = in_x ? x : W - 1;
+        src[r] = act + (((size_t)n * H + yc) * W + xc) * Cw;
+        k8[r] = in ? 0x88888888u : 0u;
+    }
+
+    v16f acc[RG][2];
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
         const int cbase = ct * 64 + m * 32 + 16 * half;
@@ -113,57 +127,62 @@ __global__ __launch_bounds__(256, 2) void tconv_mfma_kernel(
         if (!WRITE_ACC && cbase < Cout) {              // accumulators start at -theta
             const int4 *tp = reinterpret_cast<const int4 *>(thresh + cbase);
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int4 t = tp[q];
-                init[4 * q] = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.x));
-                init[4 * q + 1] = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.y));
-                init[4 * q + 2] = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.z));
-                init[4 * q + 3] = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.w));
+            for (int qq = 0; qq < 4; ++qq) {
+                const int4 t = tp[qq];
+                init[4 * qq] = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.x));
+                init[4 * qq + 1] = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.y));
+                init[4 * qq + 2] = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.z));
+                init[4 * qq + 3] = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.w));
             }
         }
 #pragma unroll
-        for (int p = 0; p < 4; ++p)
+        for (int r = 0; r < RG; ++r)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[p][m][i] = init[i];
+            for (int i = 0; i < 16; ++i) acc[r][m][i] = init[i];
     }
 
-    const uint4 *wk = wfrag + (size_t)ct * ksteps * (8 * 64) + lane;
-    auto fetch_word = [&](int ks) -> uint32_t {
-        const int k = 2 * ks + half;
-        return src[min(k, Cw - 1)];
+    // fragments: [tile64][kstep][position][m][lane]
+    const uint4 *wk = wfrag + ((size_t)ct * ksteps * 8 + p * 2) * 64 + lane;
+    auto fetch_words = [&](int ks, uint32_t (&wd)[RG]) {
+        const int k = min(2 * ks + half, Cw - 1);
+#pragma unroll
+        for (int r = 0; r < RG; ++r) wd[r] = src[r][k];
     };
-    auto step = [&](int ks, uint32_t word, const v4i (&Wt)[4][2]) {
+    auto step = [&](int ks, const uint32_t (&wd)[RG], const v4i (&Wt)[2]) {
         const bool live = 2 * ks + half < Cw;          // second word of an odd word count
-        const uint32_t m8 = live ? k8 : 0u, m2 = live ? k2 : 0u;
-        const v4i B = {(int)(((word << 3) & m8) | m2), (int)(((word << 2) & m8) | m2),
-                       (int)(((word << 1) & m8) | m2), (int)((word & m8) | m2)};
 #pragma unroll
-        for (int p = 0; p < 4; ++p)
+        for (int r = 0; r < RG; ++r) {
+            const uint32_t m8 = live ? k8[r] : 0u, m2 = m8 >> 2;
+            const uint32_t word = wd[r];
+            const v4i B = {(int)(((word << 3) & m8) | m2), (int)(((word << 2) & m8) | m2),
+                           (int)(((word << 1) & m8) | m2), (int)((word & m8) | m2)};
 #pragma unroll
-            for (int m = 0; m < 2; ++m) acc[p][m] = mfma_f4(Wt[p][m], B, acc[p][m]);
+            for (int m = 0; m < 2; ++m) acc[r][m] = mfma_f4(Wt[m], B, acc[r][m]);
+        }
     };
 
-    v4i Wa[4][2], Wb[4][2];
+    v4i Wa[2], Wb[2];
+    uint32_t wa[RG], wb[RG];
     load_step(Wa, wk);
-    uint32_t wa = fetch_word(0), wb = 0;
+    fetch_words(0, wa);
     for (int ks = 0; ks < ksteps; ks += 2) {
         const int k1 = min(ks + 1, ksteps - 1), k2n = min(ks + 2, ksteps - 1);
         load_step(Wb, wk + (size_t)k1 * (8 * 64));
-        wb = fetch_word(k1);
+        fetch_words(k1, wb);
         step(ks, wa, Wa);
         load_step(Wa, wk + (size_t)k2n * (8 * 64));
-        wa = fetch_word(k2n);
+        fetch_words(k2n, wa);
         if (ks + 1 < ksteps) step(ks + 1, wb, Wb);
     }
 
-    // ---- epilogue: output pixel (2y+dy, 2x+dx) of position p = 2*dy + dx
+    // ---- epilogue: input pixel (y, x) -> output pixel (2y+dy, 2x+dx)
     const int Cow = Cout >> 5;
-    const long n = row / H;
-    const int y = (int)(row - n * H);
+    const int dy = p >> 1, dx = p & 1;
     const uint32_t psel = half ? 0x07060302u : 0x05040100u;
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-        const int dy = p >> 1, dx = p & 1;
+    for (int r = 0; r < RG; ++r) {
+        const int y = y0 + r;
+        const bool in = in_x && y < H;
         const size_t pix = ((size_t)n * 2 * H + 2 * y + dy) * 2 * W + 2 * x + dx;
         if (WRITE_ACC) {
             uint32_t bits[2] = {0, 0};
@@ -173,15 +192,15 @@ __global__ __launch_bounds__(256, 2) void tconv_mfma_kernel(
                 int vals[16];
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    vals[i] = (int)acc[p][m][i];
+                    vals[i] = (int)acc[r][m][i];
                     const int th = cbase < Cout ? thresh[cbase + i] : 0x7fffffff;
                     bits[m] |= (uint32_t)(vals[i] < th) << i;       // 1 = below threshold
                 }
                 if (in && cbase < Cout && out_acc) {
                     int4 *dst = reinterpret_cast<int4 *>(out_acc + pix * Cout + cbase);
 #pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        dst[q] = make_int4(vals[4 * q], vals[4 * q + 1], vals[4 * q + 2], vals[4 * q + 3]);
+                    for (int qq = 0; qq < 4; ++qq)
+                        dst[qq] = make_int4(vals[4 * qq], vals[4 * qq + 1], vals[4 * qq + 2], vals[4 * qq + 3]);
                 }
             }
             const uint32_t word = finish_word64(bits[0], bits[1], psel);
@@ -190,8 +209,8 @@ __global__ __launch_bounds__(256, 2) void tconv_mfma_kernel(
             uint32_t s0 = 0, s1 = 0;
 #pragma unroll
             for (int i = 15; i >= 0; --i) {
-                s0 = __builtin_amdgcn_alignbit(s0, __float_as_uint(acc[p][0][i]), 31);
-                s1 = __builtin_amdgcn_alignbit(s1, __float_as_uint(acc[p][1][i]), 31);
+                s0 = __builtin_amdgcn_alignbit(s0, __float_as_uint(acc[r][0][i]), 31);
+                s1 = __builtin_amdgcn_alignbit(s1, __float_as_uint(acc[r][1][i]), 31);
             }
             const uint32_t word = finish_word64(s0, s1, psel);
             if (in && ct * 2 + half < Cow) out_bits[pix * Cow + ct * 2 + half] = word;
@@ -203,17 +222,17 @@ int launch_tconv_mfma(const uint32_t *act, int N, int H, int W, const TconvLayou
                       const void *blob, const int32_t *thresh, uint32_t *out_bits, int32_t *out_acc,
                       hipStream_t s)
 {
-    const int groups_x = ceil_div(W, 32);
-    const long groups = (long)N * H * groups_x;
-    if (groups > 0x7fffffffL * 4) return fail(MBU_ERR_SHAPE, "too many pixel groups for one launch");
+    const int groups_x = ceil_div(W, 32), groups_y = ceil_div(H, RG);
+    const long groups = (long)N * groups_y * groups_x;
+    if (groups > 0x7fffffffL) return fail(MBU_ERR_SHAPE, "too many pixel groups for one launch");
     const uint4 *wfrag = (const uint4 *)((const uint8_t *)blob + L.off_f4);
-    dim3 grid((unsigned)((groups + 3) / 4), (unsigned)(L.cout_pad64 / 64));
+    dim3 grid((unsigned)groups, (unsigned)(L.cout_pad64 / 64));   // 4 waves = the 4 positions
     if (out_acc)
         MBU_LAUNCH(tconv_mfma_kernel<true>, grid, dim3(256), 0, s, act, N, H, W, L.cin_words,
-                   L.ksteps, wfrag, L.cout, groups, groups_x, thresh, out_bits, out_acc);
+                   L.ksteps, wfrag, L.cout, groups, groups_x, groups_y, thresh, out_bits, out_acc);
     else
         MBU_LAUNCH(tconv_mfma_kernel<false>, grid, dim3(256), 0, s, act, N, H, W, L.cin_words,
-                   L.ksteps, wfrag, L.cout, groups, groups_x, thresh, out_bits, out_acc);
+                   L.ksteps, wfrag, L.cout, groups, groups_x, groups_y, thresh, out_bits, out_acc);
     return check_launch("tconv2x2_masked_binary");
 }
 
