@@ -45,6 +45,7 @@ __global__ __launch_bounds__(256) void stem_kernel(const float *__restrict__ img
     const size_t pix = ((size_t)n * H + y) * W + x;
     for (int k = 0; k < Cow; ++k) {
         uint32_t s0 = 0, s1 = 0;
+#pragma unroll 2
         for (int b = 31; b >= 0; --b) {
             const float *wo = w + (size_t)(k * 32 + b) * 9 * CI;
             float a0 = 0.0f, a1 = 0.0f;
