@@ -23,43 +23,6 @@
 
 namespace mbu {
 
-// Position of a pixel tile, advanced by a fixed stride without divisions: the stride is
-// split on the host into (dx, dy, dn) = stride mod tiles_x, (stride / tiles_x) mod tiles_y,
-// stride / (tiles_x * tiles_y).
-struct TileStep {
-    int tiles_x, tiles_y, dx, dy, dn;
-};
-struct TilePos {
-    int tx, ty, n;
-    __device__ __forceinline__ void advance(const TileStep &st)
-    {
-        tx += st.dx;
-        if (tx >= st.tiles_x) { tx -= st.tiles_x; ++ty; }
-        ty += st.dy;
-        if (ty >= st.tiles_y) { ty -= st.tiles_y; ++n; }
-        n += st.dn;
-    }
-};
-__host__ __device__ inline TilePos tile_pos(int pt, int tiles_x, int tiles_y)
-{
-    TilePos p;
-    p.tx = pt % tiles_x;
-    const int q = pt / tiles_x;
-    p.ty = q % tiles_y;
-    p.n = q / tiles_y;
-    return p;
-}
-static TileStep tile_step(int stride, int tiles_x, int tiles_y)
-{
-    TileStep st;
-    st.tiles_x = tiles_x;
-    st.tiles_y = tiles_y;
-    st.dx = stride % tiles_x;
-    st.dy = (stride / tiles_x) % tiles_y;
-    st.dn = stride / (tiles_x * tiles_y);
-    return st;
-}
-
 constexpr int TW = 32;            // pixels per matrix column tile (one image-row segment)
 constexpr int HALO_W = TW + 2;
 
