@@ -176,6 +176,41 @@ int mbu_upsample2x_bits(const uint32_t *in, int N, int H, int W, int C,
 int mbu_concat_bits(const uint32_t *a, int Ca, const uint32_t *b, int Cb,
                     int N, int H, int W, uint32_t *out, void *stream);
 
+/* Which implementation the float32 first layer uses (results are identical bit for bit). */
+typedef enum mbu_stem_path {
+    MBU_STEM_AUTO = 0,   /* matrix cores, unless out_pre is requested (default)            */
+    MBU_STEM_VALU = 1,   /* the sequential fused-multiply-add chain for every output       */
+    MBU_STEM_MFMA = 2    /* split-bf16 estimate on the matrix cores; outputs whose sign    */
+                         /* the estimate cannot decide are recomputed by the chain         */
+} mbu_stem_path;
+int mbu_set_stem_path(int path);
+int mbu_get_stem_path(void);
+
+/* Full-precision first layer (Sec. 4.1: the first convolution stays full precision; its
+ * binary activation feeds the masked-binary layers): 3x3, stride 1, zero padding, no bias,
+ *   y[n,y,x,o] = sum over ky, kx, ci (in that order, from 0.0f, one fused multiply-add per
+ *                term) of w[o,ky,kx,ci] * image[n,ci,y+ky-1,x+kx-1],   bit = (y >= 0).
+ * The order is part of the definition because the sign feeds bit-exact layers.
+ *   image_nchw  float32 [N][Ci][H][W], Ci in {1, 3}, at most 2 GiB
+ *   w           float32 [Co][3][3][Ci], Co a positive multiple of 32
+ *   out_bits    packed [N][H][W][Co/32]
+ *   out_pre     float32 NHWC [N][H][W][Co] or NULL (parity / debugging).  On the VALU path
+ *               (and with MBU_STEM_AUTO) these are the chain's values y.  With MBU_STEM_MFMA
+ *               they are the matrix-core estimates, within 2^-18 * ||w_o||_2 * ||patch||_2
+ *               of y, except for the recomputed outputs, which are y itself.
+ * Errors: NULL / misaligned pointers, bad shapes. */
+int mbu_stem_fp32(const float *image_nchw, int N, int Ci, int H, int W, const float *w, int Co,
+                  uint32_t *out_bits, float *out_pre, void *stream);
+
+/* Full-precision last layer (Sec. 4.1; Sec. 3.2.2 lists 1x1 convolutions as trivial):
+ *   logit[n,k,y,x] = b[k] + sum_c w[k][c] * a[n,y,x,c],  a = +-1 from the packed bits.
+ *   act          packed [N][H][W][C/32], C in {32, 64, 128}
+ *   w, b         float32 [K][C], [K], K <= 32
+ *   logits_nchw  float32 [N][K][H][W]
+ * Accurate to about 1e-6 relative (fp32 accumulation of exact products). */
+int mbu_classifier_fp32(const uint32_t *act, int N, int H, int W, int C, const float *w,
+                        const float *b, int K, float *logits_nchw, void *stream);
+
 /* One masked-binary layer of the network: host struct, device pointers inside. */
 typedef struct mbu_conv_layer {
     const void *packed_w;    /* blob from mbu_pack_weights(cout, cin)  */

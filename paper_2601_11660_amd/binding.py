@@ -17,9 +17,11 @@ LIB_PATH = os.path.join(_HERE, "libmbu_hip.so")
 MBU_OK = 0
 MBU_ERR_NULL, MBU_ERR_SHAPE, MBU_ERR_ALIGN, MBU_ERR_WORKSPACE, MBU_ERR_HIP, MBU_ERR_ARG = -1, -2, -3, -4, -5, -6
 PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
+STEM_AUTO, STEM_VALU, STEM_MFMA = 0, 1, 2
 
 EXPORTS = [
     "mbu_last_error", "mbu_set_conv_path", "mbu_get_conv_path", "mbu_set_conv_tuning", "mbu_pack_act",
+    "mbu_set_stem_path", "mbu_get_stem_path", "mbu_stem_fp32", "mbu_classifier_fp32",
     "mbu_packed_weights_bytes", "mbu_pack_weights", "mbu_conv3x3_masked_binary",
     "mbu_conv3x3_masked_binary_fused", "mbu_conv3x3_masked_binary_concat",
     "mbu_packed_tconv_weights_bytes", "mbu_pack_tconv_weights", "mbu_tconv2x2_masked_binary",
@@ -71,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.mbu_packed_tconv_weights_bytes.argtypes = [ci, ci, ctypes.POINTER(ctypes.c_size_t)]
         L.mbu_pack_tconv_weights.argtypes = [vp, ci, ci, vp, vp]
         L.mbu_tconv2x2_masked_binary.argtypes = [vp, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp]
+        L.mbu_stem_fp32.argtypes = [vp, ci, ci, ci, ci, vp, ci, vp, vp, vp]
+        L.mbu_classifier_fp32.argtypes = [vp, ci, ci, ci, ci, vp, vp, ci, vp, vp]
         L.mbu_maxpool2x2_bits.argtypes = [vp, ci, ci, ci, ci, vp, vp]
         L.mbu_upsample2x_bits.argtypes = [vp, ci, ci, ci, ci, vp, vp]
         L.mbu_concat_bits.argtypes = [vp, ci, vp, ci, ci, ci, ci, vp, vp]
@@ -126,6 +130,38 @@ def get_conv_path() -> int:
 def set_conv_tuning(kernel: int = 0) -> None:
     """mbu_set_conv_tuning: 0 automatic, 1 block-cooperative, 3 / 6 wave-private variants."""
     check(lib().mbu_set_conv_tuning(kernel, 0))
+
+
+def set_stem_path(path: int) -> None:
+    check(lib().mbu_set_stem_path(path))
+
+
+def get_stem_path() -> int:
+    return lib().mbu_get_stem_path()
+
+
+def stem_fp32(image: torch.Tensor, w: torch.Tensor, want_pre: bool = False
+              ) -> Tuple[torch.Tensor, Optional[torch.Tensor]]:
+    """mbu_stem_fp32: image float32 NCHW, w float32 [Co,3,3,Ci] -> (packed bits [N,H,W,Co/32],
+    float32 NHWC pre-activations or None)."""
+    N, Ci, H, W = image.shape
+    Co = w.shape[0]
+    bits = torch.empty((N, H, W, Co // 32), dtype=torch.int32, device=image.device)
+    pre = torch.empty((N, H, W, Co), dtype=torch.float32, device=image.device) if want_pre else None
+    check(lib().mbu_stem_fp32(_dev(image, (torch.float32,)), N, Ci, H, W, _dev(w, (torch.float32,)),
+                              Co, bits.data_ptr(), pre.data_ptr() if pre is not None else None,
+                              _stream()))
+    return bits, pre
+
+
+def classifier_fp32(act: torch.Tensor, c: int, w: torch.Tensor, b: torch.Tensor) -> torch.Tensor:
+    """mbu_classifier_fp32: packed bits [N,H,W,C/32], w [K,C], b [K] -> float32 logits NCHW."""
+    N, H, W, _ = act.shape
+    K = w.shape[0]
+    out = torch.empty((N, K, H, W), dtype=torch.float32, device=act.device)
+    check(lib().mbu_classifier_fp32(_dev(act, (torch.int32,)), N, H, W, c, _dev(w, (torch.float32,)),
+                                    _dev(b, (torch.float32,)), K, out.data_ptr(), _stream()))
+    return out
 
 
 # Packed words are stored in int32 tensors (same bits as the ABI's uint32).

@@ -1,4 +1,5 @@
 """Builds the HIP library in-tree: paper_2601_11660_amd/libmbu_hip.so (gfx950 only)."""
+import concurrent.futures
 import glob
 import os
 import subprocess
@@ -7,14 +8,22 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmbu_hip.so")
+OBJ_DIR = os.path.join(ROOT, "_build")
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # packed-fp32 instruction forms are kept out of the generated code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-ffp-contract=off",
     "-Wno-unused-command-line-argument",
 ]
+
+# per-source additions
+EXTRA_FLAGS = {
+    # the first layer reads its few accumulators straight back with vector instructions:
+    # keep them in ordinary vector registers instead of accumulation registers
+    "stem_mfma.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+}
 
 
 def sources():
@@ -24,10 +33,23 @@ def sources():
 def build(verbose: bool = False) -> str:
     """Compile every HIP source and link the shared library (always recompiles)."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC,
-                                   "-o", LIB] + sources()
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    inc = ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+
+    def compile_one(src):
+        obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
+        cmd = [hipcc] + HIPCC_FLAGS + EXTRA_FLAGS.get(os.path.basename(src), []) + inc + ["-c", src, "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+        return obj
+
+    workers = min(8, len(os.sched_getaffinity(0)))
+    with concurrent.futures.ThreadPoolExecutor(max_workers=workers) as pool:
+        objs = list(pool.map(compile_one, sources()))
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs
     if verbose:
-        print(" ".join(cmd))
+        print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
     return LIB
 

@@ -14,12 +14,12 @@ namespace mbu {
 //
 // One thread owns two horizontally adjacent pixels; the weight of a term is
 // wave-uniform, arrives through the scalar cache and feeds both pixels' chains.
-// A chain that starts at +0.0f can never end at -0.0f, so "sum >= 0" is the complement
-// of the sign bit, collected with one funnel shift per output channel.
-template <int CI>
+// The output bit is the comparison "sum >= 0" itself (false for a NaN sum), shifted into
+// the word one channel at a time.
+template <int CI, bool WRITE_PRE>
 __global__ __launch_bounds__(256) void stem_kernel(const float *__restrict__ img, int N, int H,
                                                    int W, const float *__restrict__ w, int Co,
-                                                   uint32_t *__restrict__ out)
+                                                   uint32_t *__restrict__ out, float *__restrict__ pre)
 {
     const int PW = (W + 1) >> 1;
     const long total = (long)N * H * PW;
@@ -59,25 +59,33 @@ __global__ __launch_bounds__(256) void stem_kernel(const float *__restrict__ img
                         a0 = __builtin_fmaf(wv, in[ky][kx][ci], a0);
                         a1 = __builtin_fmaf(wv, in[ky][kx + 1][ci], a1);
                     }
-            s0 = __builtin_amdgcn_alignbit(s0, __float_as_uint(a0), 31);
-            s1 = __builtin_amdgcn_alignbit(s1, __float_as_uint(a1), 31);
+            s0 = (s0 << 1) | (a0 >= 0.0f ? 0u : 1u);
+            s1 = (s1 << 1) | (a1 >= 0.0f ? 0u : 1u);
+            if (WRITE_PRE) {
+                pre[pix * Co + k * 32 + b] = a0;
+                if (x + 1 < W) pre[(pix + 1) * Co + k * 32 + b] = a1;
+            }
         }
         out[pix * Cow + k] = ~s0;
         if (x + 1 < W) out[(pix + 1) * Cow + k] = ~s1;
     }
 }
 
-int launch_stem(const float *img, int N, int Ci, int H, int W, const float *w, int Co,
-                uint32_t *out_bits, hipStream_t s)
+int launch_stem_valu(const float *img, int N, int Ci, int H, int W, const float *w, int Co,
+                     uint32_t *out_bits, float *out_pre, hipStream_t s)
 {
     long total = (long)N * H * ((W + 1) / 2);
     unsigned blocks = (unsigned)((total + 255) / 256);
-    if (Ci == 3)
-        MBU_LAUNCH(stem_kernel<3>, dim3(blocks), dim3(256), 0, s, img, N, H, W, w, Co, out_bits);
-    else if (Ci == 1)
-        MBU_LAUNCH(stem_kernel<1>, dim3(blocks), dim3(256), 0, s, img, N, H, W, w, Co, out_bits);
-    else
+#define MBU_STEM_LAUNCH(CI, PRE) \
+    MBU_LAUNCH((stem_kernel<CI, PRE>), dim3(blocks), dim3(256), 0, s, img, N, H, W, w, Co, out_bits, out_pre)
+    if (Ci == 3) {
+        if (out_pre) MBU_STEM_LAUNCH(3, true); else MBU_STEM_LAUNCH(3, false);
+    } else if (Ci == 1) {
+        if (out_pre) MBU_STEM_LAUNCH(1, true); else MBU_STEM_LAUNCH(1, false);
+    } else {
         return fail(MBU_ERR_SHAPE, "stem supports 1 or 3 image channels, got %d", Ci);
+    }
+#undef MBU_STEM_LAUNCH
     return check_launch("stem");
 }
 

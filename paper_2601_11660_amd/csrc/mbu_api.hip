@@ -9,6 +9,7 @@ namespace mbu {
 
 static thread_local char g_err[512] = "";
 static int g_conv_path = MBU_PATH_AUTO;
+static int g_stem_path = MBU_STEM_AUTO;
 
 int fail(int code, const char *fmt, ...)
 {
@@ -179,6 +180,14 @@ static int run_conv(const uint32_t *act, int N, int H, int W, int Cin, const voi
     return launch_conv_mfma(act, N, H, W, L, packed_w, thresh, out_bits, out_acc, s);
 }
 
+static int run_stem(const float *img, int N, int Ci, int H, int W, const float *w, int Co,
+                    uint32_t *out_bits, float *out_pre, hipStream_t s)
+{
+    const bool valu = g_stem_path == MBU_STEM_VALU || (g_stem_path == MBU_STEM_AUTO && out_pre);
+    if (valu) return launch_stem_valu(img, N, Ci, H, W, w, Co, out_bits, out_pre, s);
+    return launch_stem_mfma(img, N, Ci, H, W, w, Co, out_bits, out_pre, s);
+}
+
 }  // namespace mbu
 
 using namespace mbu;
@@ -196,6 +205,48 @@ int mbu_set_conv_path(int path)
 }
 
 int mbu_get_conv_path(void) { return g_conv_path; }
+
+int mbu_set_stem_path(int path)
+{
+    if (path != MBU_STEM_AUTO && path != MBU_STEM_VALU && path != MBU_STEM_MFMA)
+        return fail(MBU_ERR_ARG, "mbu_set_stem_path: unknown path %d", path);
+    g_stem_path = path;
+    return MBU_OK;
+}
+
+int mbu_get_stem_path(void) { return g_stem_path; }
+
+int mbu_stem_fp32(const float *image_nchw, int N, int Ci, int H, int W, const float *w, int Co,
+                  uint32_t *out_bits, float *out_pre, void *stream)
+{
+    const char *fn = "mbu_stem_fp32";
+    MBU_REQ_PTR(fn, image_nchw);
+    MBU_REQ_PTR(fn, w);
+    MBU_REQ_PTR(fn, out_bits);
+    if (out_pre && !aligned16(out_pre)) return fail(MBU_ERR_ALIGN, "%s: out_pre is not 16-byte aligned", fn);
+    if (Ci != 1 && Ci != 3) return fail(MBU_ERR_SHAPE, "%s: Ci must be 1 or 3, got %d", fn, Ci);
+    if (Co <= 0 || Co % 32 || Co > 65536) return fail(MBU_ERR_SHAPE, "%s: Co must be a positive multiple of 32, got %d", fn, Co);
+    int rc = check_dims4(fn, N, H, W, Co);
+    if (rc) return rc;
+    if ((double)N * Ci * H * W * 4.0 >= 2147483648.0) return fail(MBU_ERR_SHAPE, "%s: image larger than 2 GiB", fn);
+    if (out_pre && (double)N * H * W * Co * 4.0 > 16.0e9) return fail(MBU_ERR_SHAPE, "%s: out_pre too large", fn);
+    return run_stem(image_nchw, N, Ci, H, W, w, Co, out_bits, out_pre, (hipStream_t)stream);
+}
+
+int mbu_classifier_fp32(const uint32_t *act, int N, int H, int W, int C, const float *w,
+                        const float *b, int K, float *logits_nchw, void *stream)
+{
+    const char *fn = "mbu_classifier_fp32";
+    MBU_REQ_PTR(fn, act);
+    MBU_REQ_PTR(fn, w);
+    MBU_REQ_PTR(fn, b);
+    MBU_REQ_PTR(fn, logits_nchw);
+    int rc = check_dims4(fn, N, H, W, C);
+    if (rc) return rc;
+    if (C != 32 && C != 64 && C != 128) return fail(MBU_ERR_SHAPE, "%s: C must be 32, 64 or 128, got %d", fn, C);
+    if (K <= 0 || K > 32) return fail(MBU_ERR_SHAPE, "%s: K must be 1..32, got %d", fn, K);
+    return launch_classifier(act, N, H, W, C, w, b, K, logits_nchw, (hipStream_t)stream);
+}
 
 int mbu_set_conv_tuning(int rows_per_wave, int reserved)
 {
@@ -483,7 +534,7 @@ int mbu_unet_forward(const mbu_unet_desc *d, const float *image_nchw, int N, int
             return fail(MBU_ERR_HIP, "%s: hipEventRecord failed", fn);
         switch (st.kind) {
         case Step::STEM:
-            rc = launch_stem(image_nchw, N, d->in_channels, H, W, d->stem_w, d->base, buf((int)i), s);
+            rc = run_stem(image_nchw, N, d->in_channels, H, W, d->stem_w, d->base, buf((int)i), nullptr, s);
             break;
         case Step::CONV: {
             const mbu_conv_layer &L = d->convs[st.conv];

@@ -92,8 +92,12 @@ int launch_concat(const uint32_t *a, int Caw, const uint32_t *b, int Cbw, long p
 // out[n][y][x] = [ skip[n][y][x] | up[n][y/2][x/2] ]  (H, W are the output size)
 int launch_upcat(const uint32_t *skip, int Csw, const uint32_t *low, int Clw,
                  int N, int H, int W, uint32_t *out, hipStream_t s);
-int launch_stem(const float *img, int N, int Ci, int H, int W, const float *w, int Co,
-                uint32_t *out_bits, hipStream_t s);
+// first layer: sequential float32 chain on the vector ALU / matrix-core estimate with the
+// sequential chain for undecided signs; out_pre (NHWC float32) may be NULL
+int launch_stem_valu(const float *img, int N, int Ci, int H, int W, const float *w, int Co,
+                     uint32_t *out_bits, float *out_pre, hipStream_t s);
+int launch_stem_mfma(const float *img, int N, int Ci, int H, int W, const float *w, int Co,
+                     uint32_t *out_bits, float *out_pre, hipStream_t s);
 int launch_classifier(const uint32_t *act, int N, int H, int W, int C, const float *w,
                       const float *b, int K, float *out, hipStream_t s);
 

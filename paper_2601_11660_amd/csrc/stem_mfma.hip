@@ -1,0 +1,366 @@
+// Full-precision first layer (Sec. 4.1) on the matrix cores, with sign bits that are
+// identical to those of the sequential float32 definition.
+//
+// Definition (what the output bits must equal): y = sum over (ky, kx, ci) in that order of
+// w * x, started at 0.0f, one fused multiply-add per term, zero padding; bit = (y >= 0).
+// Only the SIGN of y leaves this layer, and the sign of a sum is known without the exact
+// rounding sequence whenever a cheaper estimate is further from zero than its own error:
+//
+//   fast estimate  every float is the exact sum v = vh + vm + vl of three bf16 terms (8 + 8 + 8
+//                  significand bits); yf = sum of the six products wh*xh, wh*xm, wm*xh,
+//                  wh*xl, wl*xh, wm*xm on v_mfma_f32_32x32x16_bf16 (bf16 products are
+//                  exact in the fp32 accumulator; the three dropped products are below
+//                  2^-25 |w x|);
+//   error budget   |yf - y| <= kappa * ||w_o||_2 * ||x_patch||_2 covers the dropped
+//                  products, the accumulation rounding of the matrix instruction and the
+//                  rounding of the sequential chain itself (27 * 2^-24), all relative to
+//                  sum |w||x| <= ||w||_2 ||x||_2;
+//   decision       |yf| >  T = kappa * max_o ||w_o|| * ||x_patch||  ->  sign(y) = sign(yf);
+//                  otherwise the output is recomputed by the sequential chain itself.
+//
+// About 1 output in 10^5 takes the second route with normally distributed data, so the
+// layer costs 24 matrix instructions per 32 pixels x 64 channels instead of 64 x 27 fused
+// multiply-adds per pixel.  Non-finite inputs, and norms outside [2^-60, 2^60] (where bf16
+// terms could be flushed or products overflow), make T infinite and send every affected
+// output down the sequential route; an all-zero patch gives +0.0f without any arithmetic.
+//
+// GEMM view: D[channel][pixel] = sum_k Wt[channel][k] * X[k][pixel], k = (ky*3 + kx)*Ci + ci
+// (the memory order of the weights), padded to KT*16.  A wave owns 64 output channels
+// (two 32-row tiles, weights split once and kept in registers) and walks over tiles of
+// 32 consecutive pixels of an image row.  Lane (column j, half h) gathers the patch values
+// k = 16t + 8h + i of pixel x0 + j through a raw buffer resource - a border tap or a padded
+// k gets an offset beyond the buffer and reads 0.0f.
+#include "mbu_internal.h"
+#include "mfma_common.h"
+
+namespace mbu {
+
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef float v2f __attribute__((ext_vector_type(2)));
+
+// Error budget of the fast estimate relative to ||w||_2 ||x||_2 (see the header comment):
+// sequential chain 27 * 2^-24 = 1.6e-6, dropped products 3e-8, matrix accumulation measured
+// below 5e-7; 2^-18 = 3.8e-6 leaves a factor of almost two.
+constexpr float STEM_KAPPA = 0x1p-18f;
+constexpr uint32_t OOB = 0x80000000u;   // byte offset beyond any accepted image
+
+__device__ __forceinline__ uint32_t bf16_pair(float a, float b)
+{
+    const v2f f = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, v2bf));   // low half = a
+}
+
+// (a, b) -> packed bf16 pairs hi, mid, lo with v = hi + mid + lo exactly: each rounding to
+// nearest leaves a remainder of at most 16, then 8 significant bits, and the remainders are
+// computed without error
+__device__ __forceinline__ void split_pair(float a, float b, uint32_t &hi, uint32_t &mid, uint32_t &lo)
+{
+    hi = bf16_pair(a, b);
+    const float a1 = a - __uint_as_float(hi << 16), b1 = b - __uint_as_float(hi & 0xffff0000u);
+    mid = bf16_pair(a1, b1);
+    const float a2 = a1 - __uint_as_float(mid << 16), b2 = b1 - __uint_as_float(mid & 0xffff0000u);
+    lo = __builtin_amdgcn_perm(__float_as_uint(b2), __float_as_uint(a2), 0x07060302u);   // already bf16
+}
+
+__device__ __forceinline__ v8bf as_v8bf(const uint4 &v) { return __builtin_bit_cast(v8bf, v); }
+
+__device__ __forceinline__ float swap_add(float v)
+{
+    const uint32_t u = __float_as_uint(v);
+    const auto sw = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(sw[0]) + __uint_as_float(sw[1]);
+}
+
+template <int CI, bool WRITE_PRE>
+__global__ __launch_bounds__(256) void stem_mfma_kernel(
+    const float *__restrict__ img, uint32_t img_bytes, int N, int H, int W,
+    const float *__restrict__ w, int Co, int nchunks, int nslots, int ntiles, TileStep tstep,
+    uint32_t *__restrict__ out, float *__restrict__ pre)
+{
+    constexpr int KV = 9 * CI;             // terms per output
+    constexpr int KT = (KV + 15) / 16;     // 16-wide K blocks
+    constexpr int NS = KT * 8;             // patch values per lane
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int gw = blockIdx.x * 4 + wave;
+    if (gw >= nchunks * nslots) return;    // whole wave leaves; nothing is shared
+    const int chunk = gw % nchunks;        // 64 output channels, fixed for the wave
+    const int slot = gw / nchunks;
+    const int col = lane & 31, half = lane >> 5;
+    const bool tile1 = chunk * 64 + 32 < Co;   // second 32-channel tile exists (Co % 32 == 0)
+
+    // ---- weights of this wave: split once, kept in registers; row norms for the bound
+    uint4 Wh[2][KT], Wm[2][KT], Wl[2][KT];
+    uint32_t rb = 0;   // bit pattern of the largest ||w_row||^2 seen (see below)
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+        const int ch = chunk * 64 + m * 32 + tile_row_to_channel(col);
+        float part = 0.0f;
+#pragma unroll
+        for (int t = 0; t < KT; ++t) {
+            float v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int k = 16 * t + 8 * half + i;
+                const bool ok = ch < Co && k < KV;
+                const float wv = w[ok ? (size_t)ch * KV + k : 0];   // unconditional load
+                v[i] = ok ? wv : 0.0f;
+                part = __builtin_fmaf(v[i], v[i], part);
+            }
+            uint32_t h4[4], m4[4], l4[4];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) split_pair(v[2 * d], v[2 * d + 1], h4[d], m4[d], l4[d]);
+            Wh[m][t] = make_uint4(h4[0], h4[1], h4[2], h4[3]);
+            Wm[m][t] = make_uint4(m4[0], m4[1], m4[2], m4[3]);
+            Wl[m][t] = make_uint4(l4[0], l4[1], l4[2], l4[3]);
+        }
+        part = swap_add(part);                          // both halves: ||w_row||^2
+        rb = max(rb, __float_as_uint(part));
+    }
+    // wave maximum of the row norms: the unsigned order of the bit patterns of non-negative
+    // floats is their numeric order, with +inf and every NaN on top, so a non-finite weight
+    // survives the reduction and poisons the bound below
+#pragma unroll
+    for (int o = 16; o >= 1; o >>= 1) rb = max(rb, (uint32_t)__shfl_xor((int)rb, o));
+    const float Wn = __builtin_sqrtf(__uint_as_float(rb));
+    // outside this range (or NaN) bf16 terms may be flushed or products may overflow: no bound
+    const bool w_sane = Wn >= 0x1p-60f && Wn <= 0x1p60f;
+
+    // ---- per-lane table of the NS gathered patch values: byte offset from the pixel and
+    // which border makes the tap fall outside the image
+    uint32_t off4[NS];
+    uint32_t m_up = 0, m_dn = 0, m_lf = 0, m_rt = 0;
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        const int k = 16 * (s >> 3) + 8 * half + (s & 7);
+        const int kk = k < KV ? k : 0;
+        const int tap = kk / CI, ci = kk - tap * CI;
+        const int ky = tap / 3, kx = tap - 3 * ky;
+        off4[s] = k < KV ? (uint32_t)(((long)ci * H * W + (long)(ky - 1) * W + (kx - 1)) * 4) : OOB;
+        if (k < KV) {
+            m_up |= (ky == 0 ? 1u : 0u) << s;
+            m_dn |= (ky == 2 ? 1u : 0u) << s;
+            m_lf |= (kx == 0 ? 1u : 0u) << s;
+            m_rt |= (kx == 2 ? 1u : 0u) << s;
+        }
+    }
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)img, 0, (int)img_bytes, 0x00020000);
+
+    const int Cow = Co >> 5;
+    const uint32_t psel = half ? 0x07060302u : 0x05040100u;
+    const int widx = chunk * 2 + half;
+    // geometry of a tile for this lane, and the gather of its patch values (0.0f outside the
+    // image): issued one tile ahead, so the loads of the next tile fly during the matrix
+    // instructions and the epilogue of the current one
+    struct Geo { int y, n, x, xc; uint32_t pb; };
+    auto geometry = [&](const TilePos &tp) {
+        Geo g;
+        g.y = tp.ty; g.n = tp.n;
+        g.x = tp.tx * 32 + col;
+        g.xc = min(g.x, W - 1);
+        g.pb = (uint32_t)((((size_t)g.n * CI * H + g.y) * W + g.xc) * 4);
+        return g;
+    };
+    float v[NS];
+    auto gather = [&](const TilePos &tp, const Geo &g) {
+        const bool interior = g.y > 0 && g.y < H - 1 && tp.tx > 0 && tp.tx * 32 + 32 < W;
+        if (interior) {
+#pragma unroll
+            for (int s = 0; s < NS; ++s)
+                v[s] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, g.pb + off4[s], 0, 0));
+        } else {
+            const uint32_t inv = (g.y == 0 ? m_up : 0u) | (g.y == H - 1 ? m_dn : 0u) |
+                                 (g.xc == 0 ? m_lf : 0u) | (g.xc == W - 1 ? m_rt : 0u);
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                const uint32_t o = ((inv >> s) & 1u) ? OOB : g.pb + off4[s];
+                v[s] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, o, 0, 0));
+            }
+        }
+    };
+
+    TilePos cur = tile_pos(slot, tstep.tiles_x, tstep.tiles_y);   // (tile in row, row, image)
+    Geo g = geometry(cur);
+    gather(cur, g);
+    for (int tl = slot; tl < ntiles; tl += nslots) {
+        // ---- split, norm, zero test
+        uint4 Bh[KT], Bm[KT], Bl[KT];
+        float n2 = 0.0f;
+        uint32_t orb = 0;
+#pragma unroll
+        for (int t = 0; t < KT; ++t) {
+            uint32_t h4[4], m4[4], l4[4];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const float a = v[8 * t + 2 * d], b = v[8 * t + 2 * d + 1];
+                split_pair(a, b, h4[d], m4[d], l4[d]);
+                n2 = __builtin_fmaf(a, a, n2);
+                n2 = __builtin_fmaf(b, b, n2);
+                orb |= __float_as_uint(a) | __float_as_uint(b);
+            }
+            Bh[t] = make_uint4(h4[0], h4[1], h4[2], h4[3]);
+            Bm[t] = make_uint4(m4[0], m4[1], m4[2], m4[3]);
+            Bl[t] = make_uint4(l4[0], l4[1], l4[2], l4[3]);
+        }
+
+        // ---- the next tile's patch values (the wave's last tile simply fetches itself again)
+        TilePos nxt = cur;
+        if (tl + nslots < ntiles) nxt.advance(tstep);
+        const Geo gn = geometry(nxt);
+        gather(nxt, gn);
+
+        // ---- fast estimate on the matrix cores (small terms first)
+        // the two channel tiles alternate, so consecutive instructions never depend on each other
+        v16f acc[2];
+#pragma unroll
+        for (int m = 0; m < 2; ++m)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[m][i] = 0.0f;
+#define MBU_STEM_MMA(WP, BP)                                                                         \
+    _Pragma("unroll") for (int t = 0; t < KT; ++t)                                                   \
+        _Pragma("unroll") for (int m = 0; m < 2; ++m)                                                \
+            acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_v8bf(WP[m][t]), as_v8bf(BP[t]), acc[m], 0, 0, 0)
+        MBU_STEM_MMA(Wl, Bh);
+        MBU_STEM_MMA(Wh, Bl);
+        MBU_STEM_MMA(Wm, Bm);
+        MBU_STEM_MMA(Wm, Bh);
+        MBU_STEM_MMA(Wh, Bm);
+        MBU_STEM_MMA(Wh, Bh);
+#undef MBU_STEM_MMA
+
+        // ---- decision threshold of this pixel
+        const int y = g.y, n = g.n, x = g.x, xc = g.xc;
+        n2 = swap_add(n2);
+        {
+            const auto sw = __builtin_amdgcn_permlane32_swap(orb, orb, false, false);
+            orb = sw[0] | sw[1];
+        }
+        const bool zero = (orb << 1) == 0;            // every patch value is +-0
+        const float nx = __builtin_sqrtf(n2);
+        // a norm that is NaN, infinite or so extreme that bf16 terms may have been flushed or
+        // products may have overflowed sends the whole pixel down the sequential route
+        const float T = (w_sane && nx >= 0x1p-60f && nx <= 0x1p60f) ? STEM_KAPPA * Wn * nx
+                                                                    : __builtin_inff();
+        float mn = __builtin_fminf(__builtin_fabsf(acc[0][0]), __builtin_fabsf(acc[0][1]));
+#pragma unroll
+        for (int i = 2; i < 16; ++i) mn = __builtin_fminf(mn, __builtin_fabsf(acc[0][i]));
+        if (tile1) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mn = __builtin_fminf(mn, __builtin_fabsf(acc[1][i]));
+        }
+        // (non-finite estimates need no test of their own: they only arise from non-finite
+        // or extreme inputs, which make T infinite)
+        const bool flag = x < W && !zero && !(mn > T);
+
+        // ---- sign bits (1 = negative) of the 2 x 16 channels of this lane
+        uint32_t sg[2] = {0u, 0u};
+#pragma unroll
+        for (int i = 15; i >= 0; --i)
+#pragma unroll
+            for (int m = 0; m < 2; ++m)
+                sg[m] = __builtin_amdgcn_alignbit(sg[m], __float_as_uint(acc[m][i]), 31);
+
+        const size_t pix = ((size_t)n * H + y) * W + xc;
+        if (WRITE_PRE && x < W) {
+#pragma unroll
+            for (int m = 0; m < 2; ++m) {
+                const int cb = chunk * 64 + m * 32 + 16 * half;
+                if (cb < Co) {
+                    float4 *dst = reinterpret_cast<float4 *>(pre + pix * Co + cb);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        dst[q] = zero ? make_float4(0.0f, 0.0f, 0.0f, 0.0f)
+                                      : make_float4(acc[m][4 * q], acc[m][4 * q + 1], acc[m][4 * q + 2],
+                                                    acc[m][4 * q + 3]);
+                }
+            }
+        }
+
+        // ---- sequential route for the undecided outputs (rare)
+        if (__builtin_amdgcn_ballot_w64(flag) != 0) {
+            if (WRITE_PRE) __builtin_amdgcn_s_waitcnt(0);   // the estimates are stored before the corrections
+            if (flag) {
+                // the whole patch of this pixel, in the order of the sum; a tap outside the
+                // image is skipped, as in the definition
+                float pv[KV];
+                uint32_t okm = 0;
+#pragma unroll
+                for (int k = 0; k < KV; ++k) {
+                    const int tap = k / CI, ci = k - tap * CI;
+                    const int ky = tap / 3, kx = tap - 3 * ky;
+                    const bool ok = !((ky == 0 && y == 0) || (ky == 2 && y == H - 1) ||
+                                      (kx == 0 && xc == 0) || (kx == 2 && xc == W - 1));
+                    const uint32_t o = g.pb + (uint32_t)(((long)ci * H * W + (long)(ky - 1) * W + (kx - 1)) * 4);
+                    pv[k] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, ok ? o : OOB, 0, 0));
+                    okm |= (ok ? 1u : 0u) << k;
+                }
+#pragma unroll
+                for (int m = 0; m < 2; ++m) {
+                    uint32_t fl = 0;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        fl |= (!(__builtin_fabsf(acc[m][i]) > T) ? 1u : 0u) << i;
+                    const int cb = chunk * 64 + m * 32 + 16 * half;
+                    if (cb >= Co) fl = 0;
+                    while (fl) {
+                        const int i = __builtin_ctz(fl);
+                        fl &= fl - 1;
+                        const float *wp = w + (size_t)(cb + i) * KV;
+                        float wv[KV];
+#pragma unroll
+                        for (int k = 0; k < KV; ++k) wv[k] = wp[k];
+                        float s = 0.0f;
+#pragma unroll
+                        for (int k = 0; k < KV; ++k) {
+                            const float f = __builtin_fmaf(wv[k], pv[k], s);
+                            s = ((okm >> k) & 1u) ? f : s;
+                        }
+                        sg[m] = (sg[m] & ~(1u << i)) | ((s >= 0.0f ? 0u : 1u) << i);   // NaN -> bit 0
+                        if (WRITE_PRE) pre[pix * Co + cb + i] = s;
+                    }
+                }
+            }
+        }
+        if (zero) { sg[0] = 0u; sg[1] = 0u; }   // a chain of zero terms ends at +0.0f
+        const uint32_t word = finish_word64(sg[0], sg[1], psel);
+        if (x < W && widx < Cow) out[pix * Cow + widx] = word;
+        cur = nxt;
+        g = gn;
+    }
+}
+
+int launch_stem_mfma(const float *img, int N, int Ci, int H, int W, const float *w, int Co,
+                     uint32_t *out_bits, float *out_pre, hipStream_t s)
+{
+    const double bytes = (double)N * Ci * H * W * 4.0;
+    if (bytes >= 2147483648.0) return fail(MBU_ERR_SHAPE, "stem: image larger than 2 GiB");
+    const int tiles_x = ceil_div(W, 32);
+    const long ntiles = (long)N * H * tiles_x;
+    if (ntiles > 0x7fffffffL) return fail(MBU_ERR_SHAPE, "stem: too many tiles for one launch");
+    const int nchunks = ceil_div(Co, 64);
+    // two waves per SIMD over the whole chip (what the register budget allows), so all waves
+    // are resident at once; every wave keeps one 64-channel chunk
+    const int max_waves = 2 * 4 * 256;
+    if (nchunks > max_waves) return fail(MBU_ERR_SHAPE, "stem: too many output channels");
+    const int nslots = (int)min(ntiles, (long)(max_waves / nchunks));
+    const int waves = nslots * nchunks;
+    const TileStep tstep = tile_step(nslots, tiles_x, H);
+    const dim3 grid(ceil_div(waves, 4)), block(256);
+#define MBU_STEM_LAUNCH(CI, PRE)                                                                    \
+    MBU_LAUNCH((stem_mfma_kernel<CI, PRE>), grid, block, 0, s, img, (uint32_t)bytes, N, H, W, w, Co, \
+               nchunks, nslots, (int)ntiles, tstep, out_bits, out_pre)
+    if (Ci == 3) {
+        if (out_pre) MBU_STEM_LAUNCH(3, true); else MBU_STEM_LAUNCH(3, false);
+    } else if (Ci == 1) {
+        if (out_pre) MBU_STEM_LAUNCH(1, true); else MBU_STEM_LAUNCH(1, false);
+    } else {
+        return fail(MBU_ERR_SHAPE, "stem supports 1 or 3 image channels, got %d", Ci);
+    }
+#undef MBU_STEM_LAUNCH
+    return check_launch("stem_mfma");
+}
+
+}  // namespace mbu

@@ -175,3 +175,25 @@ def test_unet_plan_validation_and_workspace():
     assert L.mbu_unet_forward(ctypes.byref(d), None, 1, 64, 128, 0x50000, 0x60000, 1 << 40, None) == B.MBU_ERR_NULL
     d.stem_w, d.cls_w, d.cls_b = 0x70000, 0x80000, 0x90000
     assert L.mbu_unet_forward(ctypes.byref(d), 0x40000, 1, 64, 128, 0x50000, 0x60000, 16, None) == B.MBU_ERR_WORKSPACE
+
+
+def test_stem_and_classifier_argument_validation():
+    L = B.lib()
+    img, w, o, p = 0x10000, 0x20000, 0x30000, 0x40000
+    f = L.mbu_stem_fp32
+    assert f(None, 1, 3, 8, 8, w, 64, o, None, None) == B.MBU_ERR_NULL
+    assert f(img, 1, 3, 8, 8, w, 64, None, p, None) == B.MBU_ERR_NULL
+    assert f(img, 1, 2, 8, 8, w, 64, o, None, None) == B.MBU_ERR_SHAPE
+    assert f(img, 1, 3, 8, 8, w, 48, o, None, None) == B.MBU_ERR_SHAPE
+    assert f(img, 1, 3, 0, 8, w, 64, o, None, None) == B.MBU_ERR_SHAPE
+    assert f(img, 1, 3, 8, 8, w, 64, o, p + 4, None) == B.MBU_ERR_ALIGN
+    assert f(img, 64, 3, 4096, 4096, w, 64, o, None, None) == B.MBU_ERR_SHAPE     # > 2 GiB image
+    assert L.mbu_set_stem_path(9) == B.MBU_ERR_ARG
+    assert L.mbu_set_stem_path(B.STEM_VALU) == B.MBU_OK and L.mbu_get_stem_path() == B.STEM_VALU
+    assert L.mbu_set_stem_path(B.STEM_AUTO) == B.MBU_OK
+    g = L.mbu_classifier_fp32
+    a, b = 0x50000, 0x60000
+    assert g(None, 1, 8, 8, 64, w, b, 19, o, None) == B.MBU_ERR_NULL
+    assert g(a, 1, 8, 8, 96, w, b, 19, o, None) == B.MBU_ERR_SHAPE
+    assert g(a, 1, 8, 8, 64, w, b, 33, o, None) == B.MBU_ERR_SHAPE
+    assert g(a, 1, 8, 8, 64, w, b + 4, 19, o, None) == B.MBU_ERR_ALIGN

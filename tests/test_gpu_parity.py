@@ -462,3 +462,124 @@ def test_unet_wide_batch8_full_size():
     zf = synth.cost_aware_zero_fractions(plan, 1024, 1024, 0.6)
     case = synth.unet_case(4, 0, 8, 1024, 1024, base=128, keeps=[1.0 - z for z in zf])
     check_unet_by_induction(case, 8, 1024, 1024, rows_per_layer=2)
+
+
+# ------------------------------------------------------------------------ float32 ends
+STEM_PATHS = [(B.STEM_VALU, "valu"), (B.STEM_MFMA, "mfma")]
+STEM_KAPPA = 2.0 ** -18      # the matrix path's documented error budget
+
+
+def _stem_norm_bound(image, w):
+    """||w_o||_2 * ||patch(n,y,x)||_2 for every output, float64 [N,H,W,Co]."""
+    x2 = torch.from_numpy(image.astype(np.float64) ** 2).sum(1, keepdim=True)
+    p2 = torch.nn.functional.conv2d(x2, torch.ones(1, 1, 3, 3, dtype=torch.float64), padding=1)
+    pn = np.sqrt(p2.numpy()[:, 0])                                    # [N,H,W]
+    wn = np.sqrt((w.astype(np.float64) ** 2).reshape(w.shape[0], -1).sum(1))
+    return pn[..., None] * wn[None, None, None, :]
+
+
+def check_stem(image, w, path, pname, label):
+    say(f"stem {label} path={pname} image={image.shape} Co={w.shape[0]}")
+    B.set_stem_path(path)
+    try:
+        bits, _ = B.stem_fp32(dev(image), dev(w))
+        bits2, pre = B.stem_fp32(dev(image), dev(w), want_pre=True)
+        torch.cuda.synchronize()
+    finally:
+        B.set_stem_path(B.STEM_AUTO)
+    ref_pre, ref_sgn = O.stem(image, w)
+    exp = bitref.pack_pm1(ref_sgn)
+    got, got2, pre = host_u32(bits), host_u32(bits2), host(pre)
+    assert np.array_equal(got, exp), f"{label}: {int((got != exp).sum())} packed words differ"
+    assert np.array_equal(got2, exp), f"{label}: bits differ when pre-activations are requested"
+    return pre, ref_pre
+
+
+STEM_SHAPES = [  # N, Ci, H, W, Co
+    (1, 3, 37, 45, 64), (2, 3, 64, 100, 64), (1, 1, 33, 70, 32), (1, 3, 130, 257, 128),
+    (3, 3, 16, 16, 96), (1, 3, 1, 1, 64), (1, 1, 2, 31, 64), (1, 3, 3, 32, 32),
+]
+
+
+@pytest.mark.parametrize("path,pname", STEM_PATHS)
+@pytest.mark.parametrize("shape", STEM_SHAPES)
+def test_stem_matches_oracle(shape, path, pname):
+    N, Ci, H, W, Co = shape
+    rng = np.random.default_rng([11, N, Ci, H, W, Co])
+    image = rng.standard_normal((N, Ci, H, W), dtype=np.float32)
+    w = rng.standard_normal((Co, 3, 3, Ci), dtype=np.float32)
+    pre, ref = check_stem(image, w, path, pname, "normal")
+    if path == B.STEM_VALU:
+        # same rounding sequence on both sides: the values themselves are identical, which
+        # more than meets the layer's stated accuracy of 1e-4 relative
+        assert np.array_equal(pre, ref)
+        assert (np.abs(pre - ref) <= 1e-4 * np.maximum(1.0, np.abs(ref))).all()
+    else:
+        err = np.abs(pre.astype(np.float64) - ref.astype(np.float64))
+        bound = STEM_KAPPA * _stem_norm_bound(image, w)
+        assert (err <= bound).all(), f"estimate outside its error budget, worst {float((err / bound).max()):.3f}"
+
+
+@pytest.mark.parametrize("path,pname", STEM_PATHS)
+def test_stem_degenerate_inputs(path, pname):
+    """Sums that are exactly zero or cancel almost completely, zero regions, extreme scales:
+    the cases in which only the sequential chain defines the sign."""
+    rng = np.random.default_rng(5)
+    H, W, Co = 40, 70, 64
+    # small integers: many sums are exactly 0 (tie -> +1) and all are exactly representable
+    img = rng.integers(-2, 3, size=(1, 3, H, W)).astype(np.float32)
+    w = rng.integers(-2, 3, size=(Co, 3, 3, 3)).astype(np.float32)
+    pre, ref = check_stem(img, w, path, pname, "integers")
+    assert (ref == 0).sum() > 1000 and np.array_equal(pre, ref)
+    # all-zero image, and an image with zero regions and signed zeros
+    check_stem(np.zeros((1, 3, H, W), np.float32), w, path, pname, "zero image")
+    img = rng.standard_normal((1, 3, H, W), dtype=np.float32)
+    img[:, :, 10:25, 20:50] = 0.0
+    img[:, :, 12:14, 22:40] = -0.0
+    check_stem(img, rng.standard_normal((Co, 3, 3, 3), dtype=np.float32), path, pname, "zero regions")
+    # nearly cancelling sums: two copies of a channel with opposite weights plus a tiny third
+    img = rng.standard_normal((1, 3, H, W), dtype=np.float32)
+    img[:, 1] = img[:, 0]
+    img[:, 2] *= np.float32(1e-7)
+    w = rng.standard_normal((Co, 3, 3, 3), dtype=np.float32)
+    w[..., 1] = -w[..., 0]
+    check_stem(img, w, path, pname, "cancellation")
+    # extreme but finite scales, mixed inside one image
+    for scale_i, scale_w in ((1e30, 1e-3), (1e-30, 1.0), (1e-25, 1e-20), (1e18, 1e18)):
+        img = rng.standard_normal((1, 3, H, W), dtype=np.float32) * np.float32(scale_i)
+        img[:, :, :, 35:] *= np.float32(1e-6)
+        w = rng.standard_normal((Co, 3, 3, 3), dtype=np.float32) * np.float32(scale_w)
+        check_stem(img, w, path, pname, f"scale {scale_i:g} x {scale_w:g}")
+    # non-finite pixels: the comparison "sum >= 0" is false for NaN on both sides
+    img = rng.standard_normal((1, 3, H, W), dtype=np.float32)
+    img[0, 1, 5, 7] = np.nan
+    img[0, 0, 20, 60] = np.inf
+    img[0, 2, 30, 3] = -np.inf
+    check_stem(img, rng.standard_normal((Co, 3, 3, 3), dtype=np.float32), path, pname, "non-finite")
+
+
+def test_stem_full_size_frame():
+    """All 134 M outputs of the benchmark frame's first layer against the oracle."""
+    case = synth.unet_case(3, 0, 1, 1024, 2048, keep=0.6)
+    pre, ref = check_stem(case.image, case.stem_w, B.STEM_MFMA, "mfma", "1024x2048")
+    err = np.abs(pre.astype(np.float64) - ref.astype(np.float64))
+    bound = STEM_KAPPA * _stem_norm_bound(case.image, case.stem_w)
+    worst = float((err / bound).max())
+    undecided = float((np.abs(pre) <= bound).mean())
+    say(f"stem 1024x2048: worst |estimate - chain| / budget = {worst:.3f}; "
+        f"fraction of outputs inside the budget (recomputed) <= {undecided:.2e}")
+    assert worst <= 1.0
+
+
+@pytest.mark.parametrize("shape", [(1, 9, 33, 32, 5), (2, 16, 40, 64, 19), (1, 7, 100, 128, 32),
+                                   (1, 64, 64, 64, 1)])
+def test_classifier_matches_oracle(shape):
+    N, H, W, C, K = shape
+    say(f"classifier {shape}")
+    rng = np.random.default_rng([12, N, H, W, C, K])
+    a = synth.pm1_bits(rng, (N, H, W, C))
+    w = (rng.standard_normal((K, C), dtype=np.float32) / np.float32(8.0))
+    b = rng.standard_normal((K,), dtype=np.float32)
+    got = host(B.classifier_fp32(B.pack_act(dev(a)), C, dev(w), dev(b)))
+    ref = O.classifier(a, w, b)
+    assert (np.abs(got - ref) <= 1e-4 * np.maximum(1.0, np.abs(ref))).all()
