@@ -182,14 +182,12 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
         }
     };
 
-    TilePos cur = tile_pos(slot, tstep.tiles_x, tstep.tiles_y);   // (tile in row, row, image)
-    Geo g = geometry(cur);
-    gather(cur, g);
-    for (int tl = slot; tl < ntiles; tl += nslots) {
-        // ---- split, norm, zero test
-        uint4 Bh[KT], Bm[KT], Bl[KT];
-        float n2 = 0.0f;
-        uint32_t orb = 0;
+    // split of the gathered values into the three bf16 operand planes, squared norm and
+    // OR of the bit patterns (zero test) of this lane's share of the patch
+    struct Planes { uint4 h[KT], m[KT], l[KT]; float n2; uint32_t orb; };
+    auto split = [&](Planes &P) {
+        P.n2 = 0.0f;
+        P.orb = 0;
 #pragma unroll
         for (int t = 0; t < KT; ++t) {
             uint32_t h4[4], m4[4], l4[4];
@@ -197,40 +195,100 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
             for (int d = 0; d < 4; ++d) {
                 const float a = v[8 * t + 2 * d], b = v[8 * t + 2 * d + 1];
                 split_pair(a, b, h4[d], m4[d], l4[d]);
-                n2 = __builtin_fmaf(a, a, n2);
-                n2 = __builtin_fmaf(b, b, n2);
-                orb |= __float_as_uint(a) | __float_as_uint(b);
+                P.n2 = __builtin_fmaf(a, a, P.n2);
+                P.n2 = __builtin_fmaf(b, b, P.n2);
+                P.orb |= __float_as_uint(a) | __float_as_uint(b);
             }
-            Bh[t] = make_uint4(h4[0], h4[1], h4[2], h4[3]);
-            Bm[t] = make_uint4(m4[0], m4[1], m4[2], m4[3]);
-            Bl[t] = make_uint4(l4[0], l4[1], l4[2], l4[3]);
+            P.h[t] = make_uint4(h4[0], h4[1], h4[2], h4[3]);
+            P.m[t] = make_uint4(m4[0], m4[1], m4[2], m4[3]);
+            P.l[t] = make_uint4(l4[0], l4[1], l4[2], l4[3]);
         }
+    };
 
-        // ---- the next tile's patch values (the wave's last tile simply fetches itself again)
-        TilePos nxt = cur;
-        if (tl + nslots < ntiles) nxt.advance(tstep);
-        const Geo gn = geometry(nxt);
-        gather(nxt, gn);
-
-        // ---- fast estimate on the matrix cores (small terms first)
-        // the two channel tiles alternate, so consecutive instructions never depend on each other
+    // Software pipeline over the wave's tiles: while the matrix instructions of tile i run,
+    // the vector ALU splits the (already loaded) values of tile i+1; then the loads of tile
+    // i+2 are issued and tile i's epilogue runs.  A wave's last tiles fetch themselves again.
+    TilePos cur = tile_pos(slot, tstep.tiles_x, tstep.tiles_y);   // (tile in row, row, image)
+    Geo g = geometry(cur);
+    gather(cur, g);
+    Planes B;
+    split(B);
+    TilePos nxt = cur;
+    if (slot + nslots < ntiles) nxt.advance(tstep);
+    Geo gn = geometry(nxt);
+    gather(nxt, gn);
+    for (int tl = slot; tl < ntiles; tl += nslots) {
+        // ---- fast estimate of tile i on the matrix cores (small terms first; the two channel
+        // tiles alternate, so consecutive instructions never depend on each other).  The split
+        // of tile i+1 is cut into 24 pieces of four or five vector instructions, one after each
+        // matrix instruction, which is what fits into its shadow; the scheduling fences and the
+        // empty statements that "use" each piece's results keep the interleaving as written.
         v16f acc[2];
 #pragma unroll
         for (int m = 0; m < 2; ++m)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[m][i] = 0.0f;
-#define MBU_STEM_MMA(WP, BP)                                                                         \
-    _Pragma("unroll") for (int t = 0; t < KT; ++t)                                                   \
-        _Pragma("unroll") for (int m = 0; m < 2; ++m)                                                \
-            acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_v8bf(WP[m][t]), as_v8bf(BP[t]), acc[m], 0, 0, 0)
-        MBU_STEM_MMA(Wl, Bh);
-        MBU_STEM_MMA(Wh, Bl);
-        MBU_STEM_MMA(Wm, Bm);
-        MBU_STEM_MMA(Wm, Bh);
-        MBU_STEM_MMA(Wh, Bm);
-        MBU_STEM_MMA(Wh, Bh);
-#undef MBU_STEM_MMA
+        Planes Bn;
+        Bn.n2 = 0.0f;
+        Bn.orb = 0;
+        uint32_t sh[NS / 2], sm[NS / 2], sl[NS / 2];   // packed pairs of the three planes
+        float r1[NS];                                  // remainders after the first term
+        int piece = 0;
+        auto mma = [&](const uint4 (&WP)[2][KT], const uint4 (&BP)[KT]) {
+#pragma unroll
+            for (int t = 0; t < KT; ++t)
+#pragma unroll
+                for (int m = 0; m < 2; ++m) {
+                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_v8bf(WP[m][t]), as_v8bf(BP[t]), acc[m], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    // piece = 3 * pair + stage
+                    const int p = piece / 3, st = piece % 3;
+                    if (p < NS / 2) {
+                        const float a = v[2 * p], b = v[2 * p + 1];
+                        if (st == 0) {          // first term and its remainder
+                            sh[p] = bf16_pair(a, b);
+                            r1[2 * p] = a - __uint_as_float(sh[p] << 16);
+                            r1[2 * p + 1] = b - __uint_as_float(sh[p] & 0xffff0000u);
+                            asm volatile("" : "+v"(sh[p]), "+v"(r1[2 * p]), "+v"(r1[2 * p + 1]));
+                        } else if (st == 1) {   // second term, third term = what is left (8 bits)
+                            sm[p] = bf16_pair(r1[2 * p], r1[2 * p + 1]);
+                            const float a2 = r1[2 * p] - __uint_as_float(sm[p] << 16);
+                            const float b2 = r1[2 * p + 1] - __uint_as_float(sm[p] & 0xffff0000u);
+                            sl[p] = __builtin_amdgcn_perm(__float_as_uint(b2), __float_as_uint(a2), 0x07060302u);
+                            asm volatile("" : "+v"(sm[p]), "+v"(sl[p]));
+                        } else {                // norm and zero test
+                            Bn.n2 = __builtin_fmaf(a, a, Bn.n2);
+                            Bn.n2 = __builtin_fmaf(b, b, Bn.n2);
+                            Bn.orb |= __float_as_uint(a) | __float_as_uint(b);
+                            asm volatile("" : "+v"(Bn.n2), "+v"(Bn.orb));
+                        }
+                    }
+                    ++piece;
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+        };
+        mma(Wl, B.h);
+        mma(Wh, B.l);
+        mma(Wm, B.m);
+        mma(Wm, B.h);
+        mma(Wh, B.m);
+        mma(Wh, B.h);
+        static_assert(3 * (NS / 2) <= 12 * KT, "one piece per matrix instruction");
+#pragma unroll
+        for (int t = 0; t < KT; ++t) {
+            Bn.h[t] = make_uint4(sh[4 * t], sh[4 * t + 1], sh[4 * t + 2], sh[4 * t + 3]);
+            Bn.m[t] = make_uint4(sm[4 * t], sm[4 * t + 1], sm[4 * t + 2], sm[4 * t + 3]);
+            Bn.l[t] = make_uint4(sl[4 * t], sl[4 * t + 1], sl[4 * t + 2], sl[4 * t + 3]);
+        }
 
+        // ---- loads of tile i+2
+        TilePos nn = nxt;
+        if (tl + 2 * nslots < ntiles) nn.advance(tstep);
+        const Geo gnn = geometry(nn);
+        gather(nn, gnn);
+
+        float n2 = B.n2;
+        uint32_t orb = B.orb;
         // ---- decision threshold of this pixel
         const int y = g.y, n = g.n, x = g.x, xc = g.xc;
         n2 = swap_add(n2);
@@ -327,8 +385,10 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
         if (zero) { sg[0] = 0u; sg[1] = 0u; }   // a chain of zero terms ends at +0.0f
         const uint32_t word = finish_word64(sg[0], sg[1], psel);
         if (x < W && widx < Cow) out[pix * Cow + widx] = word;
-        cur = nxt;
+        B = Bn;
         g = gn;
+        gn = gnn;
+        nxt = nn;
     }
 }
 
