@@ -93,117 +93,148 @@ int launch_stem_valu(const float *img, int N, int Ci, int H, int W, const float 
 // Classifier: logit[k] = b[k] + sum_c w[k][c] * a_c, a_c = +-1 from the packed bits.
 // The result only has to be accurate (not bit-reproducible), so the 1x1 convolution
 // runs on the matrix cores as a (classes x channels) x (channels x pixels) product in
-// bf16 with fp32 accumulation: +-1 is exact in bf16 and every fp32 weight is split
-// into three bf16 terms hi + mid + lo (24 mantissa bits in total), so the products are
-// exact and the only rounding is the fp32 accumulation.  The kernel is then bound by
-// the NCHW logits it has to write.
+// fp16 with fp32 accumulation: +-1 is exact in fp16; every class row of the weights is
+// scaled by a power of two into [0.5, 1) and split into two fp16 terms hi + lo (22
+// significand bits), so the products are exact and the only rounding is the fp32
+// accumulation; the scale is undone, and the bias added, by one fused multiply-add per
+// logit.  The kernel is then bound by the NCHW logits it has to write.
 //
-// v_mfma_f32_32x32x16_bf16: rows = classes (padded to 32), columns = 32 consecutive
+// v_mfma_f32_32x32x16_f16: rows = classes (padded to 32), columns = 32 consecutive
 // pixels, 16 channels per instruction, 8 per lane half.  The channel order inside an
-// instruction is free; it is chosen so that the two bf16 of a dword are channels p and
-// p+16 of a packed word: (word << (15-p)) & 0x80008000 | 0x3f803f80 is then the pair
+// instruction is free; it is chosen so that the two fp16 of a dword are channels p and
+// p+16 of a packed word: (word << (15-p)) & 0x80008000 | 0x3c003c00 is then the pair
 // (-a_p, -a_{p+16}), and the weights are stored negated to cancel the sign.
 typedef float v16f __attribute__((ext_vector_type(16)));
-typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 
-__device__ inline v8bf as_bf8(uint4 v) { return __builtin_bit_cast(v8bf, v); }
+__device__ inline v8h as_h8(uint4 v) { return __builtin_bit_cast(v8h, v); }
+
+__device__ inline uint32_t f16_pair(float lo, float hi)
+{
+    const _Float16 a = (_Float16)lo, b = (_Float16)hi;   // round to nearest even
+    return (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, b) << 16);
+}
 
 template <int CW>
-__global__ __launch_bounds__(256) void classifier_kernel(const uint32_t *__restrict__ act,
+__global__ __launch_bounds__(256, CW == 4 ? 2 : 3) void classifier_kernel(const uint32_t *__restrict__ act,
                                                          long pixels, long HW,
                                                          const float *__restrict__ w,
                                                          const float *__restrict__ b, int K,
                                                          float *__restrict__ out)
 {
     constexpr int C = 32 * CW;
+    constexpr int G = 2;          // pixel groups per iteration: independent accumulator chains
     const int lane = threadIdx.x & 63;
     const int col = lane & 31, half = lane >> 5;
     const int row = col;  // class index of this lane in the weight operand
+    const size_t rbase = (size_t)(row < K ? row : 0) * C;   // loads are unconditional (clamped row)
+
+    // power-of-two scale of this lane's class row: largest |weight| into [0.5, 1)
+    float mx = 0.0f;
+#pragma unroll 8
+    for (int c = 0; c < C; ++c) mx = fmaxf(mx, fabsf(w[rbase + c]));
+    int e = 0;
+    if (mx > 0.0f && mx < __builtin_inff()) (void)frexpf(mx, &e);
+    const float scale = ldexpf(1.0f, -e);
 
     // weight operand: instruction t = 2*wd + tp covers, in lane half h, dword d:
-    // low bf16 = channel 32*wd + 8*tp + 4*h + d, high bf16 = that + 16
-    uint4 wa[2 * CW][3];
+    // low fp16 = channel 32*wd + 8*tp + 4*h + d, high fp16 = that + 16
+    uint4 wa[2 * CW][2];
 #pragma unroll
     for (int t = 0; t < 2 * CW; ++t) {
-        uint32_t parts[3][4];
+        uint32_t hi4[4], lo4[4];
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
             const int clo = 32 * (t >> 1) + 8 * (t & 1) + 4 * half + d;
-            float v[2];
-            v[0] = row < K ? -w[(size_t)row * C + clo] : 0.0f;
-            v[1] = row < K ? -w[(size_t)row * C + clo + 16] : 0.0f;
-            uint32_t sp[2][3];
-#pragma unroll
-            for (int e = 0; e < 2; ++e) {
-                float r = v[e];
-#pragma unroll
-                for (int j = 0; j < 3; ++j) {
-                    const uint32_t top = __float_as_uint(r) & 0xffff0000u;  // truncated bf16
-                    sp[e][j] = top;
-                    r = r - __uint_as_float(top);                           // exact
-                }
-            }
-#pragma unroll
-            for (int j = 0; j < 3; ++j) parts[j][d] = (sp[0][j] >> 16) | sp[1][j];
+            const float w0 = w[rbase + clo], w1 = w[rbase + clo + 16];
+            const float v0 = row < K ? -w0 * scale : 0.0f;   // exact scaling
+            const float v1 = row < K ? -w1 * scale : 0.0f;
+            const _Float16 h0 = (_Float16)v0, h1 = (_Float16)v1;
+            hi4[d] = f16_pair(v0, v1);
+            lo4[d] = f16_pair(v0 - (float)h0, v1 - (float)h1);
         }
-#pragma unroll
-        for (int j = 0; j < 3; ++j)
-            wa[t][j] = make_uint4(parts[j][0], parts[j][1], parts[j][2], parts[j][3]);
+        wa[t][0] = make_uint4(hi4[0], hi4[1], hi4[2], hi4[3]);
+        wa[t][1] = make_uint4(lo4[0], lo4[1], lo4[2], lo4[3]);
     }
-    // accumulator register r of lane half h is class 8*(r/4) + 4*h + r%4
-    float bias[16];
+    // accumulator register r of lane half h is class 8*(r/4) + 4*h + r%4: its 1/scale and
+    // bias come from the lane that holds that class row
+    float mul[16], bias[16];
+    const float inv = ldexpf(1.0f, e);
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
         const int cls = 8 * (r >> 2) + 4 * half + (r & 3);
-        bias[r] = cls < K ? b[cls] : 0.0f;
+        const float bv = b[cls < K ? cls : 0];
+        bias[r] = cls < K ? bv : 0.0f;
+        mul[r] = __shfl(inv, cls);
     }
     const int sh = 4 - 4 * half;
     const long groups = (pixels + 31) / 32;
     const long wave_id = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
     const long n_waves = (long)gridDim.x * 4;
-    // the packed words of the wave's next pixel group are fetched while the current group is
-    // multiplied and stored
-    auto fetch = [&](long g, uint32_t (&wd)[CW]) {
-        const long pix = g * 32 + col;
-        const long pc = pix < pixels ? pix : pixels - 1;
+    const long stride = n_waves * G;
+    // The packed words of the wave's pixel groups are fetched two iterations ahead of their
+    // use, so that the loads fly during the matrix instructions and the stores of two others.
+    auto fetch = [&](long g0, uint32_t (&wd)[G][CW]) {
 #pragma unroll
-        for (int k = 0; k < CW; ++k) wd[k] = act[pc * CW + k];
+        for (int u = 0; u < G; ++u) {
+            const long pix = (g0 + u) * 32 + col;
+            const long pc = pix < pixels ? pix : pixels - 1;
+#pragma unroll
+            for (int k = 0; k < CW; ++k) wd[u][k] = act[pc * CW + k];
+        }
     };
-    uint32_t words[CW], next[CW];
-    if (wave_id < groups) fetch(wave_id, words);
-    for (long g = wave_id; g < groups; g += n_waves) {
-        const long gn = g + n_waves < groups ? g + n_waves : g;
-        fetch(gn, next);
-        const long pix = g * 32 + col;
-        const bool live = pix < pixels;
-        v16f acc;
+    uint32_t cur[G][CW], nx1[G][CW], nx2[G][CW];
+    const long first = wave_id * G;
+    if (first < groups) {
+        fetch(first, cur);
+        fetch(first + stride < groups ? first + stride : first, nx1);
+    }
+    for (long g0 = first; g0 < groups; g0 += stride) {
+        const long g2 = g0 + 2 * stride < groups ? g0 + 2 * stride : g0;
+        fetch(g2, nx2);
+        v16f acc[G];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] = bias[r];
+        for (int u = 0; u < G; ++u)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[u][r] = 0.0f;
 #pragma unroll
         for (int t = 0; t < 2 * CW; ++t) {
-            const uint32_t yv = words[t >> 1] << sh;
-            uint4 bv;
             const int base = 11 - 8 * (t & 1);
-            bv.x = ((yv << base) & 0x80008000u) | 0x3f803f80u;
-            bv.y = ((yv << (base - 1)) & 0x80008000u) | 0x3f803f80u;
-            bv.z = ((yv << (base - 2)) & 0x80008000u) | 0x3f803f80u;
-            bv.w = ((yv << (base - 3)) & 0x80008000u) | 0x3f803f80u;
 #pragma unroll
-            for (int j = 0; j < 3; ++j)
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_bf8(wa[t][j]), as_bf8(bv), acc, 0, 0, 0);
-        }
-        if (live) {
-            const long n = pix / HW, rem = pix - n * HW;
-            float *o = out + (size_t)n * K * HW + rem;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int cls = 8 * (r >> 2) + 4 * half + (r & 3);
-                // written once, never read by this library: keep it out of the caches
-                if (cls < K) __builtin_nontemporal_store(acc[r], o + (size_t)cls * HW);
+            for (int u = 0; u < G; ++u) {
+                const uint32_t yv = cur[u][t >> 1] << sh;
+                uint4 bv;
+                bv.x = ((yv << base) & 0x80008000u) | 0x3c003c00u;
+                bv.y = ((yv << (base - 1)) & 0x80008000u) | 0x3c003c00u;
+                bv.z = ((yv << (base - 2)) & 0x80008000u) | 0x3c003c00u;
+                bv.w = ((yv << (base - 3)) & 0x80008000u) | 0x3c003c00u;
+                acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_h8(wa[t][1]), as_h8(bv), acc[u], 0, 0, 0);
+                acc[u] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_h8(wa[t][0]), as_h8(bv), acc[u], 0, 0, 0);
             }
         }
 #pragma unroll
-        for (int k = 0; k < CW; ++k) words[k] = next[k];
+        for (int u = 0; u < G; ++u) {
+            const long pix = (g0 + u) * 32 + col;
+            if (pix < pixels) {
+                const long n = pix / HW, rem = pix - n * HW;
+                float *o = out + (size_t)n * K * HW + rem;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int cls = 8 * (r >> 2) + 4 * half + (r & 3);
+                    // written once, never read by this library: keep it out of the caches
+                    if (cls < K)
+                        __builtin_nontemporal_store(__builtin_fmaf(acc[u][r], mul[r], bias[r]),
+                                                    o + (size_t)cls * HW);
+                }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < G; ++u)
+#pragma unroll
+            for (int k = 0; k < CW; ++k) {
+                cur[u][k] = nx1[u][k];
+                nx1[u][k] = nx2[u][k];
+            }
     }
 }
 
@@ -213,8 +244,9 @@ int launch_classifier(const uint32_t *act, int N, int H, int W, int C, const flo
     long HW = (long)H * W, pixels = (long)N * HW;
     if (K > 32) return fail(MBU_ERR_SHAPE, "classifier supports at most 32 classes, got %d", K);
     long groups = (pixels + 31) / 32;
-    // enough waves to fill the chip, several pixel groups per wave to amortise the weights
-    unsigned blocks = (unsigned)min((groups + 3) / 4, (long)2048);
+    // all waves resident at once (three per SIMD, two for 128 channels), many pixel groups per
+    // wave to amortise splitting the weights
+    unsigned blocks = (unsigned)min((groups + 7) / 8, (long)(C == 128 ? 512 : 768));
     switch (C / 32) {
     case 1: MBU_LAUNCH(classifier_kernel<1>, dim3(blocks), dim3(256), 0, s, act, pixels, HW, w, b, K, out); break;
     case 2: MBU_LAUNCH(classifier_kernel<2>, dim3(blocks), dim3(256), 0, s, act, pixels, HW, w, b, K, out); break;
