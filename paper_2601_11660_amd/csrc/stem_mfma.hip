@@ -164,8 +164,7 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
         g.pb = (uint32_t)((((size_t)g.n * CI * H + g.y) * W + g.xc) * 4);
         return g;
     };
-    float v[NS];
-    auto gather = [&](const TilePos &tp, const Geo &g) {
+    auto gather = [&](const TilePos &tp, const Geo &g, float (&v)[NS]) {
         const bool interior = g.y > 0 && g.y < H - 1 && tp.tx > 0 && tp.tx * 32 + 32 < W;
         if (interior) {
 #pragma unroll
@@ -185,7 +184,7 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
     // split of the gathered values into the three bf16 operand planes, squared norm and
     // OR of the bit patterns (zero test) of this lane's share of the patch
     struct Planes { uint4 h[KT], m[KT], l[KT]; float n2; uint32_t orb; };
-    auto split = [&](Planes &P) {
+    auto split = [&](Planes &P, const float (&v)[NS]) {
         P.n2 = 0.0f;
         P.orb = 0;
 #pragma unroll
@@ -205,92 +204,45 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
         }
     };
 
-    // Software pipeline over the wave's tiles: while the matrix instructions of tile i run,
-    // the vector ALU splits the (already loaded) values of tile i+1; then the loads of tile
-    // i+2 are issued and tile i's epilogue runs.  A wave's last tiles fetch themselves again.
-    TilePos cur = tile_pos(slot, tstep.tiles_x, tstep.tiles_y);   // (tile in row, row, image)
-    Geo g = geometry(cur);
-    gather(cur, g);
-    Planes B;
-    split(B);
-    TilePos nxt = cur;
-    if (slot + nslots < ntiles) nxt.advance(tstep);
-    Geo gn = geometry(nxt);
-    gather(nxt, gn);
-    for (int tl = slot; tl < ntiles; tl += nslots) {
-        // ---- fast estimate of tile i on the matrix cores (small terms first; the two channel
-        // tiles alternate, so consecutive instructions never depend on each other).  The split
-        // of tile i+1 is cut into 24 pieces of four or five vector instructions, one after each
-        // matrix instruction, which is what fits into its shadow; the scheduling fences and the
-        // empty statements that "use" each piece's results keep the interleaving as written.
+    // One tile: split its (already loaded) patch values, re-use their registers for the loads
+    // of the tile after next, run the matrix instructions, decide and store.  Two sets of
+    // load registers alternate, so every load has almost two tile times to arrive.
+    TilePos ahead = tile_pos(slot, tstep.tiles_x, tstep.tiles_y);   // (tile in row, row, image)
+    int tl_ahead = slot;                                           // tile index `ahead` stands for
+    auto advance_ahead = [&]() {                                   // a wave's last tiles fetch themselves again
+        if (tl_ahead + nslots < ntiles) { ahead.advance(tstep); tl_ahead += nslots; }
+    };
+    auto tile = [&](float (&v)[NS], Geo &g) {
+        Planes B;
+        split(B, v);
+        const Geo gcur = g;
+        advance_ahead();
+        g = geometry(ahead);
+        gather(ahead, g, v);
+
+        // ---- fast estimate on the matrix cores (small terms first; the two channel tiles
+        // alternate, so consecutive instructions never depend on each other)
         v16f acc[2];
 #pragma unroll
         for (int m = 0; m < 2; ++m)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[m][i] = 0.0f;
-        Planes Bn;
-        Bn.n2 = 0.0f;
-        Bn.orb = 0;
-        uint32_t sh[NS / 2], sm[NS / 2], sl[NS / 2];   // packed pairs of the three planes
-        float r1[NS];                                  // remainders after the first term
-        int piece = 0;
-        auto mma = [&](const uint4 (&WP)[2][KT], const uint4 (&BP)[KT]) {
-#pragma unroll
-            for (int t = 0; t < KT; ++t)
-#pragma unroll
-                for (int m = 0; m < 2; ++m) {
-                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_v8bf(WP[m][t]), as_v8bf(BP[t]), acc[m], 0, 0, 0);
-                    __builtin_amdgcn_sched_barrier(0);
-                    // piece = 3 * pair + stage
-                    const int p = piece / 3, st = piece % 3;
-                    if (p < NS / 2) {
-                        const float a = v[2 * p], b = v[2 * p + 1];
-                        if (st == 0) {          // first term and its remainder
-                            sh[p] = bf16_pair(a, b);
-                            r1[2 * p] = a - __uint_as_float(sh[p] << 16);
-                            r1[2 * p + 1] = b - __uint_as_float(sh[p] & 0xffff0000u);
-                            asm volatile("" : "+v"(sh[p]), "+v"(r1[2 * p]), "+v"(r1[2 * p + 1]));
-                        } else if (st == 1) {   // second term, third term = what is left (8 bits)
-                            sm[p] = bf16_pair(r1[2 * p], r1[2 * p + 1]);
-                            const float a2 = r1[2 * p] - __uint_as_float(sm[p] << 16);
-                            const float b2 = r1[2 * p + 1] - __uint_as_float(sm[p] & 0xffff0000u);
-                            sl[p] = __builtin_amdgcn_perm(__float_as_uint(b2), __float_as_uint(a2), 0x07060302u);
-                            asm volatile("" : "+v"(sm[p]), "+v"(sl[p]));
-                        } else {                // norm and zero test
-                            Bn.n2 = __builtin_fmaf(a, a, Bn.n2);
-                            Bn.n2 = __builtin_fmaf(b, b, Bn.n2);
-                            Bn.orb |= __float_as_uint(a) | __float_as_uint(b);
-                            asm volatile("" : "+v"(Bn.n2), "+v"(Bn.orb));
-                        }
-                    }
-                    ++piece;
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-        };
-        mma(Wl, B.h);
-        mma(Wh, B.l);
-        mma(Wm, B.m);
-        mma(Wm, B.h);
-        mma(Wh, B.m);
-        mma(Wh, B.h);
-        static_assert(3 * (NS / 2) <= 12 * KT, "one piece per matrix instruction");
-#pragma unroll
-        for (int t = 0; t < KT; ++t) {
-            Bn.h[t] = make_uint4(sh[4 * t], sh[4 * t + 1], sh[4 * t + 2], sh[4 * t + 3]);
-            Bn.m[t] = make_uint4(sm[4 * t], sm[4 * t + 1], sm[4 * t + 2], sm[4 * t + 3]);
-            Bn.l[t] = make_uint4(sl[4 * t], sl[4 * t + 1], sl[4 * t + 2], sl[4 * t + 3]);
-        }
-
-        // ---- loads of tile i+2
-        TilePos nn = nxt;
-        if (tl + 2 * nslots < ntiles) nn.advance(tstep);
-        const Geo gnn = geometry(nn);
-        gather(nn, gnn);
+#define MBU_STEM_MMA(WP, BP)                                                                         \
+    _Pragma("unroll") for (int t = 0; t < KT; ++t)                                                   \
+        _Pragma("unroll") for (int m = 0; m < 2; ++m)                                                \
+            acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_v8bf(WP[m][t]), as_v8bf(B.BP[t]), acc[m], 0, 0, 0)
+        MBU_STEM_MMA(Wl, h);
+        MBU_STEM_MMA(Wh, l);
+        MBU_STEM_MMA(Wm, m);
+        MBU_STEM_MMA(Wm, h);
+        MBU_STEM_MMA(Wh, m);
+        MBU_STEM_MMA(Wh, h);
+#undef MBU_STEM_MMA
 
         float n2 = B.n2;
         uint32_t orb = B.orb;
         // ---- decision threshold of this pixel
-        const int y = g.y, n = g.n, x = g.x, xc = g.xc;
+        const int y = gcur.y, n = gcur.n, x = gcur.x, xc = gcur.xc;
         n2 = swap_add(n2);
         {
             const auto sw = __builtin_amdgcn_permlane32_swap(orb, orb, false, false);
@@ -351,7 +303,7 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
                     const int ky = tap / 3, kx = tap - 3 * ky;
                     const bool ok = !((ky == 0 && y == 0) || (ky == 2 && y == H - 1) ||
                                       (kx == 0 && xc == 0) || (kx == 2 && xc == W - 1));
-                    const uint32_t o = g.pb + (uint32_t)(((long)ci * H * W + (long)(ky - 1) * W + (kx - 1)) * 4);
+                    const uint32_t o = gcur.pb + (uint32_t)(((long)ci * H * W + (long)(ky - 1) * W + (kx - 1)) * 4);
                     pv[k] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, ok ? o : OOB, 0, 0));
                     okm |= (ok ? 1u : 0u) << k;
                 }
@@ -385,10 +337,17 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
         if (zero) { sg[0] = 0u; sg[1] = 0u; }   // a chain of zero terms ends at +0.0f
         const uint32_t word = finish_word64(sg[0], sg[1], psel);
         if (x < W && widx < Cow) out[pix * Cow + widx] = word;
-        B = Bn;
-        g = gn;
-        gn = gnn;
-        nxt = nn;
+    };
+
+    float va[NS], vb[NS];
+    Geo ga = geometry(ahead), gb;
+    gather(ahead, ga, va);
+    advance_ahead();
+    gb = geometry(ahead);
+    gather(ahead, gb, vb);
+    for (int tl = slot; tl < ntiles; tl += 2 * nslots) {
+        tile(va, ga);
+        if (tl + nslots < ntiles) tile(vb, gb);
     }
 }
 
