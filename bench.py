@@ -95,22 +95,24 @@ def time_layer(B, torch, act, cin, blob, cout, theta, iters=10, warm=2):
 
 def conv_sweep(B, torch, synth):
     rows = []
-    for C in (64, 128, 256, 512):
-        for keep in (0.3, 0.5, 0.7):
-            case = synth.conv_case(1, 0, 1, 512, 512, C, C, keep)
-            act = B.pack_act(torch.from_numpy(case.a).cuda())
-            blob = B.pack_weights(torch.from_numpy(case.w).cuda())
-            th = torch.from_numpy(case.theta).cuda()
-            ops = 2.0 * synth.conv_macs(1, 512, 512, C, C)
-            row = {"C": C, "keep": keep}
-            for name, path in (("mfma", B.PATH_MFMA), ("valu", B.PATH_VALU)):
-                B.set_conv_path(path)
-                ms = time_layer(B, torch, act, C, blob, C, th)
-                row[f"{name}_gops"] = round(ops / ms / 1e6, 1)
-                peak = PEAK_FP4_TFLOPS if name == "mfma" else PEAK_VALU_BIT_TOPS
-                row[f"{name}_frac"] = round(ops / ms / 1e9 / peak, 4)
-            rows.append(row)
-            del act, blob, th
+    # the twelve shapes of the layer sweep, plus one pure-binary layer (no zero weights):
+    # on the matrix path it is the masked layer with an empty mask and costs the same
+    shapes = [(C, keep) for C in (64, 128, 256, 512) for keep in (0.3, 0.5, 0.7)] + [(256, 1.0)]
+    for C, keep in shapes:
+        case = synth.conv_case(1, 0, 1, 512, 512, C, C, keep)
+        act = B.pack_act(torch.from_numpy(case.a).cuda())
+        blob = B.pack_weights(torch.from_numpy(case.w).cuda())
+        th = torch.from_numpy(case.theta).cuda()
+        ops = 2.0 * synth.conv_macs(1, 512, 512, C, C)
+        row = {"C": C, "keep": keep}
+        for name, path in (("mfma", B.PATH_MFMA), ("valu", B.PATH_VALU)):
+            B.set_conv_path(path)
+            ms = time_layer(B, torch, act, C, blob, C, th)
+            row[f"{name}_gops"] = round(ops / ms / 1e6, 1)
+            peak = PEAK_FP4_TFLOPS if name == "mfma" else PEAK_VALU_BIT_TOPS
+            row[f"{name}_frac"] = round(ops / ms / 1e9 / peak, 4)
+        rows.append(row)
+        del act, blob, th
     B.set_conv_path(B.PATH_AUTO)
     return rows
 
@@ -185,6 +187,37 @@ def transposed_decoder(B, torch, synth, steps):
     conv_macs = synth.unet_conv_macs(case.plan, n, h, w)
     return {"frames_per_s": round(1e3 / ms, 1), "ms_per_step": round(ms, 4),
             "conv3x3_macs_per_frame": conv_macs, "transposed_layers": ups}
+
+
+def paper_shapes(B, torch, synth, steps):
+    """The paper's own inference shapes (Appendix A.3: Carvana 959x640 padded to 960x640, ISIC
+    640x480, Nuclei 512x512; binary segmentation, batched) on the network with the paper's
+    transposed decoder, synthetic inputs: images/s."""
+    rows = []
+    n = 8
+    for name, h, w in (("carvana-like", 640, 960), ("isic-like", 480, 640), ("nuclei-like", 512, 512)):
+        case = synth.unet_case(7, 0, n, h, w, keep=0.6, transposed=True, n_classes=2)
+
+        def dev(a):
+            return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+        net = B.UNet(dev(case.stem_w), [(dev(wt), dev(t)) for wt, t in case.convs], dev(case.cls_w),
+                     dev(case.cls_b), levels=4, up_convs=[(dev(wt), dev(t)) for wt, t in case.up_convs])
+        image = dev(case.image)
+        logits = torch.empty((n, case.n_classes, h, w), dtype=torch.float32, device="cuda")
+        for _ in range(2):
+            net.forward(image, logits)
+        e0, e1 = B.Event(), B.Event()
+        e0.record()
+        for _ in range(steps):
+            net.forward(image, logits)
+        e1.record()
+        ms = e0.elapsed_ms(e1) / steps
+        rows.append({"workload": f"{name} {n}x3x{h}x{w}, 2 classes, transposed decoder",
+                     "ms_per_batch": round(ms, 3), "images_per_s": round(n * 1e3 / ms, 1)})
+        del net, image, logits, case
+        torch.cuda.empty_cache()
+    return rows
 
 
 def cpu_baseline(synth):
@@ -336,6 +369,7 @@ def main():
     if not args.no_sweep:
         out["conv_sweep"] = conv_sweep(B, torch, synth)
         out["transposed_decoder"] = transposed_decoder(B, torch, synth, K)
+        out["paper_shapes"] = paper_shapes(B, torch, synth, 5)
         out["wide_batch8"] = wide_batch(B, torch, synth,
                                         (0.2, 0.4, 0.6, 0.8) if args.sparsity_sweep else (0.6,))
     out["cpu_baseline"] = None if args.no_cpu else cpu_baseline(synth)

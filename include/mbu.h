@@ -211,6 +211,27 @@ int mbu_stem_fp32(const float *image_nchw, int N, int Ci, int H, int W, const fl
 int mbu_classifier_fp32(const uint32_t *act, int N, int H, int W, int C, const float *w,
                         const float *b, int K, float *logits_nchw, void *stream);
 
+/* Folds batch norm, bias and the binary activation that follow a masked-binary layer into the
+ * integer threshold of Algorithm 1 (Sec. 3.2.2: the threshold covers batch norm, bias and the
+ * binary activation).  HOST function, all pointers are host arrays of C entries.
+ *   bit = ( gamma[c] * (acc + bias[c] - mean[c]) / sqrt(var[c] + eps) + beta[c] >= 0 )
+ * is rewritten as (acc' >= thresh[c]) with acc' = acc, or acc' = -acc where flip[c] = 1 (negative
+ * gamma): the caller negates the weights of those output channels before mbu_pack_weights.
+ *   bias     NULL = no bias;  fan_in = largest |acc| (9 * Cin for the 3x3 layer), <= 2^22
+ *   thresh   int32 [C], clamped to +-(fan_in + 1) (a constant bit for gamma = 0);  flip int8 [C]
+ * Errors: NULL arrays, non-positive C / fan_in, non-finite parameters, var + eps <= 0. */
+int mbu_fold_batchnorm(const double *gamma, const double *beta, const double *mean,
+                       const double *var, double eps, const double *bias, int C, int fan_in,
+                       int32_t *thresh, int8_t *flip);
+
+/* Cost-aware masking priority (Sec. 3.1.2): score[l] = w_op * ops^[l] + (1 - w_op) * params^[l],
+ * both counts min-max normalised to [0, 1] over the L layers; `order` lists the layer indices by
+ * ascending score (the order in which layers are switched from binary to masked weights; ties
+ * keep the lower index first).  HOST function, host arrays.
+ * Errors: NULL arrays, L <= 0, w_op outside [0, 1], negative or non-finite counts. */
+int mbu_cost_rank(const double *n_ops, const double *n_params, int L, double w_op, double *score,
+                  int *order);
+
 /* One masked-binary layer of the network: host struct, device pointers inside. */
 typedef struct mbu_conv_layer {
     const void *packed_w;    /* blob from mbu_pack_weights(cout, cin)  */

@@ -206,3 +206,30 @@ def unet_forward(image, stem_w, convs, cls_w, cls_b, levels=4, up_convs=None):
         x = double_conv(x, f"dec{l}")
     logits = classifier(x, cls_w, cls_b)
     return logits, taps
+
+
+def batchnorm_sign(acc, gamma, beta, mean, var, eps, bias=None):
+    """What the integer threshold of Algorithm 1 stands for (Sec. 3.2.2: it covers batch norm,
+    bias and the binary activation): the layer's integer sums go through bias, inference-mode
+    batch norm and the sign activation, all in float64, channel = last axis.
+    Returns (y float64, +-1 int8 with y >= 0 -> +1)."""
+    acc = np.asarray(acc, dtype=np.float64)
+    g, b, m, v = (np.asarray(t, dtype=np.float64) for t in (gamma, beta, mean, var))
+    z = acc if bias is None else acc + np.asarray(bias, dtype=np.float64)
+    y = g * (z - m) / np.sqrt(v + eps) + b
+    return y, np.where(y >= 0, 1, -1).astype(np.int8)
+
+
+def cost_scores(n_ops, n_params, w_op):
+    """Weighted cost score of every layer (Sec. 3.1.2): w_op * ops^ + (1 - w_op) * params^
+    with the operation and parameter counts scaled to [0, 1] over the layers (smallest count
+    -> 0, largest -> 1).  Returns (scores, indices by ascending score; ties by index)."""
+    o = np.asarray(n_ops, dtype=np.float64)
+    p = np.asarray(n_params, dtype=np.float64)
+
+    def unit(v):
+        span = v.max() - v.min()
+        return (v - v.min()) / span if span > 0 else np.zeros_like(v)
+
+    s = w_op * unit(o) + (1.0 - w_op) * unit(p)
+    return s, np.argsort(s, kind="stable")

@@ -22,6 +22,7 @@ STEM_AUTO, STEM_VALU, STEM_MFMA = 0, 1, 2
 EXPORTS = [
     "mbu_last_error", "mbu_set_conv_path", "mbu_get_conv_path", "mbu_set_conv_tuning", "mbu_pack_act",
     "mbu_set_stem_path", "mbu_get_stem_path", "mbu_stem_fp32", "mbu_classifier_fp32",
+    "mbu_fold_batchnorm", "mbu_cost_rank",
     "mbu_packed_weights_bytes", "mbu_pack_weights", "mbu_conv3x3_masked_binary",
     "mbu_conv3x3_masked_binary_fused", "mbu_conv3x3_masked_binary_concat",
     "mbu_packed_tconv_weights_bytes", "mbu_pack_tconv_weights", "mbu_tconv2x2_masked_binary",
@@ -75,6 +76,10 @@ def lib() -> ctypes.CDLL:
         L.mbu_tconv2x2_masked_binary.argtypes = [vp, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp]
         L.mbu_stem_fp32.argtypes = [vp, ci, ci, ci, ci, vp, ci, vp, vp, vp]
         L.mbu_classifier_fp32.argtypes = [vp, ci, ci, ci, ci, vp, vp, ci, vp, vp]
+        dp = ctypes.POINTER(ctypes.c_double)
+        L.mbu_fold_batchnorm.argtypes = [dp, dp, dp, dp, ctypes.c_double, dp, ci, ci,
+                                         ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int8)]
+        L.mbu_cost_rank.argtypes = [dp, dp, ci, ctypes.c_double, dp, ctypes.POINTER(ci)]
         L.mbu_maxpool2x2_bits.argtypes = [vp, ci, ci, ci, ci, vp, vp]
         L.mbu_upsample2x_bits.argtypes = [vp, ci, ci, ci, ci, vp, vp]
         L.mbu_concat_bits.argtypes = [vp, ci, vp, ci, ci, ci, ci, vp, vp]
@@ -162,6 +167,44 @@ def classifier_fp32(act: torch.Tensor, c: int, w: torch.Tensor, b: torch.Tensor)
     check(lib().mbu_classifier_fp32(_dev(act, (torch.int32,)), N, H, W, c, _dev(w, (torch.float32,)),
                                     _dev(b, (torch.float32,)), K, out.data_ptr(), _stream()))
     return out
+
+
+def fold_batchnorm(gamma, beta, mean, var, eps: float, bias, fan_in: int):
+    """mbu_fold_batchnorm on host arrays -> (int32 thresholds, int8 flip flags) as numpy arrays."""
+    import numpy as np
+
+    def arr(a):
+        return np.ascontiguousarray(a, dtype=np.float64)
+
+    g, b, m, v = arr(gamma), arr(beta), arr(mean), arr(var)
+    C = g.shape[0]
+    bs = arr(bias) if bias is not None else None
+    thresh = np.empty(C, np.int32)
+    flip = np.empty(C, np.int8)
+    dp = ctypes.POINTER(ctypes.c_double)
+
+    def ptr(a):
+        return a.ctypes.data_as(dp)
+
+    check(lib().mbu_fold_batchnorm(ptr(g), ptr(b), ptr(m), ptr(v), float(eps),
+                                   ptr(bs) if bs is not None else None, C, int(fan_in),
+                                   thresh.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                   flip.ctypes.data_as(ctypes.POINTER(ctypes.c_int8))))
+    return thresh, flip
+
+
+def cost_rank(n_ops, n_params, w_op: float = 0.5):
+    """mbu_cost_rank on host arrays -> (scores float64, order int32) as numpy arrays."""
+    import numpy as np
+    o = np.ascontiguousarray(n_ops, dtype=np.float64)
+    p = np.ascontiguousarray(n_params, dtype=np.float64)
+    L = o.shape[0]
+    score = np.empty(L, np.float64)
+    order = np.empty(L, np.int32)
+    dp = ctypes.POINTER(ctypes.c_double)
+    check(lib().mbu_cost_rank(o.ctypes.data_as(dp), p.ctypes.data_as(dp), L, float(w_op),
+                              score.ctypes.data_as(dp), order.ctypes.data_as(ctypes.POINTER(ctypes.c_int))))
+    return score, order
 
 
 # Packed words are stored in int32 tensors (same bits as the ABI's uint32).

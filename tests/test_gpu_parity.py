@@ -583,3 +583,51 @@ def test_classifier_matches_oracle(shape):
     got = host(B.classifier_fp32(B.pack_act(dev(a)), C, dev(w), dev(b)))
     ref = O.classifier(a, w, b)
     assert (np.abs(got - ref) <= 1e-4 * np.maximum(1.0, np.abs(ref))).all()
+
+
+# ------------------------------------------------------------- deployment flow around the layer
+@pytest.mark.parametrize("shape", [(1, 20, 40, 64, 96), (2, 9, 33, 160, 64)])
+def test_layer_with_folded_batchnorm(shape):
+    """Batch norm + bias + sign after the layer (Sec. 3.2.2) folded into integer thresholds by
+    the library, channels with a negative scale handled by negating their weights: the GPU
+    layer's bits against the oracle's convolution followed by float64 batch norm and sign."""
+    N, H, W, Cin, Cout = shape
+    say(f"folded batch norm {shape}")
+    case = synth.conv_case(8, 0, N, H, W, Cin, Cout, 0.5)
+    rng = np.random.default_rng([14, Cin, Cout])
+    g = rng.standard_normal(Cout)
+    g[3::11] = 0.0
+    beta = rng.standard_normal(Cout)
+    mean = rng.standard_normal(Cout) * 6
+    var = rng.uniform(0.5, 60.0, Cout)
+    bias = rng.standard_normal(Cout)
+    eps = 1e-5
+    thresh, flip = B.fold_batchnorm(g, beta, mean, var, eps, bias, 9 * Cin)
+    assert flip.sum() > 0 and (flip == 0).sum() > 0
+    w_dev = np.where(flip[:, None, None, None] != 0, -case.w, case.w).astype(np.int8)
+    bits, _ = B.conv3x3_masked_binary(B.pack_act(dev(case.a)), Cin, B.pack_weights(dev(w_dev)), Cout,
+                                      dev(thresh))
+    torch.cuda.synchronize()
+    acc = O.conv3x3(case.a, case.w)
+    y, s = O.batchnorm_sign(acc, g, beta, mean, var, eps, bias)
+    got = bitref.unpack_pm1(host_u32(bits), Cout)
+    sure = np.abs(y) > 1e-9
+    assert sure.mean() > 0.999 and np.array_equal(got[sure], s[sure])
+
+
+def test_unet_with_cost_ranked_binary_and_masked_layers():
+    """The deployment of Sec. 3.1.2 / 3.2.1: layers are masked in ascending cost-score order,
+    the rest stay pure binary (no zero weights); every layer of the mixed network is bit-exact.
+    On the matrix path a binary layer is the masked layer with an empty mask."""
+    say("unet with cost-ranked masked layers")
+    N, H, W = 1, 64, 96
+    plan = synth.unet_channel_plan(64, 3)
+    ops = [2.0 * (H >> (lv - 1)) * (W >> (lv - 1)) * 9 * ci * co for _, ci, co, lv in plan]
+    par = [9.0 * ci * co for _, ci, co, _ in plan]
+    _, order = B.cost_rank(ops, par, 0.5)
+    masked = set(order[:len(plan) // 2].tolist())          # the cheaper half gets the zero state
+    keeps = [0.5 if i in masked else 1.0 for i in range(len(plan))]
+    case = synth.unet_case(9, 0, N, H, W, base=64, levels=3, keeps=keeps)
+    for i, (wt, _) in enumerate(case.convs):
+        assert ((wt == 0).any()) == (i in masked)
+    compare_unet_all_taps(case, N, H, W, True)

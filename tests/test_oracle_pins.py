@@ -428,3 +428,61 @@ def test_unet_with_transposed_decoder_matches_torch():
     shapes = {n: v.shape for n, v in taps}
     assert shapes["up2"] == (1, 8, 16, 64) and shapes["cat2"] == (1, 8, 16, 128)
     assert shapes["cat1"] == (1, 16, 32, 64)
+
+
+# ------------------------------------------------------------ threshold folding, cost ranking
+def test_batchnorm_sign_against_torch_and_closed_forms():
+    """Pins of the oracle's batch norm + sign step (what Algorithm 1's threshold stands for,
+    Sec. 3.2.2): the library routine in float64, and hand-solvable cases."""
+    rng = np.random.default_rng(21)
+    C = 24
+    acc = rng.integers(-300, 301, size=(2, 5, 7, C))
+    g = rng.standard_normal(C)
+    b = rng.standard_normal(C) * 3
+    m = rng.standard_normal(C) * 20
+    v = rng.uniform(0.5, 40.0, C)
+    bias = rng.standard_normal(C)
+    y, s = O.batchnorm_sign(acc, g, b, m, v, 1e-5, bias)
+    x = torch.from_numpy((acc + bias).astype(np.float64)).permute(0, 3, 1, 2)
+    ref = F.batch_norm(x, torch.from_numpy(m), torch.from_numpy(v), torch.from_numpy(g),
+                       torch.from_numpy(b), training=False, eps=1e-5).permute(0, 2, 3, 1).numpy()
+    assert np.allclose(y, ref, rtol=1e-12, atol=1e-12)
+    assert np.array_equal(s, np.where(ref >= 0, 1, -1))
+    # identity batch norm: the bit is (acc + bias >= 0); a tie gives +1
+    one, zero = np.ones(3), np.zeros(3)
+    _, s = O.batchnorm_sign(np.array([[-1, 0, 1]]), one, zero, zero, one, 0.0, np.array([0.0, 0.0, -1.0]))
+    assert s.tolist() == [[-1, 1, 1]]
+    # a negative scale reverses the comparison, a zero scale leaves the sign of beta
+    _, s = O.batchnorm_sign(np.array([[5, 5, 5]]), np.array([-1.0, 0.0, 0.0]), np.array([0.0, -2.0, 2.0]),
+                            zero, one, 0.0)
+    assert s.tolist() == [[-1, -1, 1]]
+
+
+def test_cost_scores_properties():
+    """Sec. 3.1.2's score: range, weights, order."""
+    rng = np.random.default_rng(23)
+    ops = rng.uniform(1e6, 1e11, 12)
+    par = rng.uniform(1e3, 1e7, 12)
+    for w_op in (0.0, 0.3, 0.5, 1.0):
+        s, order = O.cost_scores(ops, par, w_op)
+        assert s.min() >= 0 and s.max() <= 1 and (np.diff(s[order]) >= 0).all()
+    # w_op = 1 ranks by operations alone, w_op = 0 by parameters alone
+    assert np.array_equal(O.cost_scores(ops, par, 1.0)[1], np.argsort(ops, kind="stable"))
+    assert np.array_equal(O.cost_scores(ops, par, 0.0)[1], np.argsort(par, kind="stable"))
+    # the cheapest layer in both counts scores 0, the dearest in both scores 1
+    s, _ = O.cost_scores([1, 5, 9], [2, 3, 7], 0.25)
+    assert s[0] == 0.0 and s[2] == 1.0 and abs(s[1] - (0.25 * 0.5 + 0.75 * 0.2)) < 1e-15
+    # the paper's observation (Sec. 3.1.2): grouped as its twelve configurable layers (double
+    # convolutions, transposed convolutions), the transposed layers of a U-Net cost far fewer
+    # operations than the others and therefore head the priority list
+    plan = synth.unet_channel_plan(64, 4, transposed=True)
+    h = w = 512
+    conv_ops = [2.0 * (h >> (lv - 1)) * (w >> (lv - 1)) * 9 * ci * co for _, ci, co, lv in plan]
+    conv_par = [9.0 * ci * co for _, ci, co, _ in plan]
+    pairs = [(conv_ops[i] + conv_ops[i + 1], conv_par[i] + conv_par[i + 1]) for i in range(2, len(plan), 2)]
+    ups = [(2.0 * (h >> l) * (w >> l) * (128 << l) * (64 << l), 4.0 * (128 << l) * (64 << l))
+           for l in range(4)]                       # up1..up4: one tap per output pixel
+    layers = pairs + ups
+    _, order = O.cost_scores([o for o, _ in layers], [p for _, p in layers], 1.0)
+    assert set(order[:4].tolist()) == set(range(len(pairs), len(pairs) + 4))
+    assert 5 * max(o for o, _ in ups) <= min(o for o, _ in pairs)
