@@ -214,17 +214,33 @@ __global__ __launch_bounds__(256, CW == 4 ? 2 : 3) void classifier_kernel(const 
         }
 #pragma unroll
         for (int u = 0; u < G; ++u) {
-            const long pix = (g0 + u) * 32 + col;
-            if (pix < pixels) {
-                const long n = pix / HW, rem = pix - n * HW;
-                float *o = out + (size_t)n * K * HW + rem;
+            // Addressing with one wave-uniform base per class and one 32-bit offset per lane:
+            // the image of the group's first pixel gives the base (scalar arithmetic); a lane
+            // whose pixel lies in a later image adds whole images to its offset.
+            const long gp = (g0 + u) * 32;                         // first pixel of the group
+            if (gp >= pixels) break;
+            const long n0 = gp / HW;
+            const long rem0 = gp - n0 * HW;
+            long rel = rem0 + col;                                  // pixel relative to image n0
+            long off = rel;
+            if (rem0 + 31 >= HW) {                                  // the group crosses an image border
+                const long dn = rel / HW;
+                off = dn * K * HW + (rel - dn * HW);
+            }
+            const bool live = gp + col < pixels;
+            float *base = out + (size_t)n0 * K * HW;               // uniform
+            const uint32_t lane_off = (uint32_t)(off + (long)(4 * half) * HW);   // class 4*half folded in
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int cls = 8 * (r >> 2) + 4 * half + (r & 3);
-                    // written once, never read by this library: keep it out of the caches
-                    if (cls < K)
-                        __builtin_nontemporal_store(__builtin_fmaf(acc[u][r], mul[r], bias[r]),
-                                                    o + (size_t)cls * HW);
+            for (int q = 0; q < 4; ++q) {
+                if (live && 8 * q + 4 * half < K) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const int r = 4 * q + j;
+                        // written once, never read by this library: keep it out of the caches
+                        if (8 * q + 4 * half + j < K)
+                            __builtin_nontemporal_store(__builtin_fmaf(acc[u][r], mul[r], bias[r]),
+                                                        base + (size_t)(8 * q + j) * HW + lane_off);
+                    }
                 }
             }
         }
@@ -243,6 +259,9 @@ int launch_classifier(const uint32_t *act, int N, int H, int W, int C, const flo
 {
     long HW = (long)H * W, pixels = (long)N * HW;
     if (K > 32) return fail(MBU_ERR_SHAPE, "classifier supports at most 32 classes, got %d", K);
+    // a lane's offset from its group's image base must fit 32 bits
+    if ((double)(K + 5) * (double)HW * 4.0 >= 4294967296.0)
+        return fail(MBU_ERR_SHAPE, "classifier: image too large (%ld pixels, %d classes)", HW, K);
     long groups = (pixels + 31) / 32;
     // all waves resident at once (three per SIMD, two for 128 channels), many pixel groups per
     // wave to amortise splitting the weights

@@ -572,7 +572,8 @@ def test_stem_full_size_frame():
 
 
 @pytest.mark.parametrize("shape", [(1, 9, 33, 32, 5), (2, 16, 40, 64, 19), (1, 7, 100, 128, 32),
-                                   (1, 64, 64, 64, 1)])
+                                   (1, 64, 64, 64, 1),
+                                   (3, 5, 7, 64, 19), (4, 3, 5, 32, 3), (5, 1, 1, 64, 19)])   # 32-pixel groups across images
 def test_classifier_matches_oracle(shape):
     N, H, W, C, K = shape
     say(f"classifier {shape}")
