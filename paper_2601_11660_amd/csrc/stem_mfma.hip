@@ -204,40 +204,82 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
         }
     };
 
-    // One tile: split its (already loaded) patch values, re-use their registers for the loads
-    // of the tile after next, run the matrix instructions, decide and store.  Two sets of
-    // load registers alternate, so every load has almost two tile times to arrive.
+    // One tile: issue the loads of the tile after next, run the matrix instructions of the
+    // current tile (operand planes Bc) with the split of the next tile's values (vs -> Bn) cut
+    // into pieces of four or five vector instructions, one after each matrix instruction -
+    // vector work is hidden only between matrix instructions of the same wave - then decide
+    // and store.  Two sets of load registers and two sets of operand planes alternate.
     TilePos ahead = tile_pos(slot, tstep.tiles_x, tstep.tiles_y);   // (tile in row, row, image)
     int tl_ahead = slot;                                           // tile index `ahead` stands for
     auto advance_ahead = [&]() {                                   // a wave's last tiles fetch themselves again
         if (tl_ahead + nslots < ntiles) { ahead.advance(tstep); tl_ahead += nslots; }
     };
-    auto tile = [&](float (&v)[NS], Geo &g) {
-        Planes B;
-        split(B, v);
-        const Geo gcur = g;
+    auto tile = [&](const Planes &B, Planes &Bn, float (&vs)[NS], float (&vl)[NS], const TilePos &pcur) {
         advance_ahead();
-        g = geometry(ahead);
-        gather(ahead, g, v);
+        gather(ahead, geometry(ahead), vl);
+        const Geo gcur = geometry(pcur);
 
-        // ---- fast estimate on the matrix cores (small terms first; the two channel tiles
-        // alternate, so consecutive instructions never depend on each other)
+        // (the empty statements pin the loaded values to this iteration and "use" each piece's
+        // results, so that the pieces stay between the matrix instructions as written)
+#pragma unroll
+        for (int s = 0; s < NS; ++s) asm volatile("" : "+v"(vs[s]));
         v16f acc[2];
 #pragma unroll
         for (int m = 0; m < 2; ++m)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[m][i] = 0.0f;
-#define MBU_STEM_MMA(WP, BP)                                                                         \
-    _Pragma("unroll") for (int t = 0; t < KT; ++t)                                                   \
-        _Pragma("unroll") for (int m = 0; m < 2; ++m)                                                \
-            acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_v8bf(WP[m][t]), as_v8bf(B.BP[t]), acc[m], 0, 0, 0)
-        MBU_STEM_MMA(Wl, h);
-        MBU_STEM_MMA(Wh, l);
-        MBU_STEM_MMA(Wm, m);
-        MBU_STEM_MMA(Wm, h);
-        MBU_STEM_MMA(Wh, m);
-        MBU_STEM_MMA(Wh, h);
-#undef MBU_STEM_MMA
+        Bn.n2 = 0.0f;
+        Bn.orb = 0;
+        uint32_t sh[NS / 2], sm[NS / 2], sl[NS / 2];   // packed pairs of the three planes
+        float r1[NS];                                  // remainders after the first term
+        int piece = 0;
+        auto mma = [&](const uint4 (&WP)[2][KT], const uint4 (&BP)[KT]) {
+#pragma unroll
+            for (int t = 0; t < KT; ++t)
+#pragma unroll
+                for (int m = 0; m < 2; ++m) {
+                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_v8bf(WP[m][t]), as_v8bf(BP[t]), acc[m], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    const int p = piece / 3, st = piece % 3;   // piece = 3 * pair + stage
+                    if (p < NS / 2) {
+                        const float a = vs[2 * p], b = vs[2 * p + 1];
+                        if (st == 0) {          // first term and its remainder
+                            sh[p] = bf16_pair(a, b);
+                            r1[2 * p] = a - __uint_as_float(sh[p] << 16);
+                            r1[2 * p + 1] = b - __uint_as_float(sh[p] & 0xffff0000u);
+                            asm volatile("" : "+v"(sh[p]), "+v"(r1[2 * p]), "+v"(r1[2 * p + 1]));
+                        } else if (st == 1) {   // second term; the third is what is left (8 bits)
+                            sm[p] = bf16_pair(r1[2 * p], r1[2 * p + 1]);
+                            const float a2 = r1[2 * p] - __uint_as_float(sm[p] << 16);
+                            const float b2 = r1[2 * p + 1] - __uint_as_float(sm[p] & 0xffff0000u);
+                            sl[p] = __builtin_amdgcn_perm(__float_as_uint(b2), __float_as_uint(a2), 0x07060302u);
+                            asm volatile("" : "+v"(sm[p]), "+v"(sl[p]));
+                        } else {                // norm and zero test
+                            Bn.n2 = __builtin_fmaf(a, a, Bn.n2);
+                            Bn.n2 = __builtin_fmaf(b, b, Bn.n2);
+                            Bn.orb |= __float_as_uint(a) | __float_as_uint(b);
+                            asm volatile("" : "+v"(Bn.n2), "+v"(Bn.orb));
+                        }
+                    }
+                    ++piece;
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+        };
+        // small terms first; the two channel tiles alternate, so consecutive matrix
+        // instructions never depend on each other
+        mma(Wl, B.h);
+        mma(Wh, B.l);
+        mma(Wm, B.m);
+        mma(Wm, B.h);
+        mma(Wh, B.m);
+        mma(Wh, B.h);
+        static_assert(3 * (NS / 2) <= 12 * KT, "one piece per matrix instruction");
+#pragma unroll
+        for (int t = 0; t < KT; ++t) {
+            Bn.h[t] = make_uint4(sh[4 * t], sh[4 * t + 1], sh[4 * t + 2], sh[4 * t + 3]);
+            Bn.m[t] = make_uint4(sm[4 * t], sm[4 * t + 1], sm[4 * t + 2], sm[4 * t + 3]);
+            Bn.l[t] = make_uint4(sl[4 * t], sl[4 * t + 1], sl[4 * t + 2], sl[4 * t + 3]);
+        }
 
         float n2 = B.n2;
         uint32_t orb = B.orb;
@@ -293,40 +335,45 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
         if (__builtin_amdgcn_ballot_w64(flag) != 0) {
             if (WRITE_PRE) __builtin_amdgcn_s_waitcnt(0);   // the estimates are stored before the corrections
             if (flag) {
-                // the whole patch of this pixel, in the order of the sum; a tap outside the
-                // image is skipped, as in the definition
-                float pv[KV];
-                uint32_t okm = 0;
+                // which outputs are undecided
+                uint32_t fl[2];
 #pragma unroll
-                for (int k = 0; k < KV; ++k) {
-                    const int tap = k / CI, ci = k - tap * CI;
-                    const int ky = tap / 3, kx = tap - 3 * ky;
-                    const bool ok = !((ky == 0 && y == 0) || (ky == 2 && y == H - 1) ||
-                                      (kx == 0 && xc == 0) || (kx == 2 && xc == W - 1));
-                    const uint32_t o = gcur.pb + (uint32_t)(((long)ci * H * W + (long)(ky - 1) * W + (kx - 1)) * 4);
-                    pv[k] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, ok ? o : OOB, 0, 0));
-                    okm |= (ok ? 1u : 0u) << k;
+                for (int m = 0; m < 2; ++m) {
+                    fl[m] = 0;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        fl[m] |= (!(__builtin_fabsf(acc[m][i]) > T) ? 1u : 0u) << i;
+                    if (chunk * 64 + m * 32 + 16 * half >= Co) fl[m] = 0;
                 }
 #pragma unroll
                 for (int m = 0; m < 2; ++m) {
-                    uint32_t fl = 0;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        fl |= (!(__builtin_fabsf(acc[m][i]) > T) ? 1u : 0u) << i;
                     const int cb = chunk * 64 + m * 32 + 16 * half;
-                    if (cb >= Co) fl = 0;
-                    while (fl) {
-                        const int i = __builtin_ctz(fl);
-                        fl &= fl - 1;
+                    while (fl[m]) {
+                        const int i = __builtin_ctz(fl[m]);
+                        fl[m] &= fl[m] - 1;
                         const float *wp = w + (size_t)(cb + i) * KV;
-                        float wv[KV];
-#pragma unroll
-                        for (int k = 0; k < KV; ++k) wv[k] = wp[k];
+                        // the sum in its defined order, one kernel row (3 * CI terms) at a time;
+                        // a tap outside the image is skipped, as in the definition
                         float s = 0.0f;
 #pragma unroll
-                        for (int k = 0; k < KV; ++k) {
-                            const float f = __builtin_fmaf(wv[k], pv[k], s);
-                            s = ((okm >> k) & 1u) ? f : s;
+                        for (int ky = 0; ky < 3; ++ky) {
+                            float pv[3 * CI], wv[3 * CI];
+                            uint32_t okm = 0;
+#pragma unroll
+                            for (int e = 0; e < 3 * CI; ++e) {
+                                const int kx = e / CI, ci = e - kx * CI;
+                                const bool ok = !((ky == 0 && y == 0) || (ky == 2 && y == H - 1) ||
+                                                  (kx == 0 && xc == 0) || (kx == 2 && xc == W - 1));
+                                const uint32_t o = gcur.pb + (uint32_t)(((long)ci * H * W + (long)(ky - 1) * W + (kx - 1)) * 4);
+                                pv[e] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, ok ? o : OOB, 0, 0));
+                                wv[e] = wp[ky * 3 * CI + e];
+                                okm |= (ok ? 1u : 0u) << e;
+                            }
+#pragma unroll
+                            for (int e = 0; e < 3 * CI; ++e) {
+                                const float f = __builtin_fmaf(wv[e], pv[e], s);
+                                s = ((okm >> e) & 1u) ? f : s;
+                            }
                         }
                         sg[m] = (sg[m] & ~(1u << i)) | ((s >= 0.0f ? 0u : 1u) << i);   // NaN -> bit 0
                         if (WRITE_PRE) pre[pix * Co + cb + i] = s;
@@ -340,14 +387,21 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
     };
 
     float va[NS], vb[NS];
-    Geo ga = geometry(ahead), gb;
-    gather(ahead, ga, va);
+    Planes B0, B1;
+    TilePos p0 = ahead;
+    gather(p0, geometry(p0), va);
+    split(B0, va);
     advance_ahead();
-    gb = geometry(ahead);
-    gather(ahead, gb, vb);
+    TilePos p1 = ahead;
+    gather(p1, geometry(p1), va);
     for (int tl = slot; tl < ntiles; tl += 2 * nslots) {
-        tile(va, ga);
-        if (tl + nslots < ntiles) tile(vb, gb);
+        tile(B0, B1, va, vb, p0);
+        p0 = p1;
+        p1 = ahead;
+        if (tl + nslots >= ntiles) break;
+        tile(B1, B0, vb, va, p0);
+        p0 = p1;
+        p1 = ahead;
     }
 }
 
