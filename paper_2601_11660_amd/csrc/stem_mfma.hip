@@ -6,64 +6,70 @@
 // Only the SIGN of y leaves this layer, and the sign of a sum is known without the exact
 // rounding sequence whenever a cheaper estimate is further from zero than its own error:
 //
-//   fast estimate  every float is the exact sum v = vh + vm + vl of three bf16 terms (8 + 8 + 8
-//                  significand bits); yf = sum of the six products wh*xh, wh*xm, wm*xh,
-//                  wh*xl, wl*xh, wm*xm on v_mfma_f32_32x32x16_bf16 (bf16 products are
-//                  exact in the fp32 accumulator; the three dropped products are below
-//                  2^-25 |w x|);
-//   error budget   |yf - y| <= kappa * ||w_o||_2 * ||x_patch||_2 covers the dropped
-//                  products, the accumulation rounding of the matrix instruction and the
-//                  rounding of the sequential chain itself (27 * 2^-24), all relative to
-//                  sum |w||x| <= ||w||_2 ||x||_2;
+//   scaling        the sign of y[o, p] does not change when the weights of output channel o and
+//                  the patch of pixel p are each multiplied by a positive power of two, so
+//                  every weight row and every patch is scaled (exactly) to a Euclidean norm
+//                  in [2^12, 2^13): whatever the magnitudes of the inputs, fp16 then neither
+//                  overflows (values < 2^13) nor loses more than 2^-25 absolute per value to
+//                  its subnormal range (2^-37 of the norm; 2^-26 of it if subnormal inputs
+//                  were flushed);
+//   fast estimate  every scaled float is split into two fp16 terms v = vh + vl + r, both
+//                  rounded to nearest, |r| <= 2^-22 |v|; yf = sum wh*xh + wh*xl + wl*xh on
+//                  v_mfma_f32_32x32x16_f16 (fp16 products are exact in the fp32 accumulator);
+//   error budget   |yf - y| <= kappa * ||w_o||_2 * ||x_patch||_2 (in scaled units) covers the
+//                  dropped terms (3 * 2^-22 = 7e-7), the accumulation rounding of the matrix
+//                  instruction and the rounding of the sequential chain itself
+//                  (27 * 2^-24 = 1.6e-6), all relative to sum |w||x| <= ||w||_2 ||x||_2;
 //   decision       |yf| >  T = kappa * max_o ||w_o|| * ||x_patch||  ->  sign(y) = sign(yf);
-//                  otherwise the output is recomputed by the sequential chain itself.
+//                  otherwise the output is recomputed by the sequential chain itself, on the
+//                  unscaled float32 inputs.
 //
 // About 1 output in 10^5 takes the second route with normally distributed data, so the
-// layer costs 24 matrix instructions per 32 pixels x 64 channels instead of 64 x 27 fused
-// multiply-adds per pixel.  Non-finite inputs, and norms outside [2^-60, 2^60] (where bf16
-// terms could be flushed or products overflow), make T infinite and send every affected
-// output down the sequential route; an all-zero patch gives +0.0f without any arithmetic.
+// layer costs 12 matrix instructions per 32 pixels x 64 channels instead of 64 x 27 fused
+// multiply-adds per pixel.  Non-finite inputs, and norms outside [2^-60, 2^60], make T
+// infinite and send every affected output down the sequential route; an all-zero patch gives
+// +0.0f without any arithmetic.
 //
 // GEMM view: D[channel][pixel] = sum_k Wt[channel][k] * X[k][pixel], k = (ky*3 + kx)*Ci + ci
 // (the memory order of the weights), padded to KT*16.  A wave owns 64 output channels
-// (two 32-row tiles, weights split once and kept in registers) and walks over tiles of
-// 32 consecutive pixels of an image row.  Lane (column j, half h) gathers the patch values
-// k = 16t + 8h + i of pixel x0 + j through a raw buffer resource - a border tap or a padded
-// k gets an offset beyond the buffer and reads 0.0f.
+// (two 32-row tiles, weights scaled and split once and kept in registers) and walks over
+// tiles of 32 consecutive pixels of an image row.  Lane (column j, half h) gathers the patch
+// values k = 16t + 8h + i of pixel x0 + j through a raw buffer resource - a border tap or a
+// padded k gets an offset beyond the buffer and reads 0.0f.
 #include "mbu_internal.h"
 #include "mfma_common.h"
 
 namespace mbu {
 
-typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
-typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 v2h __attribute__((ext_vector_type(2)));
 typedef float v2f __attribute__((ext_vector_type(2)));
 
 // Error budget of the fast estimate relative to ||w||_2 ||x||_2 (see the header comment):
-// sequential chain 27 * 2^-24 = 1.6e-6, dropped products 3e-8, matrix accumulation measured
-// below 5e-7; 2^-18 = 3.8e-6 leaves a factor of almost two.
+// sequential chain 27 * 2^-24 = 1.6e-6, dropped terms 7e-7, matrix accumulation measured
+// below 5e-7; 2^-18 = 3.8e-6.
 constexpr float STEM_KAPPA = 0x1p-18f;
 constexpr uint32_t OOB = 0x80000000u;   // byte offset beyond any accepted image
 
-__device__ __forceinline__ uint32_t bf16_pair(float a, float b)
+// (a, b) -> packed fp16 pairs hi and lo with v = hi + lo + r, |r| <= 2^-22 |v| (+ 2^-25):
+// both conversions round to nearest and the remainder is computed without error
+__device__ __forceinline__ void split_pair(float a, float b, uint32_t &hi, uint32_t &lo)
 {
     const v2f f = {a, b};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, v2bf));   // low half = a
+    const v2h h = __builtin_convertvector(f, v2h);
+    const v2f r = f - __builtin_convertvector(h, v2f);
+    hi = __builtin_bit_cast(uint32_t, h);                                   // low half = a
+    lo = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, v2h));
 }
 
-// (a, b) -> packed bf16 pairs hi, mid, lo with v = hi + mid + lo exactly: each rounding to
-// nearest leaves a remainder of at most 16, then 8 significant bits, and the remainders are
-// computed without error
-__device__ __forceinline__ void split_pair(float a, float b, uint32_t &hi, uint32_t &mid, uint32_t &lo)
+// the power of two that brings a norm in [2^-60, 2^60] into [2^12, 2^13)
+__device__ __forceinline__ float norm_scale(float nrm)
 {
-    hi = bf16_pair(a, b);
-    const float a1 = a - __uint_as_float(hi << 16), b1 = b - __uint_as_float(hi & 0xffff0000u);
-    mid = bf16_pair(a1, b1);
-    const float a2 = a1 - __uint_as_float(mid << 16), b2 = b1 - __uint_as_float(mid & 0xffff0000u);
-    lo = __builtin_amdgcn_perm(__float_as_uint(b2), __float_as_uint(a2), 0x07060302u);   // already bf16
+    const uint32_t e = (__float_as_uint(nrm) >> 23) & 0xffu;               // nrm in [2^(e-127), 2^(e-126))
+    return __uint_as_float((266u - e) << 23);                              // 2^(12 - (e - 127))
 }
 
-__device__ __forceinline__ v8bf as_v8bf(const uint4 &v) { return __builtin_bit_cast(v8bf, v); }
+__device__ __forceinline__ v8h as_v8h(const uint4 &v) { return __builtin_bit_cast(v8h, v); }
 
 __device__ __forceinline__ float swap_add(float v)
 {
@@ -91,42 +97,47 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
     const int col = lane & 31, half = lane >> 5;
     const bool tile1 = chunk * 64 + 32 < Co;   // second 32-channel tile exists (Co % 32 == 0)
 
-    // ---- weights of this wave: split once, kept in registers; row norms for the bound
-    uint4 Wh[2][KT], Wm[2][KT], Wl[2][KT];
-    uint32_t rb = 0;   // bit pattern of the largest ||w_row||^2 seen (see below)
+    // ---- weights of this wave: every row scaled to a norm in [2^12, 2^13), split once, kept
+    // in registers.  The lane holds half of the K range of row `col` of both channel tiles.
+    uint4 Wh[2][KT], Wl[2][KT];
+    float row_unscale[2];   // 1 / scale of this lane's row (exact), for the diagnostic output
+    uint32_t rb = 0;        // bit pattern of the largest scaled row norm (see below)
+    bool w_sane = true;     // every row norm is finite and inside [2^-60, 2^60], or exactly 0
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
         const int ch = chunk * 64 + m * 32 + tile_row_to_channel(col);
+        float v[NS];
         float part = 0.0f;
 #pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            const int k = 16 * (s >> 3) + 8 * half + (s & 7);
+            const bool ok = ch < Co && k < KV;
+            const float wv = w[ok ? (size_t)ch * KV + k : 0];   // unconditional load
+            v[s] = ok ? wv : 0.0f;
+            part = __builtin_fmaf(v[s], v[s], part);
+        }
+        const float nrm = __builtin_sqrtf(swap_add(part));      // both halves: ||w_row||_2
+        const bool in_range = nrm >= 0x1p-60f && nrm <= 0x1p60f;
+        if (!(in_range || nrm == 0.0f)) w_sane = false;
+        const float sc = in_range ? norm_scale(nrm) : 1.0f;
+        row_unscale[m] = 1.0f / sc;
+        rb = max(rb, __float_as_uint(nrm * sc));
+#pragma unroll
         for (int t = 0; t < KT; ++t) {
-            float v[8];
+            uint32_t h4[4], l4[4];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int k = 16 * t + 8 * half + i;
-                const bool ok = ch < Co && k < KV;
-                const float wv = w[ok ? (size_t)ch * KV + k : 0];   // unconditional load
-                v[i] = ok ? wv : 0.0f;
-                part = __builtin_fmaf(v[i], v[i], part);
-            }
-            uint32_t h4[4], m4[4], l4[4];
-#pragma unroll
-            for (int d = 0; d < 4; ++d) split_pair(v[2 * d], v[2 * d + 1], h4[d], m4[d], l4[d]);
+            for (int d = 0; d < 4; ++d)
+                split_pair(v[8 * t + 2 * d] * sc, v[8 * t + 2 * d + 1] * sc, h4[d], l4[d]);
             Wh[m][t] = make_uint4(h4[0], h4[1], h4[2], h4[3]);
-            Wm[m][t] = make_uint4(m4[0], m4[1], m4[2], m4[3]);
             Wl[m][t] = make_uint4(l4[0], l4[1], l4[2], l4[3]);
         }
-        part = swap_add(part);                          // both halves: ||w_row||^2
-        rb = max(rb, __float_as_uint(part));
     }
-    // wave maximum of the row norms: the unsigned order of the bit patterns of non-negative
-    // floats is their numeric order, with +inf and every NaN on top, so a non-finite weight
-    // survives the reduction and poisons the bound below
+    // wave maximum of the scaled row norms (unsigned order of the bit patterns of non-negative
+    // floats is their numeric order) and wave-wide sanity of the rows
 #pragma unroll
     for (int o = 16; o >= 1; o >>= 1) rb = max(rb, (uint32_t)__shfl_xor((int)rb, o));
-    const float Wn = __builtin_sqrtf(__uint_as_float(rb));
-    // outside this range (or NaN) bf16 terms may be flushed or products may overflow: no bound
-    const bool w_sane = Wn >= 0x1p-60f && Wn <= 0x1p60f;
+    const float Wn = __uint_as_float(rb);
+    w_sane = __builtin_amdgcn_ballot_w64(!w_sane) == 0;
 
     // ---- per-lane table of the NS gathered patch values: byte offset from the pixel and
     // which border makes the tap fall outside the image
@@ -152,9 +163,7 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
     const int Cow = Co >> 5;
     const uint32_t psel = half ? 0x07060302u : 0x05040100u;
     const int widx = chunk * 2 + half;
-    // geometry of a tile for this lane, and the gather of its patch values (0.0f outside the
-    // image): issued one tile ahead, so the loads of the next tile fly during the matrix
-    // instructions and the epilogue of the current one
+    // geometry of a tile for this lane, and the gather of its patch values (0.0f outside the image)
     struct Geo { int y, n, x, xc; uint32_t pb; };
     auto geometry = [&](const TilePos &tp) {
         Geo g;
@@ -181,34 +190,56 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
         }
     };
 
-    // split of the gathered values into the three bf16 operand planes, squared norm and
-    // OR of the bit patterns (zero test) of this lane's share of the patch
-    struct Planes { uint4 h[KT], m[KT], l[KT]; float n2; uint32_t orb; };
-    auto split = [&](Planes &P, const float (&v)[NS]) {
-        P.n2 = 0.0f;
-        P.orb = 0;
+    // The operand planes of a tile: its patch values scaled to norm [2^12, 2^13) and split;
+    // nx = scaled norm of the pixel's patch (0 for an all-zero patch, +inf when there is no
+    // bound: non-finite or extreme values).  Built in pieces (see `tile`).
+    struct Planes { uint4 h[KT], l[KT]; float nx, sc; };
+    struct SplitState { float n2; uint32_t orb; float sc; };
+    constexpr int NPIECE = 4 + NS / 2;
+    auto split_piece = [&](int p, const float (&v)[NS], SplitState &st, Planes &P, uint32_t (&sh)[NS / 2],
+                           uint32_t (&sl)[NS / 2]) {
+        if (p == 0) {                       // squared norm of this lane's share, first half
+            st.n2 = 0.0f;
+#pragma unroll
+            for (int s = 0; s < NS / 2; ++s) st.n2 = __builtin_fmaf(v[s], v[s], st.n2);
+            asm volatile("" : "+v"(st.n2));
+        } else if (p == 1) {                // ... second half
+#pragma unroll
+            for (int s = NS / 2; s < NS; ++s) st.n2 = __builtin_fmaf(v[s], v[s], st.n2);
+            asm volatile("" : "+v"(st.n2));
+        } else if (p == 2) {                // OR of the bit patterns: exact test for an all-zero patch
+            st.orb = 0;
+#pragma unroll
+            for (int s = 0; s < NS; ++s) st.orb |= __float_as_uint(v[s]);
+            asm volatile("" : "+v"(st.orb));
+        } else if (p == 3) {                // both halves of the patch; the patch's scale
+            const float nrm = __builtin_sqrtf(swap_add(st.n2));
+            const auto sw = __builtin_amdgcn_permlane32_swap(st.orb, st.orb, false, false);
+            const bool zero = ((sw[0] | sw[1]) << 1) == 0;
+            const bool in_range = nrm >= 0x1p-60f && nrm <= 0x1p60f;
+            st.sc = in_range ? norm_scale(nrm) : 1.0f;
+            P.nx = zero ? 0.0f : (in_range ? nrm * st.sc : __builtin_inff());
+            P.sc = st.sc;
+            asm volatile("" : "+v"(st.sc), "+v"(P.nx));
+        } else {                            // one pair of values: scale, split
+            const int q = p - 4;
+            split_pair(v[2 * q] * st.sc, v[2 * q + 1] * st.sc, sh[q], sl[q]);
+            asm volatile("" : "+v"(sh[q]), "+v"(sl[q]));
+        }
+    };
+    auto finish_planes = [&](Planes &P, const uint32_t (&sh)[NS / 2], const uint32_t (&sl)[NS / 2]) {
 #pragma unroll
         for (int t = 0; t < KT; ++t) {
-            uint32_t h4[4], m4[4], l4[4];
-#pragma unroll
-            for (int d = 0; d < 4; ++d) {
-                const float a = v[8 * t + 2 * d], b = v[8 * t + 2 * d + 1];
-                split_pair(a, b, h4[d], m4[d], l4[d]);
-                P.n2 = __builtin_fmaf(a, a, P.n2);
-                P.n2 = __builtin_fmaf(b, b, P.n2);
-                P.orb |= __float_as_uint(a) | __float_as_uint(b);
-            }
-            P.h[t] = make_uint4(h4[0], h4[1], h4[2], h4[3]);
-            P.m[t] = make_uint4(m4[0], m4[1], m4[2], m4[3]);
-            P.l[t] = make_uint4(l4[0], l4[1], l4[2], l4[3]);
+            P.h[t] = make_uint4(sh[4 * t], sh[4 * t + 1], sh[4 * t + 2], sh[4 * t + 3]);
+            P.l[t] = make_uint4(sl[4 * t], sl[4 * t + 1], sl[4 * t + 2], sl[4 * t + 3]);
         }
     };
 
     // One tile: issue the loads of the tile after next, run the matrix instructions of the
-    // current tile (operand planes Bc) with the split of the next tile's values (vs -> Bn) cut
-    // into pieces of four or five vector instructions, one after each matrix instruction -
-    // vector work is hidden only between matrix instructions of the same wave - then decide
-    // and store.  Two sets of load registers and two sets of operand planes alternate.
+    // current tile (operand planes B) with the scaling and split of the next tile's values
+    // (vs -> Bn) cut into pieces, one after each matrix instruction - vector work is hidden only
+    // between matrix instructions of the same wave - then decide and store.  Two sets of load
+    // registers and two sets of operand planes alternate.
     TilePos ahead = tile_pos(slot, tstep.tiles_x, tstep.tiles_y);   // (tile in row, row, image)
     int tl_ahead = slot;                                           // tile index `ahead` stands for
     auto advance_ahead = [&]() {                                   // a wave's last tiles fetch themselves again
@@ -228,40 +259,20 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
         for (int m = 0; m < 2; ++m)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[m][i] = 0.0f;
-        Bn.n2 = 0.0f;
-        Bn.orb = 0;
-        uint32_t sh[NS / 2], sm[NS / 2], sl[NS / 2];   // packed pairs of the three planes
-        float r1[NS];                                  // remainders after the first term
-        int piece = 0;
+        SplitState st;
+        uint32_t sh[NS / 2], sl[NS / 2];
+        int piece = 0, issued = 0;
         auto mma = [&](const uint4 (&WP)[2][KT], const uint4 (&BP)[KT]) {
 #pragma unroll
             for (int t = 0; t < KT; ++t)
 #pragma unroll
                 for (int m = 0; m < 2; ++m) {
-                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_v8bf(WP[m][t]), as_v8bf(BP[t]), acc[m], 0, 0, 0);
+                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_v8h(WP[m][t]), as_v8h(BP[t]), acc[m], 0, 0, 0);
+                    ++issued;
                     __builtin_amdgcn_sched_barrier(0);
-                    const int p = piece / 3, st = piece % 3;   // piece = 3 * pair + stage
-                    if (p < NS / 2) {
-                        const float a = vs[2 * p], b = vs[2 * p + 1];
-                        if (st == 0) {          // first term and its remainder
-                            sh[p] = bf16_pair(a, b);
-                            r1[2 * p] = a - __uint_as_float(sh[p] << 16);
-                            r1[2 * p + 1] = b - __uint_as_float(sh[p] & 0xffff0000u);
-                            asm volatile("" : "+v"(sh[p]), "+v"(r1[2 * p]), "+v"(r1[2 * p + 1]));
-                        } else if (st == 1) {   // second term; the third is what is left (8 bits)
-                            sm[p] = bf16_pair(r1[2 * p], r1[2 * p + 1]);
-                            const float a2 = r1[2 * p] - __uint_as_float(sm[p] << 16);
-                            const float b2 = r1[2 * p + 1] - __uint_as_float(sm[p] & 0xffff0000u);
-                            sl[p] = __builtin_amdgcn_perm(__float_as_uint(b2), __float_as_uint(a2), 0x07060302u);
-                            asm volatile("" : "+v"(sm[p]), "+v"(sl[p]));
-                        } else {                // norm and zero test
-                            Bn.n2 = __builtin_fmaf(a, a, Bn.n2);
-                            Bn.n2 = __builtin_fmaf(b, b, Bn.n2);
-                            Bn.orb |= __float_as_uint(a) | __float_as_uint(b);
-                            asm volatile("" : "+v"(Bn.n2), "+v"(Bn.orb));
-                        }
-                    }
-                    ++piece;
+                    // one piece per matrix instruction, two while more pieces than instructions are left
+                    if (piece < NPIECE) split_piece(piece++, vs, st, Bn, sh, sl);
+                    if (piece < NPIECE && NPIECE - piece > 6 * KT - issued) split_piece(piece++, vs, st, Bn, sh, sl);
                     __builtin_amdgcn_sched_barrier(0);
                 }
         };
@@ -269,33 +280,15 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
         // instructions never depend on each other
         mma(Wl, B.h);
         mma(Wh, B.l);
-        mma(Wm, B.m);
-        mma(Wm, B.h);
-        mma(Wh, B.m);
         mma(Wh, B.h);
-        static_assert(3 * (NS / 2) <= 12 * KT, "one piece per matrix instruction");
 #pragma unroll
-        for (int t = 0; t < KT; ++t) {
-            Bn.h[t] = make_uint4(sh[4 * t], sh[4 * t + 1], sh[4 * t + 2], sh[4 * t + 3]);
-            Bn.m[t] = make_uint4(sm[4 * t], sm[4 * t + 1], sm[4 * t + 2], sm[4 * t + 3]);
-            Bn.l[t] = make_uint4(sl[4 * t], sl[4 * t + 1], sl[4 * t + 2], sl[4 * t + 3]);
-        }
+        for (; piece < NPIECE; ++piece) split_piece(piece, vs, st, Bn, sh, sl);
+        finish_planes(Bn, sh, sl);
 
-        float n2 = B.n2;
-        uint32_t orb = B.orb;
-        // ---- decision threshold of this pixel
+        // ---- decision threshold of this pixel (scaled units; nx = +inf: no bound)
         const int y = gcur.y, n = gcur.n, x = gcur.x, xc = gcur.xc;
-        n2 = swap_add(n2);
-        {
-            const auto sw = __builtin_amdgcn_permlane32_swap(orb, orb, false, false);
-            orb = sw[0] | sw[1];
-        }
-        const bool zero = (orb << 1) == 0;            // every patch value is +-0
-        const float nx = __builtin_sqrtf(n2);
-        // a norm that is NaN, infinite or so extreme that bf16 terms may have been flushed or
-        // products may have overflowed sends the whole pixel down the sequential route
-        const float T = (w_sane && nx >= 0x1p-60f && nx <= 0x1p60f) ? STEM_KAPPA * Wn * nx
-                                                                    : __builtin_inff();
+        const bool zero = B.nx == 0.0f;               // every patch value is +-0
+        const float T = w_sane ? STEM_KAPPA * Wn * B.nx : __builtin_inff();
         float mn = __builtin_fminf(__builtin_fabsf(acc[0][0]), __builtin_fabsf(acc[0][1]));
 #pragma unroll
         for (int i = 2; i < 16; ++i) mn = __builtin_fminf(mn, __builtin_fabsf(acc[0][i]));
@@ -316,17 +309,23 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
                 sg[m] = __builtin_amdgcn_alignbit(sg[m], __float_as_uint(acc[m][i]), 31);
 
         const size_t pix = ((size_t)n * H + y) * W + xc;
-        if (WRITE_PRE && x < W) {
+        if (WRITE_PRE) {
+            // the estimates in the units of the inputs: undo the (exact) scales of pixel and rows
+            // (the row scales live in other lanes: fetched with every lane active)
+            const float ux = 1.0f / B.sc;
 #pragma unroll
             for (int m = 0; m < 2; ++m) {
                 const int cb = chunk * 64 + m * 32 + 16 * half;
-                if (cb < Co) {
+                float o16[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    o16[i] = acc[m][i] * ux * __shfl(row_unscale[m], tile_channel_to_row(16 * half + i));
+                if (x < W && cb < Co) {
                     float4 *dst = reinterpret_cast<float4 *>(pre + pix * Co + cb);
 #pragma unroll
                     for (int q = 0; q < 4; ++q)
                         dst[q] = zero ? make_float4(0.0f, 0.0f, 0.0f, 0.0f)
-                                      : make_float4(acc[m][4 * q], acc[m][4 * q + 1], acc[m][4 * q + 2],
-                                                    acc[m][4 * q + 3]);
+                                      : make_float4(o16[4 * q], o16[4 * q + 1], o16[4 * q + 2], o16[4 * q + 3]);
                 }
             }
         }
@@ -390,7 +389,13 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
     Planes B0, B1;
     TilePos p0 = ahead;
     gather(p0, geometry(p0), va);
-    split(B0, va);
+    {
+        SplitState st;
+        uint32_t sh[NS / 2], sl[NS / 2];
+#pragma unroll
+        for (int p = 0; p < NPIECE; ++p) split_piece(p, va, st, B0, sh, sl);
+        finish_planes(B0, sh, sl);
+    }
     advance_ahead();
     TilePos p1 = ahead;
     gather(p1, geometry(p1), va);
