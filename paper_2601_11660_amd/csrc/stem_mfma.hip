@@ -87,6 +87,9 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
     constexpr int KV = 9 * CI;             // terms per output
     constexpr int KT = (KV + 15) / 16;     // 16-wide K blocks
     constexpr int NS = KT * 8;             // patch values per lane
+    // k = KV is the first padded term; it lives in slot BIAS_SLOT of the lanes of half BIAS_HALF
+    constexpr int BIAS_SLOT = 8 * (KV / 16) + (KV % 8), BIAS_HALF = (KV / 8) % 2;
+    static_assert(KV < 16 * KT, "a padded k is needed for the constant term");
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -120,6 +123,11 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
         const bool in_range = nrm >= 0x1p-60f && nrm <= 0x1p60f;
         if (!(in_range || nrm == 0.0f)) w_sane = false;
         const float sc = in_range ? norm_scale(nrm) : 1.0f;
+        // A row of zeros gives y = +0 for every pixel (bit 1), but its estimate 0 would never
+        // be decided.  Such a row gets a weight on the first padded k, where every pixel
+        // supplies the constant 1 (see BIAS_PAIR below): its estimate is 2^13, far above T.
+        if (nrm == 0.0f && ch < Co && KV == 16 * (BIAS_SLOT >> 3) + 8 * half + (BIAS_SLOT & 7))
+            v[BIAS_SLOT] = 0x1p13f;
         row_unscale[m] = 1.0f / sc;
         rb = max(rb, __float_as_uint(nrm * sc));
 #pragma unroll
@@ -227,7 +235,10 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
             asm volatile("" : "+v"(sh[q]), "+v"(sl[q]));
         }
     };
-    auto finish_planes = [&](Planes &P, const uint32_t (&sh)[NS / 2], const uint32_t (&sl)[NS / 2]) {
+    // the constant 1.0 (fp16) at the padded term k = KV of every pixel: its slot reads 0.0f
+    const uint32_t bias_or = half == BIAS_HALF ? (0x3c00u << (16 * (BIAS_SLOT & 1))) : 0u;
+    auto finish_planes = [&](Planes &P, uint32_t (&sh)[NS / 2], const uint32_t (&sl)[NS / 2]) {
+        sh[BIAS_SLOT / 2] |= bias_or;
 #pragma unroll
         for (int t = 0; t < KT; ++t) {
             P.h[t] = make_uint4(sh[4 * t], sh[4 * t + 1], sh[4 * t + 2], sh[4 * t + 3]);

@@ -537,6 +537,12 @@ def test_stem_degenerate_inputs(path, pname):
     img[:, :, 10:25, 20:50] = 0.0
     img[:, :, 12:14, 22:40] = -0.0
     check_stem(img, rng.standard_normal((Co, 3, 3, 3), dtype=np.float32), path, pname, "zero regions")
+    # output channels whose weights are all zero: y = +0 everywhere (bit 1), and it must not cost
+    # a sequential sum per pixel
+    w = rng.standard_normal((Co, 3, 3, 3), dtype=np.float32)
+    w[5] = 0.0
+    w[40] = -0.0
+    check_stem(rng.standard_normal((1, 3, H, W), dtype=np.float32), w, path, pname, "zero weight rows")
     # nearly cancelling sums: two copies of a channel with opposite weights plus a tiny third
     img = rng.standard_normal((1, 3, H, W), dtype=np.float32)
     img[:, 1] = img[:, 0]
