@@ -633,6 +633,15 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(
 int g_tune_rw = 0, g_tune_wm = 0;   // 0 = automatic
 int g_persistent_blocks = 512;       // resident blocks of the block-cooperative kernel (2 per CU)
 
+// waves per SIMD of the row-streaming kernel for single-step layers, 0 = kernel not used
+static int rows_kernel_waves() { return (g_tune_rw == 0 || g_tune_rw == 7) ? 2 : g_tune_rw == 8 ? 1 : 0; }
+
+bool conv_writes_pooled(int H, int W, const BlobLayout &L)
+{
+    if ((H & 1) || (W & 1)) return false;
+    return L.ksteps > 1 || (rows_kernel_waves() && conv_rows_supported(H, W, L, (const uint32_t *)16));
+}
+
 template <int RW, int MT, bool CW_EVEN, bool ONE_STEP>
 static int launch_bits_t(const uint32_t *act, int N, int H, int W, const BlobLayout &L,
                          const uint4 *wfrag, const int32_t *thresh, uint32_t *out_bits,
@@ -740,27 +749,32 @@ int launch_conv_mfma(const uint32_t *act, int N, int H, int W, const BlobLayout 
                    L.ksteps, wfrag, L.cout, thresh, out_bits, out_acc);
         return check_launch("conv_mfma_acc");
     }
-    // Kernel choice (measured on MI355X): with a single 64-channel input step the per-tile
-    // prologue and epilogue dominate and the persistent wave-private kernel wins (3 rows x 64
-    // channels per wave fit the register file together with the resident weights); with
-    // several steps the block-cooperative kernel stages less per wave and wins.
+    // Kernel choice (measured on MI355X): with a single 64-channel input step the vector work
+    // per tile (staging, sign collection) is more than half the matrix time and only the
+    // row-streaming kernel hides it (64->64 at 1024x2048: 25 us against 31 us for the
+    // wave-private tile kernel, which remains for shapes the streaming kernel does not take);
+    // with several steps the block-cooperative kernel stages least per wave and wins.
     const int mode = g_tune_rw;   // 0 = automatic; see mbu_set_conv_tuning
     const bool want_block = mode == 1 || (mode == 0 && L.ksteps > 1);
     if (want_block) {
         ConvIO io{act, nullptr, 0, L.cin_words, 0, out_bits, nullptr};
         return launch_block_auto(io, N, H, W, L, wfrag, thresh, s);
     }
+    if (rows_kernel_waves() && conv_rows_supported(H, W, L, out_bits))
+        return launch_conv_mfma_rows(act, N, H, W, L, blob, thresh, out_bits, nullptr, rows_kernel_waves(), s);
     if (mode == 6) return launch_bits<6, 1>(act, N, H, W, L, wfrag, thresh, out_bits, s);
     return launch_bits<3, 2>(act, N, H, W, L, wfrag, thresh, out_bits, s);
 }
 
 // Fused form: input = [act (Ca channels) | low (Clow channels)] when low is given - read
-// up-sampled 2x when low_shift = 1 - plus an optional 2x2-pooled second output.  Always the
-// block-cooperative kernel.
+// up-sampled 2x when low_shift = 1 - plus an optional 2x2-pooled second output.  The
+// block-cooperative kernel, or the row-streaming kernel for a single-source single-step layer.
 int launch_conv_mfma_two(const uint32_t *act, int Ca, const uint32_t *low, int Clow, int low_shift,
                          int N, int H, int W, const BlobLayout &L, const void *blob,
                          const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, hipStream_t s)
 {
+    if (!low && rows_kernel_waves() && conv_rows_supported(H, W, L, out_bits))
+        return launch_conv_mfma_rows(act, N, H, W, L, blob, thresh, out_bits, out_pool, rows_kernel_waves(), s);
     const uint4 *wfrag = (const uint4 *)((const uint8_t *)blob + L.off_f4);
     ConvIO io{act, low, low ? low_shift : 0, ceil_div(Ca, 32), low ? ceil_div(Clow, 32) : 0,
               out_bits, out_pool};

@@ -1,0 +1,390 @@
+// Masked-binary 3x3 convolution on the matrix cores for layers with at most 64 input
+// channels (one 64-channel step): row-streaming kernel.
+//
+// With a single input step the contraction of a tile is short (18 matrix instructions per
+// image row of 32 pixels x 64 channels) and the vector work around it - expanding the staged
+// bits to 4-bit codes, collecting the output signs - costs about 60 % of the matrix time when
+// it runs as a separate phase: vector instructions only hide behind matrix instructions of the
+// same wave.  This kernel therefore has no phases.  A wave owns a strip of 32 pixel columns
+// and 64 output channels, keeps the 18 weight fragments of the layer in registers for its
+// whole life and walks down the image one row at a time.  Every row is 18 matrix
+// instructions with one small piece of vector work slotted behind each of them:
+//   - the three activation rows a 3x3 window touches are held in registers as 9 fragments
+//     (3 rows x 3 tap columns); the window moves down by register copies, each fragment row
+//     overwritten right after the 6 instructions of its tap row, and the row that enters is
+//     read from LDS at the end of the row, 12 instructions before its first use;
+//   - the halo row that enters the window two rows later is expanded from bits to codes and
+//     written to one of two row slots in LDS; its bits were fetched from global memory two
+//     rows earlier;
+//   - the signs of the PREVIOUS row's accumulators (two accumulator sets alternate) are
+//     collected, completed to words and stored - and, for a layer followed by 2x2 max pooling
+//     (Sec. 2.1: OR of the bits), every second row also stores the pooled words.
+// Accumulators start at -theta through the addend of the row's first instruction per tile.
+// No barriers, nothing shared between waves.
+#include "mbu_internal.h"
+#include "mfma_common.h"
+#include <algorithm>
+
+namespace mbu {
+
+namespace {
+
+constexpr int RS_HW = 34;               // halo pixels per staged row
+constexpr int RS_ROW = 2 * RS_HW;       // uint4 entries per staged row: [half][pixel]
+constexpr int RS_RING = 2;              // staged rows kept in LDS
+constexpr uint32_t RS_BAD_LANE = 0x40000000u;   // byte offsets that no tensor of < 2^30 bytes reaches
+constexpr uint32_t RS_BAD_ROW = 0x80000000u;
+
+#define RS_FENCE() __builtin_amdgcn_sched_barrier(0)
+#define RS_PIN(x) asm volatile("" : "+v"(x))
+
+struct RowsCtx {
+    __amdgpu_buffer_rsrc_t in, out, pool;
+    uint32_t in_voff;      // byte offset of this lane's halo pixel inside an image row
+    uint32_t mx8;          // 0x88888888 when that pixel's column lies inside the image
+    uint32_t out_voff;     // byte offset of this lane's output word inside an image row
+    uint32_t pool_voff;    // ... of its pooled word inside a pooled row
+    uint32_t psel;
+    uint4 *wr;             // LDS: this lane's staged pixel, ring slot 0, word 0
+    const uint4 *rd;       // LDS: this lane's fragment of tap column 0, ring slot 0
+    int H, y0;
+    int in_row_bytes, out_row_bytes, pool_row_bytes;
+};
+
+// bits of the two words of a pixel -> codes of the negated activation, zero outside the image
+__device__ __forceinline__ void fetch_row(const RowsCtx &c, int yy, uint2 &g, bool even)
+{
+    const int yc = min(max(yy, 0), c.H - 1);
+    const int soff = yc * c.in_row_bytes;
+    if (even) {
+        const auto v = __builtin_amdgcn_raw_buffer_load_b64(c.in, c.in_voff, soff, 0);
+        g.x = v[0];
+        g.y = v[1];
+    } else {
+        g.x = __builtin_amdgcn_raw_buffer_load_b32(c.in, c.in_voff, soff, 0);
+        g.y = 0u;
+    }
+}
+
+// sign words of one finished row: stores the row's words and, on odd rows, the pooled words
+template <bool POOL, bool ODD>
+__device__ __forceinline__ void store_row(const RowsCtx &c, uint32_t s, int i_row, uint32_t &wkeep)
+{
+    // s: bit k = sign of channel k + 16 * half of tile k / 16 ... (see collection order below)
+    const uint32_t mine = ~s;
+    const auto sw = __builtin_amdgcn_permlane32_swap(mine, mine, false, false);
+    const uint32_t word = __builtin_amdgcn_perm(sw[1], sw[0], c.psel);
+    const uint32_t roff = i_row >= 0 ? (uint32_t)((c.y0 + i_row) * c.out_row_bytes) : RS_BAD_ROW;
+    __builtin_amdgcn_raw_buffer_store_b32(word, c.out, c.out_voff + roff, 0, 0);
+    if (POOL) {
+        if (!ODD) {
+            wkeep = word;
+        } else {
+            uint32_t v = wkeep | word;
+            // neighbouring lane (quad permute [1,0,3,2]) holds the next pixel of the row
+            v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, true);
+            const uint32_t poff =
+                i_row >= 0 ? (uint32_t)(((c.y0 + i_row) >> 1) * c.pool_row_bytes) : RS_BAD_ROW;
+            __builtin_amdgcn_raw_buffer_store_b32(v, c.pool, c.pool_voff + poff, 0, 0);
+        }
+    }
+}
+
+// One image row; P = parity of the row index i: accumulator set, ring slots and fetch register.
+// F[k] holds the fragments of halo row i + k (image row y0 + i + k - 1).
+template <bool CW_EVEN, bool POOL, int P>
+__device__ __forceinline__ void rows_step(const RowsCtx &c, const int i,
+                                          const v4i (&Wg)[3][3][2], const v16f (&init)[2],
+                                          v16f (&acc)[2][2], v4i (&F)[3][3], uint2 (&gq)[2], uint32_t &wkeep)
+{
+    constexpr int CUR = P, PRV = P ^ 1;
+    constexpr int RD = P ^ 1, WR = P;      // ring slot of halo row i + 3 / i + 4
+
+    uint32_t a = 0, b = 0, k8 = 0, k2 = 0, l8 = 0, l2 = 0;
+    uint4 e0, e1;
+    uint32_t s = 0;
+#pragma unroll
+    for (int t = 0; t < 18; ++t) {
+        const int ky = t / 6, kx = (t % 6) >> 1, m = t & 1;
+        acc[CUR][m] = mfma_f4(Wg[kx][ky][m], F[ky][kx], ky == 0 && kx == 0 ? init[m] : acc[CUR][m]);
+        RS_FENCE();
+        // ---- staging of halo row i + 4 (image row y0 + i + 3): bits fetched two rows ago
+        if (t == 0) {
+            a = gq[P].x;
+            b = gq[P].y;
+            const bool rin = c.y0 + i + 3 < c.H;
+            k8 = rin ? c.mx8 : 0u;
+            k2 = k8 >> 2;
+            l8 = CW_EVEN ? k8 : 0u;
+            l2 = l8 >> 2;
+            e0.x = ((a << 3) & k8) | k2;
+            RS_PIN(e0.x);
+        } else if (t == 1) {
+            e0.y = ((a << 2) & k8) | k2;
+            e0.z = ((a << 1) & k8) | k2;
+            RS_PIN(e0.y); RS_PIN(e0.z);
+        } else if (t == 2) {
+            e0.w = (a & k8) | k2;
+            e1.x = ((b << 3) & l8) | l2;
+            RS_PIN(e0.w); RS_PIN(e1.x);
+        } else if (t == 3) {
+            e1.y = ((b << 2) & l8) | l2;
+            e1.z = ((b << 1) & l8) | l2;
+            RS_PIN(e1.y); RS_PIN(e1.z);
+        } else if (t == 4) {
+            e1.w = (b & l8) | l2;
+            RS_PIN(e1.w);
+            c.wr[WR * RS_ROW] = e0;
+            c.wr[WR * RS_ROW + RS_HW] = e1;
+            // halo row i + 6 into the register just consumed
+            fetch_row(c, c.y0 + i + 5, gq[P], CW_EVEN);
+        }
+        // ---- the window moves down one row: a fragment row is overwritten as soon as its tap
+        // row has been issued
+        if (t == 5 || t == 11) {
+            const int k = t / 6;   // F[k] <- F[k + 1]
+#pragma unroll
+            for (int x = 0; x < 3; ++x) {
+                F[k][x] = F[k + 1][x];
+                RS_PIN(F[k][x]);
+            }
+        }
+        if (t == 17) {
+#pragma unroll
+            for (int x = 0; x < 3; ++x) {
+                const uint4 f = c.rd[RD * RS_ROW + x];
+                F[2][x] = (v4i){(int)f.x, (int)f.y, (int)f.z, (int)f.w};
+            }
+        }
+        // ---- signs of the previous row: one chain over the 32 registers, second tile first, so
+        // that bit k of the result is register k % 16 of tile k / 16
+        if (t >= 6 && t < 17) {
+            const int first = (t - 6) * 3, last = min(first + 3, 32);
+#pragma unroll
+            for (int e = first; e < last; ++e) {
+                const int mm = 1 - e / 16, r = 15 - e % 16;
+                s = __builtin_amdgcn_alignbit(s, __float_as_uint(acc[PRV][mm][r]), 31);
+            }
+            RS_PIN(s);
+        }
+        if (t == 17) {
+            // row i - 1 is odd when i is even; it exists unless i = 0
+            const bool valid = P == 1 || i > 0;
+            store_row<POOL, P == 0>(c, s, valid ? i - 1 : -1, wkeep);
+        }
+        RS_FENCE();
+    }
+}
+
+template <bool CW_EVEN, bool POOL, int WPS>
+__global__ __launch_bounds__(256, WPS) void conv_mfma_rows_kernel(
+    const uint32_t *__restrict__ act, int H, int W, int Cw, const uint4 *__restrict__ wfrag, int Cout,
+    int ctiles, int strips, int nseg, int seg_rows, int units, const int32_t *__restrict__ thresh,
+    uint32_t *__restrict__ out_bits, uint32_t *__restrict__ out_pool)
+{
+    __shared__ uint4 lds[4][RS_RING * RS_ROW];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int gw = blockIdx.x * 4 + wave;
+    if (gw >= units) return;                  // whole wave leaves; nothing is shared
+    int q = gw;
+    const int ct = q % ctiles; q /= ctiles;   // 64-channel output tile
+    const int sx = q % strips; q /= strips;   // strip of 32 pixel columns
+    const int sg = q % nseg;                  // segment of seg_rows image rows
+    const int n = q / nseg;
+    const int col = lane & 31, half = lane >> 5;
+    const int Cow = Cout >> 5;
+    const int y0 = sg * seg_rows;
+    const int rows = min(H, y0 + seg_rows) - y0;
+
+    RowsCtx c;
+    c.H = H;
+    c.y0 = y0;
+    c.in_row_bytes = W * Cw * 4;
+    c.out_row_bytes = W * Cow * 4;
+    c.pool_row_bytes = (W >> 1) * Cow * 4;
+    c.in = __builtin_amdgcn_make_buffer_rsrc((void *)(act + (size_t)n * H * W * Cw), 0, H * c.in_row_bytes,
+                                             0x00020000);
+    c.out = __builtin_amdgcn_make_buffer_rsrc((void *)(out_bits + (size_t)n * H * W * Cow), 0,
+                                              H * c.out_row_bytes, 0x00020000);
+    c.pool = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(POOL ? out_pool + (size_t)n * (H >> 1) * (W >> 1) * Cow : out_bits), 0,
+        POOL ? (H >> 1) * c.pool_row_bytes : 0, 0x00020000);
+    {
+        const int p = min(lane, RS_HW - 1);   // surplus lanes duplicate the last halo pixel
+        const int xx = sx * 32 + p - 1;
+        c.in_voff = (uint32_t)(min(max(xx, 0), W - 1) * Cw * 4);
+        c.mx8 = (xx >= 0 && xx < W) ? 0x88888888u : 0u;
+        c.wr = lds[wave] + p;
+        c.rd = lds[wave] + half * RS_HW + col;
+        const int x = sx * 32 + col;
+        const int widx = ct * 2 + half;
+        const bool ok = x < W && widx < Cow;
+        c.out_voff = ok ? (uint32_t)((x * Cow + widx) * 4) : RS_BAD_LANE;
+        c.pool_voff = (ok && (col & 1) == 0) ? (uint32_t)(((x >> 1) * Cow + widx) * 4) : RS_BAD_LANE;
+        c.psel = half ? 0x07060302u : 0x05040100u;
+    }
+
+    // ---- -theta for the 2 x 16 channels of this lane (exact in fp32 after clamping theta to
+    // +-2^22, which cannot change a comparison because |R| <= 9*64)
+    v16f init[2];
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+        const int cbase = (ct * 2 + m) * 32 + 16 * half;
+        int th[16];
+        if (cbase < Cout) {
+            const int4 *tp = reinterpret_cast<const int4 *>(thresh + cbase);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int4 t = tp[k];
+                th[4 * k] = t.x; th[4 * k + 1] = t.y; th[4 * k + 2] = t.z; th[4 * k + 3] = t.w;
+            }
+        } else {
+#pragma unroll
+            for (int k = 0; k < 16; ++k) th[k] = 0;
+        }
+#pragma unroll
+        for (int k = 0; k < 16; ++k) init[m][k] = 0.0f - (float)max(-(1 << 22), min(1 << 22, th[k]));
+    }
+
+    // ---- weights: [tile64][tap][m][lane], resident for the whole strip
+    v4i Wg[3][3][2];   // [kx][ky][m]
+    {
+        const uint4 *wk = wfrag + (size_t)ct * (18 * 64) + lane;
+#pragma unroll
+        for (int kx = 0; kx < 3; ++kx)
+#pragma unroll
+            for (int ky = 0; ky < 3; ++ky)
+#pragma unroll
+                for (int m = 0; m < 2; ++m) {
+                    const uint4 w = wk[((ky * 3 + kx) * 2 + m) * 64];
+                    Wg[kx][ky][m] = (v4i){(int)w.x, (int)w.y, (int)w.z, (int)w.w};
+                }
+    }
+
+    // ---- prologue: halo rows 0..3 through the two ring slots (row j in slot j mod 2), rows
+    // 0..2 into the window, row 3 left in the ring, rows 4 and 5 in flight.  LDS instructions
+    // of one wave execute in order, so a read sees the write before it.
+    uint2 gq[2];
+    v4i F[3][3];
+    {
+        uint2 g4[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) fetch_row(c, y0 - 1 + j, g4[j], CW_EVEN);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) fetch_row(c, y0 + 3 + j, gq[j], CW_EVEN);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int yy = y0 - 1 + j;
+            const uint32_t k8 = (yy >= 0 && yy < H) ? c.mx8 : 0u, k2 = k8 >> 2;
+            const uint32_t l8 = CW_EVEN ? k8 : 0u, l2 = l8 >> 2;
+            const uint32_t a = g4[j].x, b = g4[j].y;
+            uint4 e0, e1;
+            e0.x = ((a << 3) & k8) | k2; e0.y = ((a << 2) & k8) | k2;
+            e0.z = ((a << 1) & k8) | k2; e0.w = (a & k8) | k2;
+            e1.x = ((b << 3) & l8) | l2; e1.y = ((b << 2) & l8) | l2;
+            e1.z = ((b << 1) & l8) | l2; e1.w = (b & l8) | l2;
+            c.wr[(j & 1) * RS_ROW] = e0;
+            c.wr[(j & 1) * RS_ROW + RS_HW] = e1;
+            __builtin_amdgcn_wave_barrier();
+            if (j < 3) {
+#pragma unroll
+                for (int x = 0; x < 3; ++x) {
+                    const uint4 f = c.rd[(j & 1) * RS_ROW + x];
+                    F[j][x] = (v4i){(int)f.x, (int)f.y, (int)f.z, (int)f.w};
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+
+    v16f acc[2][2];
+    acc[1][0] = init[0];     // "previous row" of row 0: collected, never stored
+    acc[1][1] = init[1];
+    uint32_t wkeep = 0;
+
+    // Everything fetched so far has to be complete before the loop: the compiler sizes the
+    // waits inside the loop for the worse of its two entries, and with fetches still pending
+    // here the steady state would wait for its two-rows-ahead fetches a row early.
+#pragma unroll
+    for (int kx = 0; kx < 3; ++kx)
+#pragma unroll
+        for (int ky = 0; ky < 3; ++ky) {
+            RS_PIN(Wg[kx][ky][0]);
+            RS_PIN(Wg[kx][ky][1]);
+        }
+    RS_PIN(gq[0].x); RS_PIN(gq[0].y); RS_PIN(gq[1].x); RS_PIN(gq[1].y);
+
+    // two rows per trip (the accumulator sets alternate); with an odd row count the second
+    // row of the last trip is computed and dropped
+    int i = 0;
+#pragma unroll 1
+    for (; i < rows; i += 2) {
+        rows_step<CW_EVEN, POOL, 0>(c, i, Wg, init, acc, F, gq, wkeep);
+        rows_step<CW_EVEN, POOL, 1>(c, i + 1, Wg, init, acc, F, gq, wkeep);
+    }
+
+    // ---- the signs of the last odd row, still in accumulator set 1
+    uint32_t s = 0;
+#pragma unroll
+    for (int e = 0; e < 32; ++e) {
+        const int mm = 1 - e / 16, r = 15 - e % 16;
+        s = __builtin_amdgcn_alignbit(s, __float_as_uint(acc[1][mm][r]), 31);
+    }
+    store_row<POOL, true>(c, s, i - 1 < rows ? i - 1 : -1, wkeep);
+}
+
+template <bool POOL, int WPS>
+int launch_rows_t(const uint32_t *act, int N, int H, int W, const BlobLayout &L, const uint4 *wfrag,
+                  const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, hipStream_t s)
+{
+    const int ctiles = L.cout_pad64 / 64;
+    const int strips = ceil_div(W, 32);
+    const long base = (long)N * strips * ctiles;
+    // as many row segments as it takes to give every wave slot of the chip one unit
+    const long slots = (long)WPS * 4 * 256;
+    const int want = (int)std::max(1L, slots / base);
+    int seg_rows = ceil_div(H, want);
+    seg_rows = std::max(2, seg_rows + (seg_rows & 1));        // even: 2x2 windows stay inside a segment
+    const int nseg = ceil_div(H, seg_rows);
+    const long units = base * nseg;
+    if (units > 0x7fffffffL) return fail(MBU_ERR_SHAPE, "too many tiles for one launch");
+    const int grid = (int)((units + 3) / 4);
+    if (L.cin_words == 2)
+        MBU_LAUNCH((conv_mfma_rows_kernel<true, POOL, WPS>), dim3(grid), dim3(256), 0, s, act, H, W,
+                   L.cin_words, wfrag, L.cout, ctiles, strips, nseg, seg_rows, (int)units, thresh, out_bits,
+                   out_pool);
+    else
+        MBU_LAUNCH((conv_mfma_rows_kernel<false, POOL, WPS>), dim3(grid), dim3(256), 0, s, act, H, W,
+                   L.cin_words, wfrag, L.cout, ctiles, strips, nseg, seg_rows, (int)units, thresh, out_bits,
+                   out_pool);
+    return check_launch("conv_mfma_rows");
+}
+
+}  // namespace
+
+bool conv_rows_supported(int H, int W, const BlobLayout &L, const uint32_t *out_bits)
+{
+    // one input step, packed output wanted, every image below 2^30 bytes on both sides
+    return L.ksteps == 1 && out_bits != nullptr && (double)H * W * L.cin_words * 4 < 1073741824.0 &&
+           (double)H * W * (L.cout >> 5) * 4 < 1073741824.0;
+}
+
+int launch_conv_mfma_rows(const uint32_t *act, int N, int H, int W, const BlobLayout &L, const void *blob,
+                          const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, int waves_per_simd,
+                          hipStream_t s)
+{
+    if (!conv_rows_supported(H, W, L, out_bits))
+        return fail(MBU_ERR_SHAPE, "row-streaming kernel: layer not supported");
+    if (out_pool && ((H & 1) || (W & 1))) return fail(MBU_ERR_SHAPE, "pooled output needs even H and W");
+    const uint4 *wfrag = (const uint4 *)((const uint8_t *)blob + L.off_f4);
+    if (waves_per_simd == 1) {
+        if (out_pool) return launch_rows_t<true, 1>(act, N, H, W, L, wfrag, thresh, out_bits, out_pool, s);
+        return launch_rows_t<false, 1>(act, N, H, W, L, wfrag, thresh, out_bits, out_pool, s);
+    }
+    if (out_pool) return launch_rows_t<true, 2>(act, N, H, W, L, wfrag, thresh, out_bits, out_pool, s);
+    return launch_rows_t<false, 2>(act, N, H, W, L, wfrag, thresh, out_bits, out_pool, s);
+}
+
+}  // namespace mbu

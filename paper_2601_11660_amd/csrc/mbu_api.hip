@@ -163,7 +163,7 @@ static bool step_launches(const mbu_unet_desc *d, const std::vector<Step> &steps
     if (st.kind == Step::POOL) {
         const Step &in = steps[st.in];
         return !(in.kind == Step::CONV &&
-                 blob_layout(d->convs[in.conv].cout, d->convs[in.conv].cin).ksteps > 1);
+                 conv_writes_pooled(in.h, in.w, blob_layout(d->convs[in.conv].cout, d->convs[in.conv].cin)));
     }
     return true;
 }
@@ -250,8 +250,9 @@ int mbu_classifier_fp32(const uint32_t *act, int N, int H, int W, int C, const f
 
 int mbu_set_conv_tuning(int rows_per_wave, int reserved)
 {
-    if ((rows_per_wave != 0 && rows_per_wave != 1 && rows_per_wave != 3 && rows_per_wave != 6) || reserved != 0)
-        return fail(MBU_ERR_ARG, "mbu_set_conv_tuning: kernel in {0,1,3,6}, second argument 0");
+    if ((rows_per_wave != 0 && rows_per_wave != 1 && rows_per_wave != 3 && rows_per_wave != 6 &&
+         rows_per_wave != 7 && rows_per_wave != 8) || reserved != 0)
+        return fail(MBU_ERR_ARG, "mbu_set_conv_tuning: kernel in {0,1,3,6,7,8}, second argument 0");
     g_tune_rw = rows_per_wave;
     g_tune_wm = 0;
     return MBU_OK;
@@ -542,7 +543,7 @@ int mbu_unet_forward(const mbu_unet_desc *d, const float *image_nchw, int N, int
             // fused forms: read [skip | up(low)] in place; write the pooled output as well
             const bool from_cat = fuse && (in.kind == Step::UPCAT || in.kind == Step::CAT);
             const bool next_pool = fuse && i + 1 < steps.size() && steps[i + 1].kind == Step::POOL &&
-                                   blob_layout(L.cout, L.cin).ksteps > 1;
+                                   conv_writes_pooled(st.h, st.w, blob_layout(L.cout, L.cin));
             if (from_cat || next_pool) {
                 const uint32_t *a = from_cat ? buf(in.in) : buf(st.in);
                 const int ca = from_cat ? steps[in.in].c : L.cin;
@@ -560,7 +561,7 @@ int mbu_unet_forward(const mbu_unet_desc *d, const float *image_nchw, int N, int
         case Step::POOL: {
             const Step &in = steps[st.in];
             const bool done = fuse && in.kind == Step::CONV &&
-                              blob_layout(d->convs[in.conv].cout, d->convs[in.conv].cin).ksteps > 1;
+                              conv_writes_pooled(in.h, in.w, blob_layout(d->convs[in.conv].cout, d->convs[in.conv].cin));
             if (!done)
                 rc = launch_maxpool(buf(st.in), N, st.h * 2, st.w * 2, st.c / 32, buf((int)i), s);
             break;

@@ -81,6 +81,15 @@ int launch_conv_mfma_fused(const uint32_t *act, int Ca, const uint32_t *low, int
 int launch_conv_mfma_two(const uint32_t *act, int Ca, const uint32_t *low, int Clow, int low_shift,
                          int N, int H, int W, const BlobLayout &L, const void *blob,
                          const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, hipStream_t s);
+// row-streaming kernel for layers with a single 64-channel input step (optional 2x2-pooled
+// second output); waves_per_simd = 1 or 2
+bool conv_rows_supported(int H, int W, const BlobLayout &L, const uint32_t *out_bits);
+int launch_conv_mfma_rows(const uint32_t *act, int N, int H, int W, const BlobLayout &L, const void *blob,
+                          const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, int waves_per_simd,
+                          hipStream_t s);
+// does the matrix path write the 2x2-pooled output of this layer from its own epilogue?
+// (layers with several input steps always; single-step layers when the row-streaming kernel runs)
+bool conv_writes_pooled(int H, int W, const BlobLayout &L);
 int launch_pack_tconv(const int8_t *w, const TconvLayout &L, void *blob, hipStream_t s);
 int launch_tconv_mfma(const uint32_t *act, int N, int H, int W, const TconvLayout &L,
                       const void *blob, const int32_t *thresh, uint32_t *out_bits, int32_t *out_acc,

@@ -130,7 +130,7 @@ def test_conv_degenerate_masks_and_ties(path, pname):
         assert np.array_equal(bits, bitref.pack_pm1(O.threshold(acc_ref, th)))
 
 
-@pytest.mark.parametrize("kernel", [1, 3, 6])
+@pytest.mark.parametrize("kernel", [1, 3, 6, 7, 8])
 @pytest.mark.parametrize("shape", SMALL_SHAPES + [(1, 100, 100, 128, 128, 0.6), (2, 31, 67, 64, 192, 0.5)])
 def test_every_matrix_kernel_variant_matches_oracle(shape, kernel):
     """The library picks a kernel variant per layer shape; each variant must be exact on
@@ -142,6 +142,37 @@ def test_every_matrix_kernel_variant_matches_oracle(shape, kernel):
     B.set_conv_tuning(kernel)
     bits, _ = run_layer(case, B.PATH_MFMA, want_acc=False)
     assert np.array_equal(bits, bitref.pack_pm1(out_ref))
+
+
+ROWS_SHAPES = [
+    # N, H, W, Cin, Cout: single 64-channel input step
+    (1, 64, 64, 64, 64),
+    (2, 38, 70, 64, 128),      # ragged strip, two output tiles, two images
+    (1, 2, 2, 32, 32),         # one word in, half an output tile
+    (1, 130, 34, 40, 96),      # Cin not a multiple of 32, many row segments
+    (3, 6, 200, 64, 64),
+    (1, 256, 512, 64, 64),     # every wave slot of the chip busy
+]
+
+
+@pytest.mark.parametrize("kernel", [7, 8])
+@pytest.mark.parametrize("shape", ROWS_SHAPES)
+def test_row_streaming_kernel_with_pooled_output(shape, kernel):
+    """The row-streaming kernel of the single-step layers (one or two waves per SIMD): packed
+    output and the 2x2-pooled output written from the same pass (Sec. 2.1) against the oracle."""
+    N, H, W, Cin, Cout = shape
+    say(f"conv rows kernel={kernel} N={N} H={H} W={W} Cin={Cin} Cout={Cout}")
+    case = synth.conv_case(11, 0, N, H, W, Cin, Cout, 0.6)
+    _, out_ref = O.masked_binary_layer(case.a, case.w, case.theta)
+    B.set_conv_tuning(kernel)
+    pa = B.pack_act(dev(case.a))
+    blob = B.pack_weights(dev(case.w))
+    bits, pool = B.conv3x3_masked_binary_fused(pa, Cin, None, 0, blob, Cout, dev(case.theta), True, True)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_u32(bits), bitref.pack_pm1(out_ref))
+    assert np.array_equal(host_u32(pool), bitref.pack_pm1(O.maxpool2x2(out_ref)))
+    bits2, _ = run_layer(case, B.PATH_MFMA, want_acc=False)
+    assert np.array_equal(bits2, bitref.pack_pm1(out_ref))
 
 
 FUSED_SHAPES = [
