@@ -47,6 +47,8 @@ def parse():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (3x) so that a counter pass of "
                          "this command can scale FETCH_SIZE / WRITE_SIZE by a known transfer")
+    ap.add_argument("--kernel", type=int, default=0,
+                    help="matrix-path kernel variant (mbu_set_conv_tuning; 0 = automatic)")
     ap.add_argument("--single-layer", default=None, metavar="CIN,COUT,H,W",
                     help="time one masked-binary 3x3 layer of this shape instead of the network "
                          "(used for per-kernel counter passes); prints its own JSON line")
@@ -254,6 +256,7 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     B.set_conv_path({"auto": B.PATH_AUTO, "valu": B.PATH_VALU, "mfma": B.PATH_MFMA}[args.path])
+    B.set_conv_tuning(args.kernel)
     if args.single_layer:
         single_layer(args, B, torch, synth)
         return

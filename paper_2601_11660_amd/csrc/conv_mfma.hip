@@ -317,6 +317,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
     uint32_t *__restrict__ out_pool)
 {
     static_assert(WM * WN == 4, "four waves per block");
+    constexpr int NB = 3;                        // activation fragments in flight per wave (WN = 4)
     static_assert(!POOL || (RW % 2 == 0), "pooling pairs rows inside a wave");
     constexpr int NT = 256;
     constexpr int TH = RW * WM;
@@ -470,12 +471,49 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
             // its destination registers are free, a whole step ahead of its use.
             stage_issue(kn);
             __builtin_amdgcn_sched_barrier(0);
+            if constexpr (WN == 4) {
+                // The 3 x (RW + 2) activation fragments of the step, in the order they are used
+                // (tap column, then window row), rotate through NB registers: the read of fragment
+                // j + NB is issued right after the matrix instructions of fragment j, so the LDS
+                // latency hides behind the instructions of the NB - 1 fragments in between.
+                constexpr int NF = 3 * (RW + 2);
+                v4i fr[NB];
 #pragma unroll
-            for (int kx = 0; kx < 3; ++kx) {
-                group_mma<RW, 2>(acc, Wg[kx], tb + kx);
-                __builtin_amdgcn_sched_barrier(0);
-                load_group<2>(Wg[kx], wn_ptr, kx);
-                __builtin_amdgcn_sched_barrier(0);
+                for (int j = 0; j < NB; ++j) {
+                    const uint4 b = tb[(j / (RW + 2)) + (j % (RW + 2)) * 2 * HALO_W];
+                    fr[j] = (v4i){(int)b.x, (int)b.y, (int)b.z, (int)b.w};
+                }
+#pragma unroll
+                for (int j = 0; j < NF; ++j) {
+                    const int kx = j / (RW + 2), rho = j % (RW + 2);
+#pragma unroll
+                    for (int ky = 0; ky < 3; ++ky) {
+                        const int r = rho - ky;
+                        if (r >= 0 && r < RW) {
+#pragma unroll
+                            for (int m = 0; m < 2; ++m)
+                                acc[r][m] = mfma_f4(Wg[kx][ky][m], fr[j % NB], acc[r][m]);
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (j + NB < NF) {
+                        const int jn = j + NB;
+                        const uint4 b = tb[(jn / (RW + 2)) + (jn % (RW + 2)) * 2 * HALO_W];
+                        fr[j % NB] = (v4i){(int)b.x, (int)b.y, (int)b.z, (int)b.w};
+                    }
+                    if (rho == RW + 1) load_group<2>(Wg[kx], wn_ptr, kx);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else {
+                // the variants with larger staging plans have no registers left for a third
+                // fragment in flight: fragments are read group by group
+#pragma unroll
+                for (int kx = 0; kx < 3; ++kx) {
+                    group_mma<RW, 2>(acc, Wg[kx], tb + kx);
+                    __builtin_amdgcn_sched_barrier(0);
+                    load_group<2>(Wg[kx], wn_ptr, kx);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
             buf ^= 1;
             stage_commit(kn, tile[buf]);
