@@ -424,6 +424,11 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
 
     // ---- weight fragments: [tile64][kstep][tap][m][lane], 18 KB per step and tile
     const uint4 *wk = wfrag + (size_t)ct * ksteps * (18 * 64) + lane;
+    // the same fragments through a buffer resource: lane offset in a register, step and tap
+    // offsets in scalar registers, no address arithmetic on the vector ALU
+    const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(wfrag + (size_t)ct * ksteps * (18 * 64)), 0, ksteps * (18 * 1024), 0x00020000);
+    const int wlane = lane * 16;
     v4i Wg[3][3][2];   // [kx][ky][m]
     const int stride = gridDim.x;
     TilePos cur = tile_pos(blockIdx.x, tstep.tiles_x, tstep.tiles_y);   // the only divisions
@@ -501,7 +506,17 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
                         const uint4 b = tb[(jn / (RW + 2)) + (jn % (RW + 2)) * 2 * HALO_W];
                         fr[j % NB] = (v4i){(int)b.x, (int)b.y, (int)b.z, (int)b.w};
                     }
-                    if (rho == RW + 1) load_group<2>(Wg[kx], wn_ptr, kx);
+                    // the two weight fragments of tap (ky, kx) are free after window row RW - 1 + ky:
+                    // their successors of the next step are fetched at once, two loads per slot
+                    if (rho >= RW - 1) {
+                        const int ky = rho - (RW - 1);
+#pragma unroll
+                        for (int m = 0; m < 2; ++m) {
+                            const auto w = __builtin_amdgcn_raw_buffer_load_b128(
+                                wrs, wlane, (kn * 18 + (ky * 3 + kx) * 2 + m) * 1024, 0);
+                            Wg[kx][ky][m] = (v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
+                        }
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             } else {
