@@ -317,7 +317,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
     uint32_t *__restrict__ out_pool)
 {
     static_assert(WM * WN == 4, "four waves per block");
-    constexpr int NB = 3;                        // activation fragments in flight per wave (WN = 4)
+    constexpr int NB = 3;                        // activation fragments in flight per wave
     static_assert(!POOL || (RW % 2 == 0), "pooling pairs rows inside a wave");
     constexpr int NT = 256;
     constexpr int TH = RW * WM;
@@ -354,12 +354,20 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
         init_tab[wave][half][m][q] = f;
     }
 
-    // ---- staging plan of this thread for one pixel tile: halo pixels p = tid + NT*j
-    // bit 31 of offa = "pixel lies inside the image" (tensors are limited to 2^31 words)
-    uint32_t offa[NLD];                  // word offset of the (clamped) pixel in act
-    uint32_t offb[TWO_SRC ? NLD : 1];    // ... of the pixel (y/2, x/2) in low
+    // ---- staging plan of this thread for one pixel tile: halo pixels p = tid + NT*j.
+    // Both sources are read through buffer resources (tensors below 4 GiB): byte offset of the
+    // pixel in a register, offset of the 64-channel step in a scalar register.
+    const __amdgpu_buffer_rsrc_t ars =
+        __builtin_amdgcn_make_buffer_rsrc((void *)act, 0, (int)((size_t)N * H * W * Cwa * 4), 0x00020000);
+    const __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(TWO_SRC ? low : act), 0,
+        TWO_SRC ? (int)((size_t)N * (H >> low_shift) * (W >> low_shift) * Cwb * 4) : 0, 0x00020000);
+    uint32_t offa[NLD];                  // byte offset of the (clamped) pixel in act
+    uint32_t offb[TWO_SRC ? NLD : 1];    // ... of the pixel (y/2, x/2) or (y, x) in low
+    uint32_t inside = 0;                 // bit j: pixel j lies inside the image
     auto plan = [&](const TilePos &tp) {
         const int tx = tp.tx, ty = tp.ty, n = tp.n;
+        inside = 0;
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
             int p = tid + NT * j;
@@ -368,16 +376,17 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
             const int yy = ty * TH + r - 1, xx = tx * TW + c - 1;
             const bool in = yy >= 0 && yy < H && xx >= 0 && xx < W;
             const int yc = min(max(yy, 0), H - 1), xc = min(max(xx, 0), W - 1);
-            offa[j] = (uint32_t)((((size_t)n * H + yc) * W + xc) * Cwa) | (in ? 0x80000000u : 0u);
+            offa[j] = (uint32_t)((((size_t)n * H + yc) * W + xc) * Cwa * 4);
+            inside |= (in ? 1u : 0u) << j;
             if (TWO_SRC)   // second source: same pixel, or pixel (y/2, x/2) of a half-size tensor
                 offb[j] = (uint32_t)((((size_t)n * (H >> low_shift) + (yc >> low_shift)) * (W >> low_shift) +
-                                      (xc >> low_shift)) * Cwb);
+                                      (xc >> low_shift)) * Cwb * 4);
         }
     };
     // word k (wave-uniform) of staged pixel j of the virtual input
     auto word = [&](int j, int k) -> uint32_t {
-        if (TWO_SRC && k >= Cwa) return low[offb[j] + (k - Cwa)];
-        return act[(offa[j] & 0x7fffffffu) + k];
+        if (TWO_SRC && k >= Cwa) return __builtin_amdgcn_raw_buffer_load_b32(brs, offb[j], (k - Cwa) * 4, 0);
+        return __builtin_amdgcn_raw_buffer_load_b32(ars, offa[j], k * 4, 0);
     };
     uint2 gq[NLD];
     auto stage_issue = [&](int ks) {
@@ -385,12 +394,16 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
         if (CW_EVEN) {   // both sources have an even word count: one aligned 8-byte load
             if (TWO_SRC && k0 >= Cwa) {
 #pragma unroll
-                for (int j = 0; j < NLD; ++j)
-                    gq[j] = *reinterpret_cast<const uint2 *>(low + offb[j] + (k0 - Cwa));
+                for (int j = 0; j < NLD; ++j) {
+                    const auto v = __builtin_amdgcn_raw_buffer_load_b64(brs, offb[j], (k0 - Cwa) * 4, 0);
+                    gq[j] = make_uint2(v[0], v[1]);
+                }
             } else {
 #pragma unroll
-                for (int j = 0; j < NLD; ++j)
-                    gq[j] = *reinterpret_cast<const uint2 *>(act + (offa[j] & 0x7fffffffu) + k0);
+                for (int j = 0; j < NLD; ++j) {
+                    const auto v = __builtin_amdgcn_raw_buffer_load_b64(ars, offa[j], k0 * 4, 0);
+                    gq[j] = make_uint2(v[0], v[1]);
+                }
             }
         } else {
             const int k1 = min(k0 + 1, Cw - 1);
@@ -410,7 +423,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
             const int r = p / HALO_W, c = p - r * HALO_W;
             uint4 *d = buf + (r * 2) * HALO_W + c;
             const uint32_t a = gq[j].x, b = gq[j].y;
-            const uint32_t k8 = (uint32_t)((int)offa[j] >> 31) & 0x88888888u, k2 = k8 >> 2;
+            const uint32_t k8 = ((inside >> j) & 1u) ? 0x88888888u : 0u, k2 = k8 >> 2;
             const uint32_t l8 = second ? k8 : 0u, l2 = l8 >> 2;
             uint4 e0, e1;
             e0.x = ((a << 3) & k8) | k2; e0.y = ((a << 2) & k8) | k2;
@@ -470,65 +483,52 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
                 if (pt + stride < ptiles) nxt.advance(tstep);
                 plan(nxt);
             }
-            const uint4 *wn_ptr = wk + (size_t)kn * (18 * 64);
             const uint4 *tb = tile[buf] + tb_off;
             // The scheduling fences keep every fetch where it is written: issued as early as
             // its destination registers are free, a whole step ahead of its use.
             stage_issue(kn);
             __builtin_amdgcn_sched_barrier(0);
-            if constexpr (WN == 4) {
-                // The 3 x (RW + 2) activation fragments of the step, in the order they are used
-                // (tap column, then window row), rotate through NB registers: the read of fragment
-                // j + NB is issued right after the matrix instructions of fragment j, so the LDS
-                // latency hides behind the instructions of the NB - 1 fragments in between.
-                constexpr int NF = 3 * (RW + 2);
-                v4i fr[NB];
+            // The 3 x (RW + 2) activation fragments of the step, in the order they are used
+            // (tap column, then window row), rotate through NB registers: the read of fragment
+            // j + NB is issued right after the matrix instructions of fragment j, so the LDS
+            // latency hides behind the instructions of the NB - 1 fragments in between.
+            constexpr int NF = 3 * (RW + 2);
+            v4i fr[NB];
 #pragma unroll
-                for (int j = 0; j < NB; ++j) {
-                    const uint4 b = tb[(j / (RW + 2)) + (j % (RW + 2)) * 2 * HALO_W];
-                    fr[j] = (v4i){(int)b.x, (int)b.y, (int)b.z, (int)b.w};
-                }
+            for (int j = 0; j < NB; ++j) {
+                const uint4 b = tb[(j / (RW + 2)) + (j % (RW + 2)) * 2 * HALO_W];
+                fr[j] = (v4i){(int)b.x, (int)b.y, (int)b.z, (int)b.w};
+            }
 #pragma unroll
-                for (int j = 0; j < NF; ++j) {
-                    const int kx = j / (RW + 2), rho = j % (RW + 2);
+            for (int j = 0; j < NF; ++j) {
+                const int kx = j / (RW + 2), rho = j % (RW + 2);
 #pragma unroll
-                    for (int ky = 0; ky < 3; ++ky) {
-                        const int r = rho - ky;
-                        if (r >= 0 && r < RW) {
+                for (int ky = 0; ky < 3; ++ky) {
+                    const int r = rho - ky;
+                    if (r >= 0 && r < RW) {
 #pragma unroll
-                            for (int m = 0; m < 2; ++m)
-                                acc[r][m] = mfma_f4(Wg[kx][ky][m], fr[j % NB], acc[r][m]);
-                        }
+                        for (int m = 0; m < 2; ++m)
+                            acc[r][m] = mfma_f4(Wg[kx][ky][m], fr[j % NB], acc[r][m]);
                     }
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (j + NB < NF) {
-                        const int jn = j + NB;
-                        const uint4 b = tb[(jn / (RW + 2)) + (jn % (RW + 2)) * 2 * HALO_W];
-                        fr[j % NB] = (v4i){(int)b.x, (int)b.y, (int)b.z, (int)b.w};
-                    }
-                    // the two weight fragments of tap (ky, kx) are free after window row RW - 1 + ky:
-                    // their successors of the next step are fetched at once, two loads per slot
-                    if (rho >= RW - 1) {
-                        const int ky = rho - (RW - 1);
-#pragma unroll
-                        for (int m = 0; m < 2; ++m) {
-                            const auto w = __builtin_amdgcn_raw_buffer_load_b128(
-                                wrs, wlane, (kn * 18 + (ky * 3 + kx) * 2 + m) * 1024, 0);
-                            Wg[kx][ky][m] = (v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
-                        }
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
                 }
-            } else {
-                // the variants with larger staging plans have no registers left for a third
-                // fragment in flight: fragments are read group by group
-#pragma unroll
-                for (int kx = 0; kx < 3; ++kx) {
-                    group_mma<RW, 2>(acc, Wg[kx], tb + kx);
-                    __builtin_amdgcn_sched_barrier(0);
-                    load_group<2>(Wg[kx], wn_ptr, kx);
-                    __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (j + NB < NF) {
+                    const int jn = j + NB;
+                    const uint4 b = tb[(jn / (RW + 2)) + (jn % (RW + 2)) * 2 * HALO_W];
+                    fr[j % NB] = (v4i){(int)b.x, (int)b.y, (int)b.z, (int)b.w};
                 }
+                // the two weight fragments of tap (ky, kx) are free after window row RW - 1 + ky:
+                // their successors of the next step are fetched at once, two loads per slot
+                if (rho >= RW - 1) {
+                    const int ky = rho - (RW - 1);
+#pragma unroll
+                    for (int m = 0; m < 2; ++m) {
+                        const auto w = __builtin_amdgcn_raw_buffer_load_b128(
+                            wrs, wlane, (kn * 18 + (ky * 3 + kx) * 2 + m) * 1024, 0);
+                        Wg[kx][ky][m] = (v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
             buf ^= 1;
             stage_commit(kn, tile[buf]);
@@ -734,8 +734,9 @@ static int launch_block_t(const ConvIO &io, int N, int H, int W, const BlobLayou
     const int tiles64 = L.cout_pad64 / 64;
     long tiles = (long)N * ceil_div(H, RW * WM) * ceil_div(W, TW);
     if (tiles > 0x7fffffffL) return fail(MBU_ERR_SHAPE, "too many tiles for one launch");
-    if ((double)N * H * W * io.cwa >= 2147483648.0)
-        return fail(MBU_ERR_SHAPE, "input tensor too large for one launch (2^31 words)");
+    if ((double)N * H * W * io.cwa * 4 >= 2147483648.0 ||
+        (TWO_SRC && (double)N * (H >> io.low_shift) * (W >> io.low_shift) * io.cwb * 4 >= 2147483648.0))
+        return fail(MBU_ERR_SHAPE, "input tensor too large for one launch (2 GiB)");
     // persistent blocks: two per compute unit in total, spread over the output-channel
     // groups; each strides over the pixel tiles
     const int groups = ceil_div(tiles64, WN);
