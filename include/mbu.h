@@ -68,7 +68,9 @@ int mbu_get_conv_path(void);
  * kernel 0 = let the library choose per layer (default); 1 = block-cooperative kernel
  * (four waves share a staged window, 4 rows x 64 channels per wave); 3 = persistent
  * wave-private kernel with 3 rows x 64 channels per wave; 6 = the same with 6 rows x 32
- * channels.  `reserved` must be 0.  Results never depend on it.  MBU_ERR_ARG otherwise. */
+ * channels; 7 / 8 = row-streaming kernel for layers with at most 64 input channels, two /
+ * one waves per SIMD (7 is what 0 picks for such layers; other layers are not affected).
+ * `reserved` must be 0.  Results never depend on it.  MBU_ERR_ARG otherwise. */
 int mbu_set_conv_tuning(int kernel, int reserved);
 
 /* Bit-packing of activations (Sec. 1: many binary values are grouped into one word
@@ -105,8 +107,9 @@ int mbu_pack_weights(const int8_t *w_ohwi, int Cout, int Cin, void *packed,
  *   thresh    int32 [Cout]
  *   out_bits  packed [N][H][W][Cout/32], or NULL
  *   out_acc   int32 NHWC [N][H][W][Cout], or NULL (debug/parity; costs bandwidth)
- * At least one output must be non-NULL; outputs must not alias `act`.
- * Errors: NULL/misaligned pointers, non-positive dims, Cout % 32 != 0, blob that
+ * At least one output must be non-NULL; outputs must not alias `act`.  On the matrix path a
+ * packed input tensor (each of the two of the fused forms) must stay below 2 GiB.
+ * Errors: NULL/misaligned pointers, non-positive dims, Cout % 32 != 0, input too large; a blob that
  * was packed for other (Cout, Cin) is undefined behaviour (checked only by size
  * arguments, the header is device memory). */
 int mbu_conv3x3_masked_binary(const uint32_t *act, int N, int H, int W, int Cin,

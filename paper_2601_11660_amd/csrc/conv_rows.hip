@@ -27,8 +27,6 @@
 
 namespace mbu {
 
-namespace {
-
 constexpr int RS_HW = 34;               // halo pixels per staged row
 constexpr int RS_ROW = 2 * RS_HW;       // uint4 entries per staged row: [half][pixel]
 constexpr int RS_RING = 2;              // staged rows kept in LDS
@@ -336,7 +334,7 @@ __global__ __launch_bounds__(256, WPS) void conv_mfma_rows_kernel(
 }
 
 template <bool POOL, int WPS>
-int launch_rows_t(const uint32_t *act, int N, int H, int W, const BlobLayout &L, const uint4 *wfrag,
+static int launch_rows_t(const uint32_t *act, int N, int H, int W, const BlobLayout &L, const uint4 *wfrag,
                   const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, hipStream_t s)
 {
     const int ctiles = L.cout_pad64 / 64;
@@ -361,8 +359,6 @@ int launch_rows_t(const uint32_t *act, int N, int H, int W, const BlobLayout &L,
                    out_pool);
     return check_launch("conv_mfma_rows");
 }
-
-}  // namespace
 
 bool conv_rows_supported(int H, int W, const BlobLayout &L, const uint32_t *out_bits)
 {
