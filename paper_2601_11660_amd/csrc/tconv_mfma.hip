@@ -15,6 +15,7 @@
 // multiplies.
 #include "mbu_internal.h"
 #include "mfma_common.h"
+#include <algorithm>
 
 namespace mbu {
 
@@ -218,6 +219,181 @@ __global__ __launch_bounds__(256, 2) void tconv_mfma_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------------
+// Fast kernel (packed bits only): the same wave tile - one position, RG rows x 32 input
+// pixels x 64 output channels - but persistent.  A block keeps its 64-channel tile and strides
+// over the pixel groups; the work of a wave is the flat sequence of (group, 64-channel step),
+// and during every step the words and the two weight fragments of the step after the next -
+// possibly the next group's - are fetched through buffer resources (lane offsets in
+// registers, step offsets in scalar registers) into the free one of three register sets.  A group's first step takes -theta as the addend of its matrix instructions
+// (no accumulator initialisation); its last step is followed by the sign collection and the
+// stores.  With one block per pixel group, as in the kernel above, every block paid the
+// latency of a dependent chain of loads before its first matrix instruction: 35 us for
+// 128 -> 64 channels at 512x1024, against 4 us of matrix work.
+template <int RG>
+struct TconvRegs {
+    uint32_t wd[RG];   // packed word (lane half's own) of the RG pixels
+    v4i W[2];          // weight fragments of the two 32-channel tiles
+};
+
+template <int RG>
+__global__ __launch_bounds__(256, RG == 2 ? 4 : 2) void tconv_bits_kernel(
+    const uint32_t *__restrict__ act, int N, int H, int W, int Cw, int ksteps,
+    const uint4 *__restrict__ wfrag, int Cout, int groups, int groups_x, int groups_y,
+    const int32_t *__restrict__ thresh, uint32_t *__restrict__ out_bits)
+{
+    constexpr uint32_t BAD = 0x40000000u;   // beyond any tensor this kernel accepts (< 2^30 bytes)
+    const int lane = threadIdx.x & 63;
+    const int p = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // position of this wave
+    const int ct = blockIdx.y;                                        // 64-channel output tile
+    const int col = lane & 31, half = lane >> 5;
+    const int Cow = Cout >> 5;
+    const int dy = p >> 1, dx = p & 1;
+    const uint32_t psel = half ? 0x07060302u : 0x05040100u;
+
+    const __amdgpu_buffer_rsrc_t ars =
+        __builtin_amdgcn_make_buffer_rsrc((void *)act, 0, N * H * W * Cw * 4, 0x00020000);
+    const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(wfrag + (size_t)ct * ksteps * 8 * 64), 0, ksteps * 8 * 1024, 0x00020000);
+    const __amdgpu_buffer_rsrc_t ors =
+        __builtin_amdgcn_make_buffer_rsrc((void *)out_bits, 0, N * H * W * 4 * Cow * 4, 0x00020000);
+    const int wlane = lane * 16;
+    // output word of this lane inside a row of output pixels, for pixel group column 0
+    const uint32_t out_lane = (ct * 2 + half < Cow) ? (uint32_t)(((2 * col + dx) * Cow + ct * 2 + half) * 4) : BAD;
+
+    // ---- -theta for the 2 x 16 channels of this lane
+    v16f init[2];
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+        const int cbase = ct * 64 + m * 32 + 16 * half;
+        int th[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) th[i] = 0;
+        if (cbase < Cout) {
+            const int4 *tp = reinterpret_cast<const int4 *>(thresh + cbase);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int4 t = tp[q];
+                th[4 * q] = t.x; th[4 * q + 1] = t.y; th[4 * q + 2] = t.z; th[4 * q + 3] = t.w;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) init[m][i] = 0.0f - (float)max(-(1 << 22), min(1 << 22, th[i]));
+    }
+
+    // ---- per-group plan: byte offset of the lane's word 0 of each of the RG pixels (clamped
+    // to the image) and whether the pixel exists
+    struct Plan { uint32_t off[RG]; uint32_t k8[RG]; int gx, gy, n; };
+    auto plan = [&](int g) {
+        Plan P;
+        P.gx = g % groups_x;
+        const int q = g / groups_x;
+        P.gy = q % groups_y;
+        P.n = q / groups_y;
+        const int x = P.gx * 32 + col;
+        const int xc = min(x, W - 1);
+#pragma unroll
+        for (int r = 0; r < RG; ++r) {
+            const int y = P.gy * RG + r;
+            const int yc = min(y, H - 1);
+            P.off[r] = (uint32_t)((((P.n * H + yc) * W + xc) * Cw + half) * 4);
+            P.k8[r] = (x < W && y < H) ? 0x88888888u : 0u;
+        }
+        return P;
+    };
+    // a word index past the pixel's last word (odd word count) reads the next pixel's first
+    // word, or 0 past the end of the tensor: it is expanded with a zero mask either way
+    auto fetch = [&](const Plan &P, int ks, TconvRegs<RG> &R) {
+#pragma unroll
+        for (int r = 0; r < RG; ++r) R.wd[r] = __builtin_amdgcn_raw_buffer_load_b32(ars, P.off[r], ks * 8, 0);
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            const auto w = __builtin_amdgcn_raw_buffer_load_b128(wrs, wlane, ((ks * 4 + p) * 2 + m) * 1024, 0);
+            R.W[m] = (v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
+        }
+    };
+
+    // compute cursor (g, ks, cur) and fetch cursor (gf, kf, pf), which runs two steps ahead:
+    // with ksteps >= 2 it is one or (ksteps = 2, at a group's last step) two groups ahead;
+    // `pp` is the plan of the group it left last
+    const int stride = gridDim.x;
+    int g = blockIdx.x;
+    if (g >= groups) return;
+    Plan cur = plan(g);
+    Plan pf = cur, pp = cur;
+    int gf = g, kf = 0;
+    TconvRegs<RG> S0, S1, S2;
+    auto fetch_next = [&](TconvRegs<RG> &R) {
+        fetch(pf, kf, R);
+        if (++kf == ksteps) {
+            kf = 0;
+            gf += stride;
+            pp = pf;
+            if (gf < groups) pf = plan(gf);     // past the last group: the same data again, unused
+        }
+    };
+    fetch_next(S0);
+    fetch_next(S1);
+    v16f acc[RG][2];
+    int ks = 0;
+
+    // one step with the register set R; the data of the step after the next goes to Rf.
+    // Returns false when the wave has finished its last group.
+    auto step = [&](const TconvRegs<RG> &R, TconvRegs<RG> &Rf) -> bool {
+        fetch_next(Rf);
+        __builtin_amdgcn_sched_barrier(0);
+        const bool live = 2 * ks + half < Cw;          // second word of an odd word count
+        v4i B[RG];
+#pragma unroll
+        for (int r = 0; r < RG; ++r) {
+            const uint32_t m8 = live ? cur.k8[r] : 0u, m2 = m8 >> 2;
+            const uint32_t word = R.wd[r];
+            B[r] = (v4i){(int)(((word << 3) & m8) | m2), (int)(((word << 2) & m8) | m2),
+                         (int)(((word << 1) & m8) | m2), (int)((word & m8) | m2)};
+        }
+        if (ks == 0) {
+#pragma unroll
+            for (int r = 0; r < RG; ++r)
+#pragma unroll
+                for (int m = 0; m < 2; ++m) acc[r][m] = mfma_f4(R.W[m], B[r], init[m]);
+        } else {
+#pragma unroll
+            for (int r = 0; r < RG; ++r)
+#pragma unroll
+                for (int m = 0; m < 2; ++m) acc[r][m] = mfma_f4(R.W[m], B[r], acc[r][m]);
+        }
+        if (++ks < ksteps) return true;
+        // ---- epilogue: input pixel (y, x) -> output pixel (2y + dy, 2x + dx)
+        const uint32_t lane_off = (cur.gx * 32 + col < W) ? out_lane + (uint32_t)(cur.gx * 64 * Cow * 4) : BAD;
+#pragma unroll
+        for (int r = 0; r < RG; ++r) {
+            const int y = cur.gy * RG + r;
+            uint32_t s0 = 0, s1 = 0;
+#pragma unroll
+            for (int i = 15; i >= 0; --i) {
+                s0 = __builtin_amdgcn_alignbit(s0, __float_as_uint(acc[r][0][i]), 31);
+                s1 = __builtin_amdgcn_alignbit(s1, __float_as_uint(acc[r][1][i]), 31);
+            }
+            const uint32_t word = finish_word64(s0, s1, psel);
+            if (y < H) {
+                const uint32_t row_off = (uint32_t)((((cur.n * 2 * H + 2 * y + dy) * 2 * W) * Cow) * 4);
+                __builtin_amdgcn_raw_buffer_store_b32(word, ors, lane_off + row_off, 0, 0);
+            }
+        }
+        ks = 0;
+        g += stride;
+        cur = gf == g ? pf : pp;
+        return g < groups;
+    };
+
+#pragma unroll 1
+    for (;;) {
+        if (!step(S0, S2)) break;
+        if (!step(S1, S0)) break;
+        if (!step(S2, S1)) break;
+    }
+}
+
 int launch_tconv_mfma(const uint32_t *act, int N, int H, int W, const TconvLayout &L,
                       const void *blob, const int32_t *thresh, uint32_t *out_bits, int32_t *out_acc,
                       hipStream_t s)
@@ -226,6 +402,21 @@ int launch_tconv_mfma(const uint32_t *act, int N, int H, int W, const TconvLayou
     const long groups = (long)N * groups_y * groups_x;
     if (groups > 0x7fffffffL) return fail(MBU_ERR_SHAPE, "too many pixel groups for one launch");
     const uint4 *wfrag = (const uint4 *)((const uint8_t *)blob + L.off_f4);
+    // packed bits only, at least two input steps, every tensor below 1 GiB: the persistent
+    // kernel, two blocks per compute unit spread over the 64-channel tiles
+    const int tiles64 = L.cout_pad64 / 64;
+    const double GiB = 1073741824.0;
+    if (!out_acc && L.ksteps >= 2 && (double)N * H * W * L.cin_words * 4 < GiB && (double)N * H * W * 4 * (L.cout >> 5) * 4 < GiB &&
+        (double)L.ksteps * 8 * 1024 < GiB) {
+        constexpr int RGF = RG;
+        const int gy2 = ceil_div(H, RGF);
+        const long groups2 = (long)N * gy2 * groups_x;
+        if (groups2 > 0x7fffffffL) return fail(MBU_ERR_SHAPE, "too many pixel groups for one launch");
+        const int per_tile = (int)std::min(groups2, (long)std::max(1, 512 / tiles64));
+        MBU_LAUNCH(tconv_bits_kernel<RGF>, dim3((unsigned)per_tile, (unsigned)tiles64), dim3(256), 0, s, act, N, H,
+                   W, L.cin_words, L.ksteps, wfrag, L.cout, (int)groups2, groups_x, gy2, thresh, out_bits);
+        return check_launch("tconv2x2_masked_binary");
+    }
     dim3 grid((unsigned)groups, (unsigned)(L.cout_pad64 / 64));   // 4 waves = the 4 positions
     if (out_acc)
         MBU_LAUNCH(tconv_mfma_kernel<true>, grid, dim3(256), 0, s, act, N, H, W, L.cin_words,
