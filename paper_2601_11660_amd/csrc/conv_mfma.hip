@@ -827,6 +827,8 @@ int launch_conv_mfma_two(const uint32_t *act, int Ca, const uint32_t *low, int C
                          int N, int H, int W, const BlobLayout &L, const void *blob,
                          const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, hipStream_t s)
 {
+    if (low && low_shift == 1 && g_tune_rw != 1 && conv_upcat_supported(Ca, Clow, N, H, W, L, out_bits, out_pool))
+        return launch_conv_mfma_upcat(act, Ca, low, Clow, N, H, W, L, blob, thresh, out_bits, s);
     if (!low && rows_kernel_waves() && conv_rows_supported(H, W, L, out_bits))
         return launch_conv_mfma_rows(act, N, H, W, L, blob, thresh, out_bits, out_pool, rows_kernel_waves(), s);
     const uint4 *wfrag = (const uint4 *)((const uint8_t *)blob + L.off_f4);

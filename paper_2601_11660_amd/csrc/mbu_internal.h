@@ -30,13 +30,16 @@ inline size_t round_up(size_t v, size_t m) { return (v + m - 1) / m * m; }
 // Section M (matrix-core path): 4-bit codes, uint4 [cout_pad64/64][ksteps][9 taps][2][64 lanes],
 // one 16-byte fragment per lane and (32 output channels, tap, 64 input channels); the 18
 // fragments one wave needs for a 64-channel step are contiguous (18 KB).
+// Section U (matrix-core path, input channels that arrive 2x up-sampled): the 3x3 kernel summed
+// over the taps that share a low-resolution pixel, 4-bit codes of sums in -4..4,
+// uint4 [cout_pad64/64][ksteps][4 parity classes][2][2][2][64 lanes].
 struct BlobLayout {
     int cout, cin;
     int cin_words;     // ceil(cin/32)
     int cout_pad64;    // cout rounded up to 64
     int ksteps;        // ceil(cin/64): 64-channel steps of the matrix path
     int cout_tiles32;  // cout/32
-    size_t off_pos, off_neg, off_cnt, off_f4, total;
+    size_t off_pos, off_neg, off_cnt, off_f4, off_up, total;
 };
 BlobLayout blob_layout(int cout, int cin);
 
@@ -90,6 +93,13 @@ int launch_conv_mfma_rows(const uint32_t *act, int N, int H, int W, const BlobLa
 // does the matrix path write the 2x2-pooled output of this layer from its own epilogue?
 // (layers with several input steps always; single-step layers when the row-streaming kernel runs)
 bool conv_writes_pooled(int H, int W, const BlobLayout &L);
+// [skip | 2x up-sampled low] with the up-sampled channels contracted at low resolution
+int launch_pack_upcat(const int8_t *w, const BlobLayout &L, void *blob, hipStream_t s);
+bool conv_upcat_supported(int Ca, int Clow, int N, int H, int W, const BlobLayout &L, const uint32_t *out_bits,
+                          const uint32_t *out_pool);
+int launch_conv_mfma_upcat(const uint32_t *act, int Ca, const uint32_t *low, int Clow, int N, int H, int W,
+                           const BlobLayout &L, const void *blob, const int32_t *thresh, uint32_t *out_bits,
+                           hipStream_t s);
 int launch_pack_tconv(const int8_t *w, const TconvLayout &L, void *blob, hipStream_t s);
 int launch_tconv_mfma(const uint32_t *act, int N, int H, int W, const TconvLayout &L,
                       const void *blob, const int32_t *thresh, uint32_t *out_bits, int32_t *out_acc,

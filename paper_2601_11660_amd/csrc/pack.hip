@@ -155,7 +155,9 @@ int launch_pack_weights(const int8_t *w, const BlobLayout &L, void *blob, hipStr
     if (rc) return rc;
     MBU_LAUNCH(count_kept_kernel, dim3(ceil_div(L.cout_pad64, 256)), dim3(256), 0, s, L,
                        (uint8_t *)blob);
-    return check_launch("count_kept");
+    rc = check_launch("count_kept");
+    if (rc) return rc;
+    return launch_pack_upcat(w, L, blob, s);
 }
 
 }  // namespace mbu
