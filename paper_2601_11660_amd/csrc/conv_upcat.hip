@@ -17,7 +17,8 @@
 // of one class, i.e. every second pixel of every second row, and its accumulator tile is
 // 4 rows x 32 columns x 64 channels as in the other kernels.  Per 64-channel step of the skip
 // tensor the block stages a 10 x 66 pixel window, columns split by parity so that a wave's
-// stride-2 fragments are contiguous in LDS; per step of the low tensor a 6 x 34 window.
+// stride-2 fragments are contiguous in LDS; per 128 channels of the low tensor (two steps: a
+// low step is only 32 matrix instructions per wave, too few per barrier) a 6 x 34 window.
 // Everything else - FP4 codes, -theta start, fragments rotating through three registers,
 // fetches a step ahead through buffer resources, persistent blocks - is as in conv_mfma.hip.
 #include "mbu_internal.h"
@@ -33,7 +34,8 @@ constexpr int UC_A_ROW = 2 * 2 * 33;          // uint4 per window row: [half][pa
 constexpr int UC_B_ROWS = UC_RW + 2;          // low window: 6 rows
 constexpr int UC_B_COLS = 34;
 constexpr int UC_B_ROW = 2 * 34;              // uint4 per window row: [half][34]
-constexpr int UC_TILE = UC_A_ROWS * UC_A_ROW; // the larger of the two windows
+constexpr int UC_B_SLICE = UC_B_ROWS * UC_B_ROW;   // one 64-channel slice of the low window
+constexpr int UC_TILE = UC_A_ROWS * UC_A_ROW; // the larger of the two windows (2 low slices: 816)
 
 __global__ __launch_bounds__(256, 2) void conv_mfma_upcat_kernel(
     const uint32_t *__restrict__ act, const uint32_t *__restrict__ low, int N, int H, int W, int ksA,
@@ -53,7 +55,9 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_upcat_kernel(
     const int col = lane & 31, half = lane >> 5;
     const int Hl = H >> 1, Wl = W >> 1;
     const int Cwa = 2 * ksA, Cwb = 2 * ksL;
-    const int steps = ksA + ksL;
+    // units of work per tile: ksA steps of 64 skip channels, then ksL / 2 steps of 128 low channels
+    // (a low step is only 4 taps: two of them per barrier)
+    const int units = ksA + (ksL >> 1);
     const int ct = blockIdx.y;                   // 64-channel output tile of the block
 
     if (col < 8) {   // lanes (half, col < 8) write float4 number col of their half
@@ -73,8 +77,9 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_upcat_kernel(
         __builtin_amdgcn_make_buffer_rsrc((void *)act, 0, N * H * W * Cwa * 4, 0x00020000);
     const __amdgpu_buffer_rsrc_t brs =
         __builtin_amdgcn_make_buffer_rsrc((void *)low, 0, N * Hl * Wl * Cwb * 4, 0x00020000);
-    // 3x3 fragments [tile64][skip+low steps][tap][m][lane]; combined fragments
-    // [tile64][skip+low steps][class][a][b][m][lane] (only the low steps of either are read)
+    // 3x3 fragments [tile64][64-channel step][tap][m][lane]; combined fragments
+    // [tile64][64-channel step][class][a][b][m][lane] (steps count skip and low channels alike)
+    const int steps = ksA + ksL;
     const __amdgpu_buffer_rsrc_t w3 = __builtin_amdgcn_make_buffer_rsrc(
         (void *)(wfrag + (size_t)ct * steps * (18 * 64)), 0, steps * (18 * 1024), 0x00020000);
     const __amdgpu_buffer_rsrc_t wu = __builtin_amdgcn_make_buffer_rsrc(
@@ -84,7 +89,23 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_upcat_kernel(
     // ---- staging plan.  Skip window: pixel p = tid + 256 j -> window row p / 66, column p % 66
     // (image pixel (2 Y0 - 1 + row, 2 X0 - 1 + column)), stored at [row][half][column parity]
     // [column / 2].  Low window: pixel tid -> row tid / 34, column tid % 34 (low pixel
-    // (Y0 - 1 + row, X0 - 1 + column)), stored at [row][half][column].
+    // (Y0 - 1 + row, X0 - 1 + column)), stored at [64-channel slice][row][half][column].
+    // The LDS positions do not depend on the tile: two registers hold the four of them.
+    uint32_t dst01, dst2b;
+    {
+        int d[NLA];
+#pragma unroll
+        for (int j = 0; j < NLA; ++j) {
+            int p = tid + 256 * j;
+            p = p < UC_A_ROWS * UC_A_COLS ? p : 0;      // surplus threads duplicate pixel 0
+            const int r = p / UC_A_COLS, c = p - r * UC_A_COLS;
+            d[j] = r * UC_A_ROW + (c & 1) * 33 + (c >> 1);
+        }
+        const int p = tid < UC_B_ROWS * UC_B_COLS ? tid : 0;
+        const int r = p / UC_B_COLS, c = p - r * UC_B_COLS;
+        dst01 = (uint32_t)d[0] | ((uint32_t)d[1] << 16);
+        dst2b = (uint32_t)d[2] | ((uint32_t)(r * UC_B_ROW + c) << 16);
+    }
     uint32_t offa[NLA], offb;     // byte offsets of the (clamped) pixels
     uint32_t inside = 0;          // bits 0..2: skip pixels inside the image; bit 3: low pixel
     auto plan = [&](const TilePos &tp) {
@@ -112,16 +133,17 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_upcat_kernel(
         }
     };
     uint2 gq[NLA];
-    auto stage_issue = [&](int s) {
-        if (s < ksA) {
+    auto stage_issue = [&](int u) {
+        if (u < ksA) {
 #pragma unroll
             for (int j = 0; j < NLA; ++j) {
-                const auto v = __builtin_amdgcn_raw_buffer_load_b64(ars, offa[j], s * 8, 0);
+                const auto v = __builtin_amdgcn_raw_buffer_load_b64(ars, offa[j], u * 8, 0);
                 gq[j] = make_uint2(v[0], v[1]);
             }
-        } else {
-            const auto v = __builtin_amdgcn_raw_buffer_load_b64(brs, offb, (s - ksA) * 8, 0);
+        } else {   // four words: two 64-channel slices
+            const auto v = __builtin_amdgcn_raw_buffer_load_b128(brs, offb, (u - ksA) * 16, 0);
             gq[0] = make_uint2(v[0], v[1]);
+            gq[1] = make_uint2(v[2], v[3]);
         }
     };
     auto expand_store = [&](uint2 g, bool in, uint4 *d0, uint4 *d1) {
@@ -135,51 +157,48 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_upcat_kernel(
         *d0 = e0;
         *d1 = e1;
     };
-    auto commit_skip = [&](uint4 *buf) {
+    auto stage_commit = [&](int u, uint4 *buf) {
+        if (u < ksA) {
 #pragma unroll
-        for (int j = 0; j < NLA; ++j) {
-            int p = tid + 256 * j;
-            p = p < UC_A_ROWS * UC_A_COLS ? p : 0;      // surplus threads duplicate pixel 0
-            const int r = p / UC_A_COLS, c = p - r * UC_A_COLS;
-            uint4 *d = buf + r * UC_A_ROW + (c & 1) * 33 + (c >> 1);
-            expand_store(gq[j], (inside >> j) & 1u, d, d + 2 * 33);
-        }
-    };
-    auto commit_low = [&](uint4 *buf) {
-        const int p = tid < UC_B_ROWS * UC_B_COLS ? tid : 0;
-        const int r = p / UC_B_COLS, c = p - r * UC_B_COLS;
-        uint4 *d = buf + r * UC_B_ROW + c;
-        expand_store(gq[0], (inside >> 3) & 1u, d, d + 34);
-    };
-    auto stage_commit = [&](int s, uint4 *buf) {
-        if (s < ksA) commit_skip(buf);
-        else commit_low(buf);
-    };
-
-    // ---- weights of a step in registers: Wg[kx][ky][m] for a skip step; a low step uses the
-    // four slots kx = b < 2, ky = a < 2 for the combined taps (a, b) of this wave's class
-    v4i Wg[3][3][2];
-    // fragments of step s into slot (kx, ky): the 3x3 tap (ky, kx), or - for a low step, slots
-    // kx, ky < 2 only - the combined tap (a, b) = (ky, kx) of this wave's class.  One load
-    // instruction either way: resource and offset are selected with scalar instructions.
-    auto load_w = [&](int s, int kx, int ky) {
-        const bool up = s >= ksA;
-        if (kx < 2 && ky < 2) {
-            const __amdgpu_buffer_rsrc_t rs = up ? wu : w3;
-            const int off = up ? (s * 32 + ((wave * 2 + ky) * 2 + kx) * 2) * 1024 : (s * 18 + (ky * 3 + kx) * 2) * 1024;
-#pragma unroll
-            for (int m = 0; m < 2; ++m) {
-                const auto w = __builtin_amdgcn_raw_buffer_load_b128(rs, wlane, off + m * 1024, 0);
-                Wg[kx][ky][m] = (v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
+            for (int j = 0; j < NLA; ++j) {
+                const uint32_t at = j == 0 ? (dst01 & 0xffffu) : j == 1 ? (dst01 >> 16) : (dst2b & 0xffffu);
+                expand_store(gq[j], (inside >> j) & 1u, buf + at, buf + at + 2 * 33);
             }
         } else {
-            // a low step does not use this slot: it is loaded all the same (from the last skip step)
-            const int s3 = min(s, ksA - 1);
+            const uint32_t at = dst2b >> 16;
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+                expand_store(gq[q], (inside >> 3) & 1u, buf + q * UC_B_SLICE + at, buf + q * UC_B_SLICE + at + 34);
+        }
+    };
+
+    // ---- weights of a unit in registers.  Skip step: Wg[kx][ky][m] = tap (ky, kx).  Low double
+    // step: the combined taps (a, b) of this wave's class for slice 0 in slots (kx, ky) = (b, a),
+    // for slice 1 in slots (2, a) [b = 0] and (a, 2) [b = 1]; slot (2, 2) is idle.
+    v4i Wg[3][3][2];
+    // One load instruction per fragment whatever the unit's kind: resource and offset are
+    // selected with scalar instructions.
+    auto load_w = [&](int u, int kx, int ky) {
+        const bool up = u >= ksA;
+        if (kx == 2 && ky == 2) {
+            const int s3 = min(u, ksA - 1);     // idle in a low unit: loaded all the same
 #pragma unroll
             for (int m = 0; m < 2; ++m) {
-                const auto w = __builtin_amdgcn_raw_buffer_load_b128(w3, wlane, (s3 * 18 + (ky * 3 + kx) * 2 + m) * 1024, 0);
-                Wg[kx][ky][m] = (v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
+                const auto w = __builtin_amdgcn_raw_buffer_load_b128(w3, wlane, (s3 * 18 + 8 * 2 + m) * 1024, 0);
+                Wg[2][2][m] = (v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
             }
+            return;
+        }
+        const int q = (kx < 2 && ky < 2) ? 0 : 1;
+        const int b = q == 0 ? kx : (kx == 2 ? 0 : 1);
+        const int a = q == 0 ? ky : (kx == 2 ? ky : kx);
+        const int sl = ksA + 2 * (u - ksA) + q;          // 64-channel step of the slice
+        const __amdgpu_buffer_rsrc_t rs = up ? wu : w3;
+        const int off = up ? (sl * 32 + ((wave * 2 + a) * 2 + b) * 2) * 1024 : (u * 18 + (ky * 3 + kx) * 2) * 1024;
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            const auto w = __builtin_amdgcn_raw_buffer_load_b128(rs, wlane, off + m * 1024, 0);
+            Wg[kx][ky][m] = (v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
         }
     };
 
@@ -194,15 +213,11 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_upcat_kernel(
     stage_commit(0, tile[0]);
     __syncthreads();
 
-    // fragment addresses of this lane (uint4 units from the start of a window buffer)
-    int baseA[3], baseB[2];
-#pragma unroll
-    for (int kx = 0; kx < 3; ++kx) {
-        const int s = dx + kx;                  // window column = 2 * col + s
-        baseA[kx] = dy * UC_A_ROW + half * 66 + (s & 1) * 33 + (s >> 1) + col;
-    }
-#pragma unroll
-    for (int b = 0; b < 2; ++b) baseB[b] = dy * UC_B_ROW + half * 34 + dx + b + col;
+    // fragment addresses of this lane (uint4 units from the start of a window buffer): window
+    // column 2 col + dx + kx lies in parity plane (dx + kx) & 1 at index col + (dx + kx) / 2
+    const int baseX = dy * UC_A_ROW + half * 66 + (dx & 1) * 33 + col;                        // kx = 0; kx = 2: + 1
+    const int baseY = dy * UC_A_ROW + half * 66 + ((dx + 1) & 1) * 33 + ((dx + 1) >> 1) + col;  // kx = 1
+    const int baseB = dy * UC_B_ROW + half * 34 + dx + col;                                   // + b
 
     const int Cow = Cout >> 5;
     const int widx = ct * 2 + half;
@@ -223,15 +238,16 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_upcat_kernel(
             }
 
         // ---- skip steps: fragment (kx, t) is window row dy + t, t = 2 r + ky; 27 fragments
-        for (int s = 0; s < ksA; ++s) {
-            const int sn = s + 1;                   // a skip step or the first low step
+        for (int u = 0; u < ksA; ++u) {
+            const int un = u + 1;                   // a skip step or the first low unit
             const uint4 *tb = tile[buf];
-            stage_issue(sn);
+            stage_issue(un);
             __builtin_amdgcn_sched_barrier(0);
             constexpr int NF = 27;
             v4i fr[NB];
             auto frag = [&](int j) {
-                const uint4 b = tb[baseA[j / 9] + (j % 9) * UC_A_ROW];
+                const int kx = j / 9, t = j % 9;
+                const uint4 b = tb[(kx == 1 ? baseY : baseX) + (kx == 2 ? 1 : 0) + t * UC_A_ROW];
                 return (v4i){(int)b.x, (int)b.y, (int)b.z, (int)b.w};
             };
 #pragma unroll
@@ -251,57 +267,60 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_upcat_kernel(
                 __builtin_amdgcn_sched_barrier(0);
                 if (j + NB < NF) fr[j % NB] = frag(j + NB);
                 // tap (ky, kx) is done after t = 2 (RW - 1) + ky
-                if (t >= 2 * (RW - 1)) load_w(sn, kx, t - 2 * (RW - 1));
+                if (t >= 2 * (RW - 1)) load_w(un, kx, t - 2 * (RW - 1));
                 __builtin_amdgcn_sched_barrier(0);
             }
             buf ^= 1;
-            stage_commit(sn, tile[buf]);
+            stage_commit(un, tile[buf]);
             __syncthreads();
         }
-        // ---- low steps: fragment (b, t) is window row dy + t, t = r + a; 10 fragments
-        for (int s = ksA; s < steps; ++s) {
-            const bool last = s + 1 == steps;
-            const int sn = last ? 0 : s + 1;        // a low step, or the next tile's first skip step
+        // ---- low units: fragment (q, b, t) is slice q, window row dy + t, t = r + a; 20 fragments
+        for (int u = ksA; u < units; ++u) {
+            const bool last = u + 1 == units;
+            const int un = last ? 0 : u + 1;        // a low unit, or the next tile's first skip step
             if (last) {
                 TilePos nxt = cur;
                 if (pt + stride < ptiles) nxt.advance(tstep);
                 plan(nxt);
             }
             const uint4 *tb = tile[buf];
-            stage_issue(sn);
+            stage_issue(un);
             __builtin_amdgcn_sched_barrier(0);
-            constexpr int NF = 10;
+            constexpr int NF = 20;
             v4i fr[NB];
             auto frag = [&](int j) {
-                const uint4 b = tb[baseB[j / 5] + (j % 5) * UC_B_ROW];
-                return (v4i){(int)b.x, (int)b.y, (int)b.z, (int)b.w};
+                const int q = j / 10, b = (j % 10) / 5, t = j % 5;
+                const uint4 v = tb[q * UC_B_SLICE + baseB + b + t * UC_B_ROW];
+                return (v4i){(int)v.x, (int)v.y, (int)v.z, (int)v.w};
             };
 #pragma unroll
             for (int j = 0; j < NB; ++j) fr[j] = frag(j);
 #pragma unroll
             for (int j = 0; j < NF; ++j) {
-                const int b = j / 5, t = j % 5;
+                const int q = j / 10, b = (j % 10) / 5, t = j % 5;
 #pragma unroll
                 for (int a = 0; a < 2; ++a) {
                     const int r = t - a;
+                    // slot of the combined tap (a, b) of slice q
+                    const int kx = q == 0 ? b : (b == 0 ? 2 : a), ky = q == 0 ? a : (b == 0 ? a : 2);
                     if (r >= 0 && r < RW) {
 #pragma unroll
-                        for (int m = 0; m < 2; ++m) acc[r][m] = mfma_f4(Wg[b][a][m], fr[j % NB], acc[r][m]);
+                        for (int m = 0; m < 2; ++m) acc[r][m] = mfma_f4(Wg[kx][ky][m], fr[j % NB], acc[r][m]);
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 if (j + NB < NF) fr[j % NB] = frag(j + NB);
-                // combined tap (a, b) is done after t = RW - 1 + a; the slots a low step does
-                // not use are refilled along the way when the next tile's skip step follows
-                if (t >= RW - 1) load_w(sn, b, t - (RW - 1));
-                if (last) {
-                    if (t == 0) load_w(sn, b, 2);
-                    if (b == 0 && t >= 1 && t <= 3) load_w(sn, 2, t - 1);
+                // combined tap (a, b) is done after t = RW - 1 + a: its slot is refilled for the
+                // next unit; the idle slot too when the next tile's skip step follows
+                if (t >= RW - 1) {
+                    const int a = t - (RW - 1);
+                    load_w(un, q == 0 ? b : (b == 0 ? 2 : a), q == 0 ? a : (b == 0 ? a : 2));
                 }
+                if (j == 0 && last) load_w(un, 2, 2);
                 __builtin_amdgcn_sched_barrier(0);
             }
             buf ^= 1;
-            stage_commit(sn, tile[buf]);
+            stage_commit(un, tile[buf]);
             __syncthreads();
         }
 
@@ -381,7 +400,7 @@ bool conv_upcat_supported(int Ca, int Clow, int N, int H, int W, const BlobLayou
                           const uint32_t *out_pool)
 {
     const double lim = 1073741824.0;   // byte offsets are computed in 32 bits
-    return out_bits && !out_pool && Ca > 0 && Clow > 0 && Ca % 64 == 0 && Clow % 64 == 0 && !(H & 1) && !(W & 1) &&
+    return out_bits && !out_pool && Ca > 0 && Clow > 0 && Ca % 64 == 0 && Clow % 128 == 0 && !(H & 1) && !(W & 1) &&
            (double)N * H * W * (Ca / 32) * 4 < lim && (double)N * (H / 2) * (W / 2) * (Clow / 32) * 4 < lim &&
            (double)L.ksteps * 32 * 1024 < lim;
 }
