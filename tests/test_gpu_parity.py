@@ -217,6 +217,51 @@ def test_fused_concat_upsample_pool(shape):
     assert np.array_equal(host_u32(p1), bitref.pack_pm1(O.maxpool2x2(o1)))
 
 
+UPCAT_SHAPES = [
+    # N, H, W, Ca, Clow, Cout, keep: skip channels % 64 == 0 and low channels % 128 == 0
+    (1, 16, 128, 64, 128, 64, 0.6),
+    (2, 10, 140, 64, 128, 96, 1.0),     # ragged tiles both ways, no zero weights: sums reach +-4
+    (1, 2, 2, 64, 128, 32, 0.6),        # one low pixel
+    (1, 36, 132, 128, 256, 64, 0.3),
+    (1, 8, 8, 256, 1024, 128, 0.9),     # many low steps
+    (3, 6, 66, 192, 128, 64, 0.6),      # more skip than low channels
+]
+
+
+@pytest.mark.parametrize("shape", UPCAT_SHAPES)
+def test_upsampled_decoder_kernel_matches_oracle(shape):
+    """Decoder layer over [skip | 2x up-sampled low] (Sec. 2.1) with the up-sampled channels
+    contracted at low resolution (summed taps): bit-exact against the oracle's up-sample,
+    concatenation and layer, and against the library's kernel that reads the window at full
+    resolution."""
+    N, H, W, Ca, Clow, Cout, keep = shape
+    say(f"conv upcat N={N} H={H} W={W} Ca={Ca} Clow={Clow} Cout={Cout} keep={keep}")
+    rng = np.random.default_rng(Ca + Clow + H)
+    skip = synth.pm1_bits(rng, (N, H, W, Ca))
+    low = synth.pm1_bits(rng, (N, H // 2, W // 2, Clow))
+    w = synth.ternary_weights(12, 0, 0, Cout, Ca + Clow, keep)
+    th = synth.thresholds(12, 0, 0, Cout, (9 * (Ca + Clow)) // 16)
+    _, out_ref = O.masked_binary_layer(O.concat(skip, O.upsample2x(low)), w, th)
+    blob = B.pack_weights(dev(w))
+    pa, pl = B.pack_act(dev(skip)), B.pack_act(dev(low))
+    bits, _ = B.conv3x3_masked_binary_fused(pa, Ca, pl, Clow, blob, Cout, dev(th), True, False)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_u32(bits), bitref.pack_pm1(out_ref))
+    B.set_conv_tuning(1)     # the block-cooperative kernel on the same call
+    bits1, _ = B.conv3x3_masked_binary_fused(pa, Ca, pl, Clow, blob, Cout, dev(th), True, False)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_u32(bits1), host_u32(bits))
+    if keep == 1.0:
+        # every summed tap at its extreme (+4 / -4 in the corners of the 2x2 kernels)
+        for sgn in (1, -1):
+            w1 = np.full_like(w, sgn)
+            _, ref1 = O.masked_binary_layer(O.concat(skip, O.upsample2x(low)), w1, th)
+            b1, _ = B.conv3x3_masked_binary_fused(pa, Ca, pl, Clow, B.pack_weights(dev(w1)), Cout, dev(th),
+                                                  True, False)
+            torch.cuda.synchronize()
+            assert np.array_equal(host_u32(b1), bitref.pack_pm1(ref1))
+
+
 TCONV_SHAPES = [
     # N, H, W, Cin, Cout
     (1, 8, 32, 128, 64),
