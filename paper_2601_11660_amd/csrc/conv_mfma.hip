@@ -517,16 +517,16 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
                     const uint4 b = tb[(jn / (RW + 2)) + (jn % (RW + 2)) * 2 * HALO_W];
                     fr[j % NB] = (v4i){(int)b.x, (int)b.y, (int)b.z, (int)b.w};
                 }
-                // the two weight fragments of tap (ky, kx) are free after window row RW - 1 + ky:
-                // their successors of the next step are fetched at once, two loads per slot
-                if (rho >= RW - 1) {
-                    const int ky = rho - (RW - 1);
-#pragma unroll
-                    for (int m = 0; m < 2; ++m) {
-                        const auto w = __builtin_amdgcn_raw_buffer_load_b128(
-                            wrs, wlane, (kn * 18 + (ky * 3 + kx) * 2 + m) * 1024, 0);
-                        Wg[kx][ky][m] = (v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
-                    }
+                // One weight fragment is fetched per slot.  Fragment (kx, ky, m) is free after
+                // window row RW - 1 + ky of column kx; in that order the 18 fragments of the NEXT
+                // step go to slots 3 .. 17 and the last three - tap column 2, first used in slot
+                // 13 - to slots 0 .. 2 of the step that uses them.
+                {
+                    const int i = j < 3 ? 15 + j : j - 3;
+                    const int g = i / 6, ky = (i % 6) >> 1, m = i & 1;
+                    const auto w = __builtin_amdgcn_raw_buffer_load_b128(
+                        wrs, wlane, ((j < 3 ? ks : kn) * 18 + (ky * 3 + g) * 2 + m) * 1024, 0);
+                    Wg[g][ky][m] = (v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
