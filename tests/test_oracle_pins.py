@@ -486,3 +486,36 @@ def test_cost_scores_properties():
     _, order = O.cost_scores([o for o, _ in layers], [p for _, p in layers], 1.0)
     assert set(order[:4].tolist()) == set(range(len(pairs), len(pairs) + 4))
     assert 5 * max(o for o, _ in ups) <= min(o for o, _ in pairs)
+
+
+def test_upsampled_channels_collapse_to_2x2_kernels_at_low_resolution():
+    """Identity the decoder kernel of the library relies on (a property of the definitions of
+    nearest up-sampling and of the zero-padded 3x3 layer, Sec. 2.1 / Sec. 3.1.1): the layer on
+    the up-sampled tensor equals, for every output parity class (dy, dx), a 2x2 kernel over the
+    low-resolution tensor whose entries are sums of the 3x3 taps that fall on the same low pixel
+    (rows {Y-1, Y, Y} for dy = 0, {Y, Y, Y+1} for dy = 1), with zero padding of the low tensor.
+    Checked on the oracle's accumulators, borders included; the summed entries stay in -4..4."""
+    rng = np.random.default_rng(5)
+    N, Hl, Wl, C, Co = 2, 3, 5, 6, 4
+    low = synth.pm1_bits(rng, (N, Hl, Wl, C))
+    w = rng.integers(-1, 2, size=(Co, 3, 3, C)).astype(np.int8)
+    acc, _ = O.masked_binary_layer(O.upsample2x(low), w, np.zeros(Co, np.int32))
+    taps = {0: ([0], [1, 2]), 1: ([0, 1], [2])}     # parity -> 3x3 indices on low offset 0 / 1
+    pad = np.zeros((N, Hl + 2, Wl + 2, C), np.int64)
+    pad[:, 1:-1, 1:-1] = low
+    for dy in (0, 1):
+        for dx in (0, 1):
+            k2 = np.zeros((Co, 2, 2, C), np.int64)
+            for a in (0, 1):
+                for b in (0, 1):
+                    for ky in taps[dy][a]:
+                        for kx in taps[dx][b]:
+                            k2[:, a, b] += w[:, ky, kx]
+            assert np.abs(k2).max() <= 4
+            got = np.zeros((N, Hl, Wl, Co), np.int64)
+            for a in (0, 1):
+                for b in (0, 1):
+                    # low pixel (Y - 1 + dy + a, X - 1 + dx + b), in padded coordinates + 1
+                    win = pad[:, dy + a:dy + a + Hl, dx + b:dx + b + Wl]
+                    got += np.einsum("nyxc,oc->nyxo", win, k2[:, a, b])
+            assert np.array_equal(got, acc[:, dy::2, dx::2]), (dy, dx)
