@@ -66,7 +66,8 @@ int mbu_get_conv_path(void);
 
 /* Benchmarking hook: force the kernel variant of the matrix-path convolution process-wide.
  * kernel 0 = let the library choose per layer (default); 1 = block-cooperative kernel
- * (four waves share a staged window, 4 rows x 64 channels per wave); 3 = persistent
+ * (four waves share a staged window, 4 rows x 64 channels per wave; also instead of the
+ * low-resolution kernel of layers with a 2x up-sampled second input); 3 = persistent
  * wave-private kernel with 3 rows x 64 channels per wave; 6 = the same with 6 rows x 32
  * channels; 7 / 8 = row-streaming kernel for layers with at most 64 input channels, two /
  * one waves per SIMD (7 is what 0 picks for such layers; other layers are not affected).

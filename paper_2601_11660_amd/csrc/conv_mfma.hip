@@ -692,7 +692,7 @@ static int rows_kernel_waves() { return (g_tune_rw == 0 || g_tune_rw == 7) ? 2 :
 bool conv_writes_pooled(int H, int W, const BlobLayout &L)
 {
     if ((H & 1) || (W & 1)) return false;
-    return L.ksteps > 1 || (rows_kernel_waves() && conv_rows_supported(H, W, L, (const uint32_t *)16));
+    return L.ksteps > 1 || (rows_kernel_waves() && conv_rows_supported(H, W, L, true));
 }
 
 template <int RW, int MT, bool CW_EVEN, bool ONE_STEP>
@@ -814,7 +814,7 @@ int launch_conv_mfma(const uint32_t *act, int N, int H, int W, const BlobLayout 
         ConvIO io{act, nullptr, 0, L.cin_words, 0, out_bits, nullptr};
         return launch_block_auto(io, N, H, W, L, wfrag, thresh, s);
     }
-    if (rows_kernel_waves() && conv_rows_supported(H, W, L, out_bits))
+    if (rows_kernel_waves() && conv_rows_supported(H, W, L, out_bits != nullptr))
         return launch_conv_mfma_rows(act, N, H, W, L, blob, thresh, out_bits, nullptr, rows_kernel_waves(), s);
     if (mode == 6) return launch_bits<6, 1>(act, N, H, W, L, wfrag, thresh, out_bits, s);
     return launch_bits<3, 2>(act, N, H, W, L, wfrag, thresh, out_bits, s);
@@ -829,7 +829,7 @@ int launch_conv_mfma_two(const uint32_t *act, int Ca, const uint32_t *low, int C
 {
     if (low && low_shift == 1 && g_tune_rw != 1 && conv_upcat_supported(Ca, Clow, N, H, W, L, out_bits, out_pool))
         return launch_conv_mfma_upcat(act, Ca, low, Clow, N, H, W, L, blob, thresh, out_bits, s);
-    if (!low && rows_kernel_waves() && conv_rows_supported(H, W, L, out_bits))
+    if (!low && rows_kernel_waves() && conv_rows_supported(H, W, L, out_bits != nullptr))
         return launch_conv_mfma_rows(act, N, H, W, L, blob, thresh, out_bits, out_pool, rows_kernel_waves(), s);
     const uint4 *wfrag = (const uint4 *)((const uint8_t *)blob + L.off_f4);
     ConvIO io{act, low, low ? low_shift : 0, ceil_div(Ca, 32), low ? ceil_div(Clow, 32) : 0,

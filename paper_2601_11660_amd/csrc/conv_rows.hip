@@ -360,10 +360,10 @@ static int launch_rows_t(const uint32_t *act, int N, int H, int W, const BlobLay
     return check_launch("conv_mfma_rows");
 }
 
-bool conv_rows_supported(int H, int W, const BlobLayout &L, const uint32_t *out_bits)
+bool conv_rows_supported(int H, int W, const BlobLayout &L, bool wants_bits)
 {
     // one input step, packed output wanted, every image below 2^30 bytes on both sides
-    return L.ksteps == 1 && out_bits != nullptr && (double)H * W * L.cin_words * 4 < 1073741824.0 &&
+    return L.ksteps == 1 && wants_bits && (double)H * W * L.cin_words * 4 < 1073741824.0 &&
            (double)H * W * (L.cout >> 5) * 4 < 1073741824.0;
 }
 
@@ -371,7 +371,7 @@ int launch_conv_mfma_rows(const uint32_t *act, int N, int H, int W, const BlobLa
                           const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, int waves_per_simd,
                           hipStream_t s)
 {
-    if (!conv_rows_supported(H, W, L, out_bits))
+    if (!conv_rows_supported(H, W, L, out_bits != nullptr))
         return fail(MBU_ERR_SHAPE, "row-streaming kernel: layer not supported");
     if (out_pool && ((H & 1) || (W & 1))) return fail(MBU_ERR_SHAPE, "pooled output needs even H and W");
     const uint4 *wfrag = (const uint4 *)((const uint8_t *)blob + L.off_f4);
