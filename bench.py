@@ -345,7 +345,7 @@ def main():
             "peak": PEAK_FP4_TFLOPS if mfma else PEAK_VALU_BIT_TOPS,
             "unit": "TFLOP/s" if mfma else "TOP/s",
             "frac": round(achieved / (PEAK_FP4_TFLOPS if mfma else PEAK_VALU_BIT_TOPS), 4),
-            "traffic": traffic_from_profile(),
+            "traffic": traffic_from_profile() if mfma else None,
             "algorithmic_bytes_per_launch": round(conv_bytes / n_conv),
             "launches_per_step": n_conv,
             "avg_launch_ms": round(conv_ms / n_conv, 4),
