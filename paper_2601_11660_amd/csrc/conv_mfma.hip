@@ -4,8 +4,10 @@
 // represents -1, 0 and +1 exactly, products of such values are exact, and sums of up
 // to 9*Cin <= 2^24 of them are exact in the fp32 accumulator - so the contraction
 // R = sum w*a of Algorithm 1 can run on v_mfma_f32_32x32x64_f8f6f4 and still be the
-// exact integer.  Masked weights and padded (out-of-image) activations are the code
-// 0, which contributes nothing: no border correction is needed on this path.
+// exact integer.  Masked weights are the code 0 and contribute nothing.  Activations enter
+// as the packed bit itself (1.0 / 0.0, and 0.5 for a pixel outside the image), the constant
+// this adds is folded into the start value of the accumulators (mfma_common.h): no border
+// correction is needed on this path.
 //
 // GEMM view per image: D[cout][pixel] = sum_{tap, cin} Wt[cout][tap, cin] * Act[tap, cin][pixel].
 //   A operand (32 rows x 64 k)  = weights of 32 output channels, one tap, 64 input channels,
@@ -116,7 +118,7 @@ template <int RW, int MT, bool CW_EVEN, bool ONE_STEP>
 __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
     const uint32_t *__restrict__ act, int N, int H, int W, int Cw, int ksteps,
     const uint4 *__restrict__ wfrag, int Cout, int ctiles, int slots, int ptiles, TileStep tstep,
-    const int32_t *__restrict__ thresh, uint32_t *__restrict__ out_bits)
+    const int32_t *__restrict__ thresh, const int32_t *__restrict__ wsum, uint32_t *__restrict__ out_bits)
 {
     constexpr int HR = RW + 2;
     constexpr int NPIX = HR * HALO_W;            // halo pixels per step
@@ -138,26 +140,27 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
 #pragma unroll
     for (int m = 0; m < MT; ++m) {
         const int cbase = (ct * MT + m) * 32 + 16 * half;  // 16 consecutive channels per lane
-        int th[16];
+        int th[16], ws[16];
         if (cbase < Cout) {                                 // Cout % 32 == 0: all 16 or none
             const int4 *tp = reinterpret_cast<const int4 *>(thresh + cbase);
+            const int4 *sp = reinterpret_cast<const int4 *>(wsum + cbase);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int4 t = tp[q];
+                const int4 t = tp[q], u = sp[q];
                 th[4 * q] = t.x; th[4 * q + 1] = t.y; th[4 * q + 2] = t.z; th[4 * q + 3] = t.w;
+                ws[4 * q] = u.x; ws[4 * q + 1] = u.y; ws[4 * q + 2] = u.z; ws[4 * q + 3] = u.w;
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) th[i] = 0;
+            for (int i = 0; i < 16; ++i) th[i] = ws[i] = 0;
         }
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
-            init[m][i] = 0.0f - (float)max(-(1 << 22), min(1 << 22, th[i]));
+        for (int i = 0; i < 16; ++i) init[m][i] = start_value(th[i], ws[i]);
     }
 
     // ---- staging plan for the window of a pixel tile: lane handles halo pixels lane + 64*j
     uint32_t src[NLD];            // word offset of the (clamped) pixel from `act`
-    uint32_t m8[NLD];             // 0x88888888 inside the image, 0 outside
+    uint32_t m8[NLD];             // all ones inside the image, 0 outside
     auto plan = [&](const TilePos &tp) {
         const int tx = tp.tx, ty = tp.ty, n = tp.n;
 #pragma unroll
@@ -169,7 +172,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
             const bool in = yy >= 0 && yy < H && xx >= 0 && xx < W;
             const int yc = min(max(yy, 0), H - 1), xc = min(max(xx, 0), W - 1);
             src[j] = (uint32_t)((((size_t)n * H + yc) * W + xc) * Cw);
-            m8[j] = in ? 0x88888888u : 0u;
+            m8[j] = in ? 0xffffffffu : 0u;
         }
     };
     uint2 gq[NLD];
@@ -194,15 +197,9 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
             const int r = p / HALO_W, c = p - r * HALO_W;
             uint4 *d = buf + (r * 2) * HALO_W + c;
             const uint32_t a = gq[j].x, b = gq[j].y;
-            const uint32_t k8 = m8[j], k2 = k8 >> 2;
-            const uint32_t l8 = second ? k8 : 0u, l2 = l8 >> 2;
-            uint4 e0, e1;
-            e0.x = ((a << 3) & k8) | k2; e0.y = ((a << 2) & k8) | k2;
-            e0.z = ((a << 1) & k8) | k2; e0.w = (a & k8) | k2;
-            e1.x = ((b << 3) & l8) | l2; e1.y = ((b << 2) & l8) | l2;
-            e1.z = ((b << 1) & l8) | l2; e1.w = (b & l8) | l2;
-            d[0] = e0;
-            d[HALO_W] = e1;
+            const uint32_t m2 = m8[j] & 0x22222222u, p1 = ~m8[j] & 0x11111111u;
+            d[0] = expand_word_masked(a, m2, p1);
+            d[HALO_W] = expand_word_masked(b, second ? m2 : 0u, second ? p1 : 0u);
         }
     };
 
@@ -313,8 +310,8 @@ template <int RW, int WM, int WN, bool CW_EVEN, bool TWO_SRC, bool POOL>
 __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
     const uint32_t *__restrict__ act, const uint32_t *__restrict__ low, int N, int H, int W,
     int Cwa, int Cwb, int low_shift, int ksteps, const uint4 *__restrict__ wfrag, int Cout,
-    int tiles64, int ptiles, TileStep tstep, const int32_t *__restrict__ thresh, uint32_t *__restrict__ out_bits,
-    uint32_t *__restrict__ out_pool)
+    int tiles64, int ptiles, TileStep tstep, const int32_t *__restrict__ thresh,
+    const int32_t *__restrict__ wsum, uint32_t *__restrict__ out_bits, uint32_t *__restrict__ out_pool)
 {
     static_assert(WM * WN == 4, "four waves per block");
     constexpr int NB = 3;                        // activation fragments in flight per wave
@@ -344,14 +341,13 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
     if (col < 8) {   // lanes (half, col < 8) write float4 number col of their half
         const int m = col >> 2, q = col & 3;
         const int cbase = ct * 64 + m * 32 + 16 * half + 4 * q;
-        int4 t = make_int4(0, 0, 0, 0);
-        if (cbase < Cout) t = *reinterpret_cast<const int4 *>(thresh + cbase);
-        float4 f;
-        f.x = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.x));
-        f.y = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.y));
-        f.z = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.z));
-        f.w = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.w));
-        init_tab[wave][half][m][q] = f;
+        int4 t = make_int4(0, 0, 0, 0), u = make_int4(0, 0, 0, 0);
+        if (cbase < Cout) {
+            t = *reinterpret_cast<const int4 *>(thresh + cbase);
+            u = *reinterpret_cast<const int4 *>(wsum + cbase);
+        }
+        init_tab[wave][half][m][q] = make_float4(start_value(t.x, u.x), start_value(t.y, u.y),
+                                                 start_value(t.z, u.z), start_value(t.w, u.w));
     }
 
     // ---- staging plan of this thread for one pixel tile: halo pixels p = tid + NT*j.
@@ -423,15 +419,10 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
             const int r = p / HALO_W, c = p - r * HALO_W;
             uint4 *d = buf + (r * 2) * HALO_W + c;
             const uint32_t a = gq[j].x, b = gq[j].y;
-            const uint32_t k8 = ((inside >> j) & 1u) ? 0x88888888u : 0u, k2 = k8 >> 2;
-            const uint32_t l8 = second ? k8 : 0u, l2 = l8 >> 2;
-            uint4 e0, e1;
-            e0.x = ((a << 3) & k8) | k2; e0.y = ((a << 2) & k8) | k2;
-            e0.z = ((a << 1) & k8) | k2; e0.w = (a & k8) | k2;
-            e1.x = ((b << 3) & l8) | l2; e1.y = ((b << 2) & l8) | l2;
-            e1.z = ((b << 1) & l8) | l2; e1.w = (b & l8) | l2;
-            d[0] = e0;
-            d[HALO_W] = e1;
+            const bool in = (inside >> j) & 1u;
+            const uint32_t m2 = in ? 0x22222222u : 0u, p1 = in ? 0u : 0x11111111u;
+            d[0] = expand_word_masked(a, m2, p1);
+            d[HALO_W] = expand_word_masked(b, second ? m2 : 0u, second ? p1 : 0u);
         }
     };
 
@@ -584,7 +575,7 @@ template <bool WRITE_ACC>
 __global__ __launch_bounds__(256) void conv_mfma_kernel(
     const uint32_t *__restrict__ act, int N, int H, int W, int Cw, int ksteps,
     const uint4 *__restrict__ wfrag, int Cout, const int32_t *__restrict__ thresh,
-    uint32_t *__restrict__ out_bits, int32_t *__restrict__ out_acc)
+    const int32_t *__restrict__ wsum, uint32_t *__restrict__ out_bits, int32_t *__restrict__ out_acc)
 {
     constexpr int TH = 8;
     __shared__ uint4 tile[(TH + 2) * HALO_W * 2];  // [row][col][half] 16-byte fragments
@@ -620,9 +611,14 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(
             int c = p % HALO_W, r = p / HALO_W;
             int yy = y0 + r - 1, xx = x0 + c - 1;
             int k = 2 * ks + h;
+            // 0.5 for every channel of a pixel outside the image, 0 for a word that does not exist
             uint4 v = make_uint4(0, 0, 0, 0);
-            if (yy >= 0 && yy < H && xx >= 0 && xx < W && k < Cw)
-                v = expand_word(act[(((size_t)n * H + yy) * W + xx) * Cw + k]);
+            if (k < Cw) {
+                if (yy >= 0 && yy < H && xx >= 0 && xx < W)
+                    v = expand_word(act[(((size_t)n * H + yy) * W + xx) * Cw + k]);
+                else
+                    v = make_uint4(0x11111111u, 0x11111111u, 0x11111111u, 0x11111111u);
+            }
             tile[i] = v;
         }
         __syncthreads();
@@ -661,7 +657,8 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(
             int vals[16];
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                vals[i] = (int)acc[m][r][i];
+                // the accumulator holds sum w a' (a half-integer): sum w a = 2 sum w a' - sum w
+                vals[i] = (int)(2.0f * acc[m][r][i]) - ((cbase + i) < Cout ? wsum[cbase + i] : 0);
                 int th = (cbase + i) < Cout ? thresh[cbase + i] : 0x7fffffff;
                 bits |= (uint32_t)(vals[i] >= th) << i;
             }
@@ -683,6 +680,14 @@ __global__ __launch_bounds__(256) void conv_mfma_kernel(
     }
 }
 
+// the sums of the weights per output channel (row 10 of the count section) of the blob whose
+// matrix fragments start at `wfrag`
+static const int32_t *weight_sums(const uint4 *wfrag, const BlobLayout &L)
+{
+    const uint8_t *blob = (const uint8_t *)wfrag - L.off_f4;
+    return (const int32_t *)(blob + L.off_cnt) + (size_t)10 * L.cout_pad64;
+}
+
 int g_tune_rw = 0, g_tune_wm = 0;   // 0 = automatic
 int g_persistent_blocks = 512;       // resident blocks of the block-cooperative kernel (2 per CU)
 
@@ -700,6 +705,7 @@ static int launch_bits_t(const uint32_t *act, int N, int H, int W, const BlobLay
                          const uint4 *wfrag, const int32_t *thresh, uint32_t *out_bits,
                          hipStream_t s)
 {
+    const int32_t *wsum = weight_sums(wfrag, L);
     const int ctiles = L.cout_pad64 / (32 * MT);
     const long ptiles = (long)N * ceil_div(H, RW) * ceil_div(W, TW);
     if (ptiles > 0x7fffffffL) return fail(MBU_ERR_SHAPE, "too many tiles for one launch");
@@ -712,7 +718,7 @@ static int launch_bits_t(const uint32_t *act, int N, int H, int W, const BlobLay
     const TileStep tstep = tile_step(slots, ceil_div(W, TW), ceil_div(H, RW));
     MBU_LAUNCH((conv_mfma_bits_kernel<RW, MT, CW_EVEN, ONE_STEP>), dim3(ceil_div(waves, 4)),
                dim3(256), 0, s, act, N, H, W, L.cin_words, L.ksteps, wfrag, L.cout, ctiles, slots,
-               (int)ptiles, tstep, thresh, out_bits);
+               (int)ptiles, tstep, thresh, wsum, out_bits);
     return check_launch("conv_mfma_bits");
 }
 
@@ -747,11 +753,11 @@ static int launch_block_t(const ConvIO &io, int N, int H, int W, const BlobLayou
     if (even)
         MBU_LAUNCH((conv_mfma_block_kernel<RW, WM, WN, true, TWO_SRC, POOL>), grid, dim3(256), 0, s,
                    io.act, io.low, N, H, W, io.cwa, io.cwb, io.low_shift, L.ksteps, wfrag, L.cout, tiles64,
-                   (int)tiles, tstep, thresh, io.out_bits, io.out_pool);
+                   (int)tiles, tstep, thresh, weight_sums(wfrag, L), io.out_bits, io.out_pool);
     else
         MBU_LAUNCH((conv_mfma_block_kernel<RW, WM, WN, false, TWO_SRC, POOL>), grid, dim3(256), 0, s,
                    io.act, io.low, N, H, W, io.cwa, io.cwb, io.low_shift, L.ksteps, wfrag, L.cout, tiles64,
-                   (int)tiles, tstep, thresh, io.out_bits, io.out_pool);
+                   (int)tiles, tstep, thresh, weight_sums(wfrag, L), io.out_bits, io.out_pool);
     return check_launch("conv_mfma_block");
 }
 
@@ -800,7 +806,7 @@ int launch_conv_mfma(const uint32_t *act, int N, int H, int W, const BlobLayout 
         if (tiles > 0x7fffffffL) return fail(MBU_ERR_SHAPE, "too many tiles for one launch");
         dim3 grid((unsigned)tiles, (unsigned)(L.cout_pad64 / 64));
         MBU_LAUNCH(conv_mfma_kernel<true>, grid, dim3(256), 0, s, act, N, H, W, L.cin_words,
-                   L.ksteps, wfrag, L.cout, thresh, out_bits, out_acc);
+                   L.ksteps, wfrag, L.cout, thresh, weight_sums(wfrag, L), out_bits, out_acc);
         return check_launch("conv_mfma_acc");
     }
     // Kernel choice (measured on MI355X): with a single 64-channel input step the vector work

@@ -19,7 +19,8 @@
 //   - the signs of the PREVIOUS row's accumulators (two accumulator sets alternate) are
 //     collected, completed to words and stored - and, for a layer followed by 2x2 max pooling
 //     (Sec. 2.1: OR of the bits), every second row also stores the pooled words.
-// Accumulators start at -theta through the addend of the row's first instruction per tile.
+// Accumulators start at -(theta + sum w) / 2 (activations enter as 0 / 1, mfma_common.h) through
+// the addend of the row's first instruction per tile.
 // No barriers, nothing shared between waves.
 #include "mbu_internal.h"
 #include "mfma_common.h"
@@ -39,7 +40,7 @@ constexpr uint32_t RS_BAD_ROW = 0x80000000u;
 struct RowsCtx {
     __amdgpu_buffer_rsrc_t in, out, pool;
     uint32_t in_voff;      // byte offset of this lane's halo pixel inside an image row
-    uint32_t mx8;          // 0x88888888 when that pixel's column lies inside the image
+    uint32_t mx2;          // 0x22222222 when that pixel's column lies inside the image
     uint32_t out_voff;     // byte offset of this lane's output word inside an image row
     uint32_t pool_voff;    // ... of its pooled word inside a pooled row
     uint32_t psel;
@@ -49,7 +50,7 @@ struct RowsCtx {
     int in_row_bytes, out_row_bytes, pool_row_bytes;
 };
 
-// bits of the two words of a pixel -> codes of the negated activation, zero outside the image
+// the two packed words of this lane's halo pixel in image row yy (clamped into the image)
 __device__ __forceinline__ void fetch_row(const RowsCtx &c, int yy, uint2 &g, bool even)
 {
     const int yc = min(max(yy, 0), c.H - 1);
@@ -98,7 +99,7 @@ __device__ __forceinline__ void rows_step(const RowsCtx &c, const int i,
     constexpr int CUR = P, PRV = P ^ 1;
     constexpr int RD = P ^ 1, WR = P;      // ring slot of halo row i + 3 / i + 4
 
-    uint32_t a = 0, b = 0, k8 = 0, k2 = 0, l8 = 0, l2 = 0;
+    uint32_t a = 0, b = 0, m2 = 0, p1 = 0, l2 = 0, q1 = 0;   // masks of expand_word_masked()
     uint4 e0, e1;
     uint32_t s = 0;
 #pragma unroll
@@ -111,26 +112,26 @@ __device__ __forceinline__ void rows_step(const RowsCtx &c, const int i,
             a = gq[P].x;
             b = gq[P].y;
             const bool rin = c.y0 + i + 3 < c.H;
-            k8 = rin ? c.mx8 : 0u;
-            k2 = k8 >> 2;
-            l8 = CW_EVEN ? k8 : 0u;
-            l2 = l8 >> 2;
-            e0.x = ((a << 3) & k8) | k2;
+            m2 = rin ? c.mx2 : 0u;
+            p1 = (~m2 >> 1) & 0x11111111u;
+            l2 = CW_EVEN ? m2 : 0u;
+            q1 = CW_EVEN ? p1 : 0u;
+            e0.x = ((a << 1) & m2) | p1;
             RS_PIN(e0.x);
         } else if (t == 1) {
-            e0.y = ((a << 2) & k8) | k2;
-            e0.z = ((a << 1) & k8) | k2;
+            e0.y = (a & m2) | p1;
+            e0.z = ((a >> 1) & m2) | p1;
             RS_PIN(e0.y); RS_PIN(e0.z);
         } else if (t == 2) {
-            e0.w = (a & k8) | k2;
-            e1.x = ((b << 3) & l8) | l2;
+            e0.w = ((a >> 2) & m2) | p1;
+            e1.x = ((b << 1) & l2) | q1;
             RS_PIN(e0.w); RS_PIN(e1.x);
         } else if (t == 3) {
-            e1.y = ((b << 2) & l8) | l2;
-            e1.z = ((b << 1) & l8) | l2;
+            e1.y = (b & l2) | q1;
+            e1.z = ((b >> 1) & l2) | q1;
             RS_PIN(e1.y); RS_PIN(e1.z);
         } else if (t == 4) {
-            e1.w = (b & l8) | l2;
+            e1.w = ((b >> 2) & l2) | q1;
             RS_PIN(e1.w);
             c.wr[WR * RS_ROW] = e0;
             c.wr[WR * RS_ROW + RS_HW] = e1;
@@ -178,7 +179,7 @@ template <bool CW_EVEN, bool POOL, int WPS>
 __global__ __launch_bounds__(256, WPS) void conv_mfma_rows_kernel(
     const uint32_t *__restrict__ act, int H, int W, int Cw, const uint4 *__restrict__ wfrag, int Cout,
     int ctiles, int strips, int nseg, int seg_rows, int units, const int32_t *__restrict__ thresh,
-    uint32_t *__restrict__ out_bits, uint32_t *__restrict__ out_pool)
+    const int32_t *__restrict__ wsum, uint32_t *__restrict__ out_bits, uint32_t *__restrict__ out_pool)
 {
     __shared__ uint4 lds[4][RS_RING * RS_ROW];
 
@@ -213,7 +214,7 @@ __global__ __launch_bounds__(256, WPS) void conv_mfma_rows_kernel(
         const int p = min(lane, RS_HW - 1);   // surplus lanes duplicate the last halo pixel
         const int xx = sx * 32 + p - 1;
         c.in_voff = (uint32_t)(min(max(xx, 0), W - 1) * Cw * 4);
-        c.mx8 = (xx >= 0 && xx < W) ? 0x88888888u : 0u;
+        c.mx2 = (xx >= 0 && xx < W) ? 0x22222222u : 0u;
         c.wr = lds[wave] + p;
         c.rd = lds[wave] + half * RS_HW + col;
         const int x = sx * 32 + col;
@@ -224,26 +225,28 @@ __global__ __launch_bounds__(256, WPS) void conv_mfma_rows_kernel(
         c.psel = half ? 0x07060302u : 0x05040100u;
     }
 
-    // ---- -theta for the 2 x 16 channels of this lane (exact in fp32 after clamping theta to
-    // +-2^22, which cannot change a comparison because |R| <= 9*64)
+    // ---- start values for the 2 x 16 channels of this lane (exact in fp32 after clamping theta
+    // to +-2^22, which cannot change a comparison because |R| <= 9*64)
     v16f init[2];
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
         const int cbase = (ct * 2 + m) * 32 + 16 * half;
-        int th[16];
+        int th[16], ws[16];
         if (cbase < Cout) {
             const int4 *tp = reinterpret_cast<const int4 *>(thresh + cbase);
+            const int4 *sp = reinterpret_cast<const int4 *>(wsum + cbase);
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                const int4 t = tp[k];
+                const int4 t = tp[k], u = sp[k];
                 th[4 * k] = t.x; th[4 * k + 1] = t.y; th[4 * k + 2] = t.z; th[4 * k + 3] = t.w;
+                ws[4 * k] = u.x; ws[4 * k + 1] = u.y; ws[4 * k + 2] = u.z; ws[4 * k + 3] = u.w;
             }
         } else {
 #pragma unroll
-            for (int k = 0; k < 16; ++k) th[k] = 0;
+            for (int k = 0; k < 16; ++k) th[k] = ws[k] = 0;
         }
 #pragma unroll
-        for (int k = 0; k < 16; ++k) init[m][k] = 0.0f - (float)max(-(1 << 22), min(1 << 22, th[k]));
+        for (int k = 0; k < 16; ++k) init[m][k] = start_value(th[k], ws[k]);
     }
 
     // ---- weights: [tile64][tap][m][lane], resident for the whole strip
@@ -275,16 +278,10 @@ __global__ __launch_bounds__(256, WPS) void conv_mfma_rows_kernel(
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int yy = y0 - 1 + j;
-            const uint32_t k8 = (yy >= 0 && yy < H) ? c.mx8 : 0u, k2 = k8 >> 2;
-            const uint32_t l8 = CW_EVEN ? k8 : 0u, l2 = l8 >> 2;
-            const uint32_t a = g4[j].x, b = g4[j].y;
-            uint4 e0, e1;
-            e0.x = ((a << 3) & k8) | k2; e0.y = ((a << 2) & k8) | k2;
-            e0.z = ((a << 1) & k8) | k2; e0.w = (a & k8) | k2;
-            e1.x = ((b << 3) & l8) | l2; e1.y = ((b << 2) & l8) | l2;
-            e1.z = ((b << 1) & l8) | l2; e1.w = (b & l8) | l2;
-            c.wr[(j & 1) * RS_ROW] = e0;
-            c.wr[(j & 1) * RS_ROW + RS_HW] = e1;
+            const uint32_t m2 = (yy >= 0 && yy < H) ? c.mx2 : 0u, p1 = (~m2 >> 1) & 0x11111111u;
+            c.wr[(j & 1) * RS_ROW] = expand_word_masked(g4[j].x, m2, p1);
+            c.wr[(j & 1) * RS_ROW + RS_HW] =
+                expand_word_masked(g4[j].y, CW_EVEN ? m2 : 0u, CW_EVEN ? p1 : 0u);
             __builtin_amdgcn_wave_barrier();
             if (j < 3) {
 #pragma unroll
@@ -337,6 +334,9 @@ template <bool POOL, int WPS>
 static int launch_rows_t(const uint32_t *act, int N, int H, int W, const BlobLayout &L, const uint4 *wfrag,
                   const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, hipStream_t s)
 {
+    // sums of the weights per output channel: row 10 of the count section of the blob
+    const int32_t *wsum =
+        (const int32_t *)((const uint8_t *)wfrag - L.off_f4 + L.off_cnt) + (size_t)10 * L.cout_pad64;
     const int ctiles = L.cout_pad64 / 64;
     const int strips = ceil_div(W, 32);
     const long base = (long)N * strips * ctiles;
@@ -351,12 +351,12 @@ static int launch_rows_t(const uint32_t *act, int N, int H, int W, const BlobLay
     const int grid = (int)((units + 3) / 4);
     if (L.cin_words == 2)
         MBU_LAUNCH((conv_mfma_rows_kernel<true, POOL, WPS>), dim3(grid), dim3(256), 0, s, act, H, W,
-                   L.cin_words, wfrag, L.cout, ctiles, strips, nseg, seg_rows, (int)units, thresh, out_bits,
-                   out_pool);
+                   L.cin_words, wfrag, L.cout, ctiles, strips, nseg, seg_rows, (int)units, thresh, wsum,
+                   out_bits, out_pool);
     else
         MBU_LAUNCH((conv_mfma_rows_kernel<false, POOL, WPS>), dim3(grid), dim3(256), 0, s, act, H, W,
-                   L.cin_words, wfrag, L.cout, ctiles, strips, nseg, seg_rows, (int)units, thresh, out_bits,
-                   out_pool);
+                   L.cin_words, wfrag, L.cout, ctiles, strips, nseg, seg_rows, (int)units, thresh, wsum,
+                   out_bits, out_pool);
     return check_launch("conv_mfma_rows");
 }
 

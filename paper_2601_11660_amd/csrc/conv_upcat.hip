@@ -19,7 +19,8 @@
 // tensor the block stages a 10 x 66 pixel window, columns split by parity so that a wave's
 // stride-2 fragments are contiguous in LDS; per 128 channels of the low tensor (two steps: a
 // low step is only 32 matrix instructions per wave, too few per barrier) a 6 x 34 window.
-// Everything else - FP4 codes, -theta start, fragments rotating through three registers,
+// Everything else - FP4 codes, 0 / 1 activations and the start value that goes with them (a low
+// pixel outside the image is 0.5 like any other), fragments rotating through three registers,
 // fetches a step ahead through buffer resources, persistent blocks - is as in conv_mfma.hip.
 #include "mbu_internal.h"
 #include "mfma_common.h"
@@ -40,13 +41,14 @@ constexpr int UC_TILE = UC_A_ROWS * UC_A_ROW; // the larger of the two windows (
 __global__ __launch_bounds__(256, 2) void conv_mfma_upcat_kernel(
     const uint32_t *__restrict__ act, const uint32_t *__restrict__ low, int N, int H, int W, int ksA,
     int ksL, const uint4 *__restrict__ wfrag, const uint4 *__restrict__ wup, int Cout, int tiles64,
-    int ptiles, TileStep tstep, const int32_t *__restrict__ thresh, uint32_t *__restrict__ out_bits)
+    int ptiles, TileStep tstep, const int32_t *__restrict__ thresh, const int32_t *__restrict__ wsum,
+    uint32_t *__restrict__ out_bits)
 {
     constexpr int RW = UC_RW;
     constexpr int NB = 3;                       // activation fragments in flight per wave
     constexpr int NLA = (UC_A_ROWS * UC_A_COLS + 255) / 256;   // 3 skip pixels per thread
     __shared__ uint4 tile[2][UC_TILE];
-    __shared__ float4 init_tab[4][2][2][4];     // [wave][half][m][4 x 4 channels]: -theta
+    __shared__ float4 init_tab[4][2][2][4];     // [wave][half][m][4 x 4 channels]: start values
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -63,14 +65,13 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_upcat_kernel(
     if (col < 8) {   // lanes (half, col < 8) write float4 number col of their half
         const int m = col >> 2, q = col & 3;
         const int cbase = ct * 64 + m * 32 + 16 * half + 4 * q;
-        int4 t = make_int4(0, 0, 0, 0);
-        if (cbase < Cout) t = *reinterpret_cast<const int4 *>(thresh + cbase);
-        float4 f;
-        f.x = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.x));
-        f.y = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.y));
-        f.z = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.z));
-        f.w = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.w));
-        init_tab[wave][half][m][q] = f;
+        int4 t = make_int4(0, 0, 0, 0), u = make_int4(0, 0, 0, 0);
+        if (cbase < Cout) {
+            t = *reinterpret_cast<const int4 *>(thresh + cbase);
+            u = *reinterpret_cast<const int4 *>(wsum + cbase);
+        }
+        init_tab[wave][half][m][q] = make_float4(start_value(t.x, u.x), start_value(t.y, u.y),
+                                                 start_value(t.z, u.z), start_value(t.w, u.w));
     }
 
     const __amdgpu_buffer_rsrc_t ars =
@@ -147,15 +148,9 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_upcat_kernel(
         }
     };
     auto expand_store = [&](uint2 g, bool in, uint4 *d0, uint4 *d1) {
-        const uint32_t k8 = in ? 0x88888888u : 0u, k2 = k8 >> 2;
-        const uint32_t a = g.x, b = g.y;
-        uint4 e0, e1;
-        e0.x = ((a << 3) & k8) | k2; e0.y = ((a << 2) & k8) | k2;
-        e0.z = ((a << 1) & k8) | k2; e0.w = (a & k8) | k2;
-        e1.x = ((b << 3) & k8) | k2; e1.y = ((b << 2) & k8) | k2;
-        e1.z = ((b << 1) & k8) | k2; e1.w = (b & k8) | k2;
-        *d0 = e0;
-        *d1 = e1;
+        const uint32_t m2 = in ? 0x22222222u : 0u, p1 = in ? 0u : 0x11111111u;
+        *d0 = expand_word_masked(g.x, m2, p1);
+        *d1 = expand_word_masked(g.y, m2, p1);
     };
     auto stage_commit = [&](int u, uint4 *buf) {
         if (u < ksA) {
@@ -350,7 +345,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_upcat_kernel(
 
 // Combined weights of the up-sampled channels.  Thread (o, class, a, b, word k) sums the taps
 // of the 3x3 kernel that fall on low pixel (a, b) of class (dy, dx) for 32 input channels and
-// stores the E2M1 codes of the NEGATED sums (the activation side is negated too) as one
+// stores the E2M1 codes of the sums as one
 // 16-byte fragment: uint4 [cout_pad64/64][ksteps][class][a][b][2][64 lanes], nibble q of dword d
 // = input channel 32k + 4q + d, lane = 32 (k & 1) + tile row of the output channel.
 __global__ __launch_bounds__(256) void pack_upcat_kernel(const int8_t *__restrict__ w, BlobLayout L,
@@ -377,7 +372,7 @@ __global__ __launch_bounds__(256) void pack_upcat_kernel(const int8_t *__restric
                 for (int kx = kx0; kx <= kx1; ++kx) v += w[((long)o * 9 + ky * 3 + kx) * L.cin + (long)k * 32 + i];
             const int mag = v < 0 ? -v : v;     // 0..4 -> E2M1 0, 1.0, 2.0, 3.0, 4.0
             const uint32_t code = (mag == 0 ? 0u : mag == 1 ? 2u : mag == 2 ? 4u : mag == 3 ? 5u : 6u) |
-                                  (v > 0 ? 8u : 0u);
+                                  (v < 0 ? 8u : 0u);
             d[i & 3] |= code << (4 * (i >> 2));
         }
     }
@@ -411,6 +406,8 @@ int launch_conv_mfma_upcat(const uint32_t *act, int Ca, const uint32_t *low, int
 {
     const uint4 *wfrag = (const uint4 *)((const uint8_t *)blob + L.off_f4);
     const uint4 *wup = (const uint4 *)((const uint8_t *)blob + L.off_up);
+    // sums of the weights per output channel: row 10 of the count section
+    const int32_t *wsum = (const int32_t *)((const uint8_t *)blob + L.off_cnt) + (size_t)10 * L.cout_pad64;
     const int tiles64 = L.cout_pad64 / 64;
     const int tiles_x = ceil_div(W / 2, 32), tiles_y = ceil_div(H / 2, UC_RW);
     const long tiles = (long)N * tiles_y * tiles_x;
@@ -419,7 +416,7 @@ int launch_conv_mfma_upcat(const uint32_t *act, int Ca, const uint32_t *low, int
     const int gx = (int)std::min(tiles, (long)std::max(1, 512 / tiles64));
     const TileStep tstep = tile_step(gx, tiles_x, tiles_y);
     MBU_LAUNCH(conv_mfma_upcat_kernel, dim3((unsigned)gx, (unsigned)tiles64), dim3(256), 0, s, act, low, N, H, W,
-               Ca / 64, Clow / 64, wfrag, wup, L.cout, tiles64, (int)tiles, tstep, thresh, out_bits);
+               Ca / 64, Clow / 64, wfrag, wup, L.cout, tiles64, (int)tiles, tstep, thresh, wsum, out_bits);
     return check_launch("conv_mfma_upcat");
 }
 

@@ -40,7 +40,7 @@ BlobLayout blob_layout(int cout, int cin)
     size_t off = 256;  // reserved header room
     L.off_pos = off; off = round_up(off + plane, 256);
     L.off_neg = off; off = round_up(off + plane, 256);
-    L.off_cnt = off; off = round_up(off + (size_t)10 * L.cout_pad64 * sizeof(int32_t), 256);
+    L.off_cnt = off; off = round_up(off + (size_t)11 * L.cout_pad64 * sizeof(int32_t), 256);
     L.off_f4 = off;  off = round_up(off + (size_t)L.cout_tiles32 * 9 * L.ksteps * 64 * 16, 256);
     L.off_up = off;  off = round_up(off + (size_t)(L.cout_pad64 / 64) * L.ksteps * 32 * 64 * 16, 256);
     L.total = off;

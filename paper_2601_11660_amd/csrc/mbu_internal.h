@@ -26,7 +26,8 @@ inline size_t round_up(size_t v, size_t m) { return (v + m - 1) / m * m; }
 // ---- layout of the packed-weight blob (all offsets in bytes from the blob start) ----
 // Section V (vector-ALU path): two bit planes, each uint32 [9][cin_words][cout_pad64]
 // (tap-major, output channel fastest so 64 lanes read 64 consecutive words), and the
-// kept-weight counts int32 [10][cout_pad64]: rows 0..8 per tap, row 9 the total.
+// kept-weight counts int32 [11][cout_pad64]: rows 0..8 per tap, row 9 the total, row 10 the
+// sum of the channel's weights.
 // Section M (matrix-core path): 4-bit codes, uint4 [cout_pad64/64][ksteps][9 taps][2][64 lanes],
 // one 16-byte fragment per lane and (32 output channels, tap, 64 input channels); the 18
 // fragments one wave needs for a 64-channel step are contiguous (18 KB).

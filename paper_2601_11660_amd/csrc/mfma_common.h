@@ -20,16 +20,39 @@ __device__ inline v16f mfma_f4(v4i a, v4i b, v16f c)
     return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, c, 4, 4, 0, 0, 0, 0);
 }
 
-// bits of one packed word -> 32 E2M1 codes of the NEGATED activation (bit 1 -> 0xA = -1.0,
-// bit 0 -> 0x2 = +1.0); nibble q of dword d carries channel 4q + d.
+// Activations enter the matrix instructions as a' = (a + 1) / 2, i.e. the packed bit itself:
+// code 0x2 (1.0) for bit 1, 0x0 for bit 0, and 0x1 (0.5) for a pixel outside the image, whose
+// value 0 lies half way.  Then sum w a = 2 sum w a' - sum w over ALL taps and channels, borders
+// included, so the constant goes into the threshold: the accumulators start at
+// -(theta + sum w) / 2 and hold half-integers (exact).  Half of the activation nibbles are zero
+// this way; measured on MI355X the multi-step layers run 2-3 % faster than with +-1 codes.
+//
+// bits of one packed word -> 32 E2M1 codes; nibble q of dword d carries channel 4q + d.
 __device__ inline uint4 expand_word(uint32_t w)
 {
     uint4 r;
-    r.x = ((w << 3) & 0x88888888u) | 0x22222222u;
-    r.y = ((w << 2) & 0x88888888u) | 0x22222222u;
-    r.z = ((w << 1) & 0x88888888u) | 0x22222222u;
-    r.w = (w & 0x88888888u) | 0x22222222u;
+    r.x = (w << 1) & 0x22222222u;
+    r.y = w & 0x22222222u;
+    r.z = (w >> 1) & 0x22222222u;
+    r.w = (w >> 2) & 0x22222222u;
     return r;
+}
+// the same under masks: m2 = 0x22222222 and p1 = 0 inside the image, m2 = 0 and p1 = 0x11111111
+// outside (m2 = p1 = 0 for a word the tensor does not have)
+__device__ __forceinline__ uint4 expand_word_masked(uint32_t w, uint32_t m2, uint32_t p1)
+{
+    uint4 r;
+    r.x = ((w << 1) & m2) | p1;
+    r.y = (w & m2) | p1;
+    r.z = ((w >> 1) & m2) | p1;
+    r.w = ((w >> 2) & m2) | p1;
+    return r;
+}
+// -(theta + sum w) / 2 with theta clamped to +-2^22 (which cannot change a comparison);
+// never -0.0, whose sign bit would read as "below the threshold"
+__device__ __forceinline__ float start_value(int theta, int wsum)
+{
+    return 0.0f - 0.5f * (float)(max(-(1 << 22), min(1 << 22, theta)) + wsum);
 }
 
 // Completes the packed output words of one image row from the per-lane sign collections.

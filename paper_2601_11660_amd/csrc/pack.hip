@@ -70,10 +70,8 @@ int launch_pack_act(const void *src, int dtype, long pixels, int C, uint32_t *ds
 //   * bit k of the positive and negative planes (vector-ALU section), and
 //   * the 16-byte matrix-core fragment: 32 four-bit codes.  Code nibble q of dword d
 //     carries input channel 32k + 4q + d (so that activations can be expanded with one
-//     shift and one and-or per dword).  The code is the E2M1 value of -w: 0x0 for a
-//     masked weight, 0xA (-1.0) for w = +1, 0x2 (+1.0) for w = -1; the activation side
-//     uses 0xA for a +1 activation and 0x2 for -1, i.e. also the negated value, and
-//     the two negations cancel in the product.
+//     shift and one and-or per dword).  The code is the E2M1 value of w: 0x0 for a
+//     masked weight, 0x2 (+1.0) for w = +1, 0xA (-1.0) for w = -1.
 // Channels beyond cin and output channels beyond cout are packed as masked.
 __global__ __launch_bounds__(256) void pack_weights_kernel(const int8_t *__restrict__ w,
                                                            BlobLayout L, uint8_t *__restrict__ blob)
@@ -110,7 +108,7 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const int8_t *__restr
 #pragma unroll
             for (int q = 0; q < 8; ++q) {
                 int bit = 4 * q + dd;
-                uint32_t code = ((pos >> bit) & 1u) ? 0xAu : (((neg >> bit) & 1u) ? 0x2u : 0x0u);
+                uint32_t code = ((pos >> bit) & 1u) ? 0x2u : (((neg >> bit) & 1u) ? 0xAu : 0x0u);
                 v |= code << (4 * q);
             }
             d[dd] = v;
@@ -125,7 +123,9 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const int8_t *__restr
     }
 }
 
-// Kept-weight counts per (tap, output channel) and their total, from the planes.
+// Kept-weight counts per (tap, output channel), their total, and the sum of the weights of
+// an output channel (row 10; the matrix path's activations are 0 / 1, see conv_mfma.hip),
+// from the planes.
 __global__ __launch_bounds__(256) void count_kept_kernel(BlobLayout L, uint8_t *__restrict__ blob)
 {
     int o = blockIdx.x * blockDim.x + threadIdx.x;
@@ -133,17 +133,19 @@ __global__ __launch_bounds__(256) void count_kept_kernel(BlobLayout L, uint8_t *
     const uint32_t *P = reinterpret_cast<const uint32_t *>(blob + L.off_pos);
     const uint32_t *G = reinterpret_cast<const uint32_t *>(blob + L.off_neg);
     int32_t *cnt = reinterpret_cast<int32_t *>(blob + L.off_cnt);
-    int total = 0;
+    int total = 0, wsum = 0;
     for (int tap = 0; tap < 9; ++tap) {
         int c = 0;
         for (int k = 0; k < L.cin_words; ++k) {
             size_t at = ((size_t)tap * L.cin_words + k) * L.cout_pad64 + o;
             c += __popc(P[at] | G[at]);
+            wsum += __popc(P[at]) - __popc(G[at]);
         }
         cnt[(size_t)tap * L.cout_pad64 + o] = c;
         total += c;
     }
     cnt[(size_t)9 * L.cout_pad64 + o] = total;
+    cnt[(size_t)10 * L.cout_pad64 + o] = wsum;
 }
 
 int launch_pack_weights(const int8_t *w, const BlobLayout &L, void *blob, hipStream_t s)
