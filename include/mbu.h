@@ -184,8 +184,11 @@ int mbu_concat_bits(const uint32_t *a, int Ca, const uint32_t *b, int Cb,
 typedef enum mbu_stem_path {
     MBU_STEM_AUTO = 0,   /* matrix cores, unless out_pre is requested (default)            */
     MBU_STEM_VALU = 1,   /* the sequential fused-multiply-add chain for every output       */
-    MBU_STEM_MFMA = 2    /* split-bf16 estimate on the matrix cores; outputs whose sign    */
+    MBU_STEM_MFMA = 2,   /* split-fp16 estimate on the matrix cores; outputs whose sign    */
                          /* the estimate cannot decide are recomputed by the chain         */
+    MBU_STEM_MFMA_GATHER = 3  /* the same with the per-pixel gather kernel also for three  */
+                         /* image channels (otherwise a wave walks down a strip of the     */
+                         /* image and shares the split values between patches)             */
 } mbu_stem_path;
 int mbu_set_stem_path(int path);
 int mbu_get_stem_path(void);

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libmbu_hip.so")
 MBU_OK = 0
 MBU_ERR_NULL, MBU_ERR_SHAPE, MBU_ERR_ALIGN, MBU_ERR_WORKSPACE, MBU_ERR_HIP, MBU_ERR_ARG = -1, -2, -3, -4, -5, -6
 PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
-STEM_AUTO, STEM_VALU, STEM_MFMA = 0, 1, 2
+STEM_AUTO, STEM_VALU, STEM_MFMA, STEM_MFMA_GATHER = 0, 1, 2, 3
 
 EXPORTS = [
     "mbu_last_error", "mbu_set_conv_path", "mbu_get_conv_path", "mbu_set_conv_tuning", "mbu_pack_act",

@@ -209,9 +209,10 @@ int mbu_get_conv_path(void) { return g_conv_path; }
 
 int mbu_set_stem_path(int path)
 {
-    if (path != MBU_STEM_AUTO && path != MBU_STEM_VALU && path != MBU_STEM_MFMA)
+    if (path != MBU_STEM_AUTO && path != MBU_STEM_VALU && path != MBU_STEM_MFMA && path != MBU_STEM_MFMA_GATHER)
         return fail(MBU_ERR_ARG, "mbu_set_stem_path: unknown path %d", path);
     g_stem_path = path;
+    g_stem_gather = path == MBU_STEM_MFMA_GATHER;
     return MBU_OK;
 }
 

@@ -116,6 +116,7 @@ int launch_upcat(const uint32_t *skip, int Csw, const uint32_t *low, int Clw,
 // sequential chain for undecided signs; out_pre (NHWC float32) may be NULL
 int launch_stem_valu(const float *img, int N, int Ci, int H, int W, const float *w, int Co,
                      uint32_t *out_bits, float *out_pre, hipStream_t s);
+extern int g_stem_gather;   // set with the stem path: the per-pixel gather kernel everywhere
 int launch_stem_mfma(const float *img, int N, int Ci, int H, int W, const float *w, int Co,
                      uint32_t *out_bits, float *out_pre, hipStream_t s);
 int launch_classifier(const uint32_t *act, int N, int H, int W, int C, const float *w,

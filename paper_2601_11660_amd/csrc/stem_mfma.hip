@@ -38,6 +38,7 @@
 // padded k gets an offset beyond the buffer and reads 0.0f.
 #include "mbu_internal.h"
 #include "mfma_common.h"
+#include <algorithm>
 
 namespace mbu {
 
@@ -421,11 +422,467 @@ __global__ __launch_bounds__(256) void stem_mfma_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------------------
+// Row-walking variant for three image channels.
+//
+// The kernel above gathers and splits all 27 values of every patch although a value belongs
+// to nine patches.  Here a wave walks down a strip of 32 pixel columns; for every image row it
+// keeps the three rows of the 3x3 window as raw floats (lane p = halo pixel p of the strip:
+// 9 values), scales and splits them ONCE per tile and hands them to the 32 patches of the row
+// through wave-private LDS.  Sharing the split values means sharing the scale: instead of one
+// power of two per patch the whole window (3 rows x 34 pixels x 3 channels) is scaled by one
+// power of two s that brings its largest magnitude into [2^13, 2^14).  The error budget of the
+// estimate changes in one place: the remainder of the split is bounded by 2^-22 |v| + 2^-25
+// (the second term is the spacing of fp16 subnormals), and with a patch that is small against
+// its window the absolute term no longer vanishes against the patch norm.  It is therefore part
+// of the decision threshold:
+//     T = kappa * max_o ||w_o|| * ||s x_patch||  +  2^-9
+// (sum_k |w_k| 2^-25 <= sqrt(27) 2^13 2^-25 = 1.3e-3 < 2^-9 for rows scaled to a norm below
+// 2^13).  Outputs with |estimate| <= T take the sequential route as before, so the bits are
+// those of the definition whatever the data; a window that holds values more than ~2^17
+// apart merely sends more of its small patches down that route.  Windows with a non-finite
+// value, or with a largest magnitude below 2^-111, get T = +inf.  The squared patch norm is the
+// sum of three per-pixel column sums exchanged through LDS; a NaN in it makes T NaN and the
+// comparison fail, which is the sequential route again.
+//
+// K order of the matrix instruction (32 terms = 16 dwords of two fp16 values; lane (j, h) of a
+// B operand supplies dwords 8t + 4h + d of block t): the LDS arrays hold one dword per halo
+// pixel p - P_r[p] = channels (0, 1) of window row r, R01[p] = channel 2 of rows (0, 1),
+// R2[p] = (channel 2 of row 2, 0) - and pixel j reads entries j, j + 1, j + 2 (kx = 0, 1, 2):
+//     h = 0:  P0[j] P0[j+1] P0[j+2] P1[j]  |  P1[j+1] P1[j+2] R01[j]   R01[j+1]
+//     h = 1:  P2[j] P2[j+1] P2[j+2] R2[j]  |  R2[j+1] R2[j+2] R01[j+2] (1.0, 0)
+// The last dword is the constant that gives an all-zero weight row a decidable estimate (see
+// the kernel above).  The weights are loaded in the same order.
+constexpr int SR_HW = 34;                    // halo pixels of a strip
+constexpr int SR_ARR = 36;                   // dwords per LDS array (34 used)
+constexpr int SR_PLANE = 5 * SR_ARR;         // arrays P0 P1 R01 P2 R2 of one plane (hi or lo)
+constexpr int SR_CONST = SR_PLANE - 1;       // spare dword of R2: the constant entry
+constexpr int SR_N = 2 * SR_PLANE;           // per halo pixel: squared column norm, OR of the bits
+constexpr int SR_WAVE = SR_N + 2 * SR_ARR;   // dwords per wave
+constexpr float SR_FLOOR = 0x1p-9f;
+
+// index into the 27 weights of an output channel for half h, dword dh = 4t + d, fp16 value e;
+// -1: no term (weight 0), -2: the constant term
+__host__ __device__ constexpr int sr_term(int h, int dh, int e)
+{
+    if (h == 0) {
+        if (dh < 3) return (0 * 3 + dh) * 3 + e;
+        if (dh < 6) return (1 * 3 + (dh - 3)) * 3 + e;
+        return (e * 3 + (dh - 6)) * 3 + 2;
+    }
+    if (dh < 3) return (2 * 3 + dh) * 3 + e;
+    if (dh < 6) return e == 0 ? (2 * 3 + (dh - 3)) * 3 + 2 : -1;
+    if (dh == 6) return (e * 3 + 2) * 3 + 2;
+    return e == 0 ? -2 : -1;
+}
+
+// maximum over the wave of a value that is the same non-negative number in no particular lane
+// order (0 is the identity): shifts inside rows of 16 lanes, then lane 15 of a row into the
+// next row, lane 31 into the upper half; lane 63 holds the result
+__device__ __forceinline__ uint32_t wave_umax(uint32_t x)
+{
+    x = max(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, true));   // row_shr:1
+    x = max(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, true));   // row_shr:2
+    x = max(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, true));   // row_shr:4
+    x = max(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, true));   // row_shr:8
+    x = max(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x142, 0xa, 0xf, false));  // row_bcast:15
+    x = max(x, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x143, 0xc, 0xf, false));  // row_bcast:31
+    return (uint32_t)__builtin_amdgcn_readlane((int)x, 63);
+}
+
+__global__ __launch_bounds__(256, 3) void stem_rows_kernel(
+    const float *__restrict__ img, uint32_t img_bytes, int H, int W, const float *__restrict__ w, int Co,
+    int nchunks, int strips, int nseg, int seg_rows, int units, uint32_t *__restrict__ out)
+{
+    constexpr int KV = 27;
+    __shared__ uint32_t lds[4][SR_WAVE];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int gw = blockIdx.x * 4 + wave;
+    if (gw >= units) return;                   // whole wave leaves; nothing is shared
+    int q = gw;
+    const int chunk = q % nchunks; q /= nchunks;   // 64 output channels
+    const int sx = q % strips; q /= strips;        // strip of 32 pixel columns
+    const int sg = q % nseg;                       // segment of seg_rows image rows
+    const int n = q / nseg;
+    const int col = lane & 31, half = lane >> 5;
+    const bool tile1 = chunk * 64 + 32 < Co;       // second 32-channel tile exists (Co % 32 == 0)
+    const int y0 = sg * seg_rows;
+    const int rows = min(H, y0 + seg_rows) - y0;
+    const int x0 = sx * 32;
+
+    // ---- weights: rows scaled to a norm in [2^12, 2^13), split once, in the K order above
+    uint4 Wh[2][2], Wl[2][2];
+    uint32_t rb = 0;
+    bool w_sane = true;
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+        const int ch = chunk * 64 + m * 32 + tile_row_to_channel(col);
+        float v[16];
+        float part = 0.0f;
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {
+            const int k0 = sr_term(0, s >> 1, s & 1), k1 = sr_term(1, s >> 1, s & 1);
+            const int k = half ? k1 : k0;
+            const bool ok = ch < Co && k >= 0;
+            const float wv = w[ok ? (size_t)ch * KV + k : 0];   // unconditional load
+            v[s] = ok ? wv : 0.0f;
+            part = __builtin_fmaf(v[s], v[s], part);
+        }
+        const float nrm = __builtin_sqrtf(swap_add(part));
+        const bool in_range = nrm >= 0x1p-60f && nrm <= 0x1p60f;
+        if (!(in_range || nrm == 0.0f)) w_sane = false;
+        const float sc = in_range ? norm_scale(nrm) : 1.0f;
+        if (nrm == 0.0f && ch < Co && half == 1) v[14] = 0x1p13f;   // the constant term (dword 7)
+        rb = max(rb, __float_as_uint(nrm * sc));
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            uint32_t h4[4], l4[4];
+#pragma unroll
+            for (int d = 0; d < 4; ++d)
+                split_pair(v[8 * t + 2 * d] * sc, v[8 * t + 2 * d + 1] * sc, h4[d], l4[d]);
+            Wh[m][t] = make_uint4(h4[0], h4[1], h4[2], h4[3]);
+            Wl[m][t] = make_uint4(l4[0], l4[1], l4[2], l4[3]);
+        }
+    }
+    rb = wave_umax(rb);
+    const float KW = STEM_KAPPA * 1.001f * __uint_as_float(rb);   // margin: norm and root are rounded
+    w_sane = __builtin_amdgcn_ballot_w64(!w_sane) == 0;
+
+    // ---- addresses.  Staging: lane p < 34 owns halo pixel p (image column x0 - 1 + p); the
+    // other lanes repeat pixel 33.  Zero padding: a column or row outside the image gets an
+    // offset beyond the buffer and reads 0.0f.
+    const __amdgpu_buffer_rsrc_t rsrc =
+        __builtin_amdgcn_make_buffer_rsrc((void *)img, 0, (int)img_bytes, 0x00020000);
+    const int p = min(lane, SR_HW - 1);
+    const int xs = x0 - 1 + p;
+    const uint32_t xoff = (xs >= 0 && xs < W) ? (uint32_t)xs * 4u : OOB;
+    uint32_t *const ldsw = lds[wave];
+    uint32_t *const wr = ldsw + p;
+    const uint32_t *const q0 = ldsw + (half ? 3 * SR_ARR : 0) + col;            // P0 | P2, then P1 | R2
+    const uint32_t *const q2 = ldsw + 2 * SR_ARR + col + (half ? 2 : 0);        // R01[j] | R01[j+2]
+    const uint32_t *const q3 = ldsw + (half ? SR_CONST : 2 * SR_ARR + col + 1); // R01[j+1] | constant
+    if (lane == 0) {
+        ldsw[SR_CONST] = 0x3c00u;              // (1.0, 0) in the hi plane, 0 in the lo plane
+        ldsw[SR_CONST + SR_PLANE] = 0u;
+    }
+
+    const int Cow = Co >> 5;
+    const uint32_t psel = half ? 0x07060302u : 0x05040100u;
+    const int widx = chunk * 2 + half;
+    const int xo = x0 + col;                   // output pixel column of this lane
+    // packed output of image n as a buffer: lane offset inside a row, row offset per tile
+    const uint32_t out_row_bytes = (uint32_t)W * Cow * 4u;
+    const __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(out + (size_t)n * H * W * Cow), 0, (int)(H * out_row_bytes), 0x00020000);
+    // (validity goes into the row offset alone: two out-of-range marks would add up to 0)
+    const uint32_t out_voff = (uint32_t)(xo * Cow + widx) * 4u;
+
+    struct Planes { uint4 h[2], l[2]; float ns[3]; uint32_t ob[3]; bool ok; };
+
+    // one image row of the strip: three floats per lane
+    auto fetch = [&](int yy, float (&v)[3]) {
+        const bool rin = yy >= 0 && yy < H;
+        const int yc = min(max(yy, 0), H - 1);
+        const uint32_t vo = rin ? xoff : OOB;
+#pragma unroll
+        for (int c = 0; c < 3; ++c)
+            v[c] = __uint_as_float(
+                __builtin_amdgcn_raw_buffer_load_b32(rsrc, vo, (int)((((size_t)n * 3 + c) * H + yc) * W * 4), 0));
+    };
+    // largest magnitude of a row over the wave, as the bit pattern of a non-negative float
+    auto row_max = [&](const float (&v)[3]) {
+        const uint32_t a = __float_as_uint(v[0]) & 0x7fffffffu, b = __float_as_uint(v[1]) & 0x7fffffffu,
+                       c = __float_as_uint(v[2]) & 0x7fffffffu;
+        return wave_umax(max(max(a, b), c));
+    };
+
+    // Staging of a window (rows a[0..2], their maxima rm[0..2]) in pieces; piece k of STAGE_PIECES.
+    // The scaled values are kept as the pairs that are split together: channels (0, 1) of a
+    // row, channel 2 of rows (0, 1), channel 2 of row 2.
+    struct Stage { v2f pr[3], z01, z2; float s, nsq; uint32_t orb; bool ok; uint32_t sh[5], sl[5]; };
+    auto split2 = [](v2f f, uint32_t &hi, uint32_t &lo) {
+        hi = __builtin_bit_cast(uint32_t, __builtin_convertvector(f, v2h));
+        // f - hi (exact: the difference has at most 24 bits) with the fp16 operand converted by
+        // the instruction itself: -1.0 * hi.lo + f[0], -1.0 * hi.hi + f[1]
+        v2f r;
+        asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel_hi:[1,0,0]" : "=v"(r[0]) : "v"(hi), "v"(f[0]));
+        asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r[1]) : "v"(hi), "v"(f[1]));
+        lo = __builtin_bit_cast(uint32_t, __builtin_convertvector(r, v2h));
+    };
+    constexpr int STAGE_PIECES = 12;
+    auto stage_piece = [&](int k, const float (&a)[3][3], const uint32_t (&rm)[3], Stage &st, Planes &Bn) {
+        if (k == 0) {
+            const uint32_t mb = max(max(rm[0], rm[1]), rm[2]);
+            const uint32_t e = mb >> 23;
+            st.ok = e >= 16u && e <= 254u;
+            st.s = st.ok ? __uint_as_float((267u - e) << 23) : 1.0f;
+            st.pr[0] = (v2f){a[0][0] * st.s, a[0][1] * st.s};
+            st.pr[1] = (v2f){a[1][0] * st.s, a[1][1] * st.s};
+            asm volatile("" : "+v"(st.pr[0]), "+v"(st.pr[1]));
+        } else if (k == 1) {
+            st.pr[2] = (v2f){a[2][0] * st.s, a[2][1] * st.s};
+            st.z01 = (v2f){a[0][2] * st.s, a[1][2] * st.s};
+            st.z2 = (v2f){a[2][2] * st.s, 0.0f};
+            asm volatile("" : "+v"(st.pr[2]), "+v"(st.z01), "+v"(st.z2));
+        } else if (k == 2) {
+            float n2 = st.z2[0] * st.z2[0];
+#pragma unroll
+            for (int r = 0; r < 3; ++r) {
+                n2 = __builtin_fmaf(st.pr[r][0], st.pr[r][0], n2);
+                n2 = __builtin_fmaf(st.pr[r][1], st.pr[r][1], n2);
+            }
+            n2 = __builtin_fmaf(st.z01[0], st.z01[0], n2);
+            st.nsq = __builtin_fmaf(st.z01[1], st.z01[1], n2);
+            asm volatile("" : "+v"(st.nsq));
+        } else if (k == 3) {
+            uint32_t o[3];
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+                o[r] = __float_as_uint(a[r][0]) | __float_as_uint(a[r][1]) | __float_as_uint(a[r][2]);
+            st.orb = o[0] | o[1] | o[2];
+            asm volatile("" : "+v"(st.orb));
+            // squared norm and OR of this pixel's column, for the three patches it belongs to
+            ldsw[SR_N + 2 * p] = __float_as_uint(st.nsq);
+            ldsw[SR_N + 2 * p + 1] = st.orb;
+        } else if (k == 4) {
+            split2(st.pr[0], st.sh[0], st.sl[0]);
+            asm volatile("" : "+v"(st.sh[0]), "+v"(st.sl[0]));
+        } else if (k == 5) {
+            split2(st.pr[1], st.sh[1], st.sl[1]);
+            asm volatile("" : "+v"(st.sh[1]), "+v"(st.sl[1]));
+        } else if (k == 6) {
+            split2(st.z01, st.sh[2], st.sl[2]);
+            asm volatile("" : "+v"(st.sh[2]), "+v"(st.sl[2]));
+        } else if (k == 7) {
+            split2(st.pr[2], st.sh[3], st.sl[3]);
+            asm volatile("" : "+v"(st.sh[3]), "+v"(st.sl[3]));
+        } else if (k == 8) {
+            split2(st.z2, st.sh[4], st.sl[4]);
+            asm volatile("" : "+v"(st.sh[4]), "+v"(st.sl[4]));
+        } else if (k == 9) {
+            // array order in LDS: P0 P1 R01 P2 R2
+#pragma unroll
+            for (int i = 0; i < 5; ++i) {
+                wr[i * SR_ARR] = st.sh[i];
+                wr[i * SR_ARR + SR_PLANE] = st.sl[i];
+            }
+            __builtin_amdgcn_wave_barrier();
+        } else if (k == 10) {
+            // LDS instructions of a wave execute in order: these reads see the writes above
+            Bn.h[0] = make_uint4(q0[0], q0[1], q0[2], q0[SR_ARR]);
+            Bn.h[1] = make_uint4(q0[SR_ARR + 1], q0[SR_ARR + 2], q2[0], q3[0]);
+            Bn.l[0] = make_uint4(q0[SR_PLANE], q0[SR_PLANE + 1], q0[SR_PLANE + 2], q0[SR_PLANE + SR_ARR]);
+            Bn.l[1] = make_uint4(q0[SR_PLANE + SR_ARR + 1], q0[SR_PLANE + SR_ARR + 2], q2[SR_PLANE], q3[SR_PLANE]);
+        } else {
+            // the three columns of this lane's patch; the threshold is formed where it is used
+#pragma unroll
+            for (int d = 0; d < 3; ++d) {
+                Bn.ns[d] = __uint_as_float(ldsw[SR_N + 2 * (col + d)]);
+                Bn.ob[d] = ldsw[SR_N + 2 * (col + d) + 1];
+            }
+            Bn.ok = st.ok;
+            __builtin_amdgcn_wave_barrier();   // the next window is written after these reads
+        }
+    };
+
+    // ---- decision and store of a finished row
+    struct Done { float T; bool zero; int i; };
+    struct Epi { float mn; uint32_t sg[2]; };
+    constexpr int EPI_PIECES = 7;
+    auto epi_piece = [&](int k, const v16f (&acc)[2], const Done &dn, Epi &ep) {
+        if (k == 0) {
+            float mn = __builtin_fminf(__builtin_fabsf(acc[0][0]), __builtin_fabsf(acc[0][1]));
+#pragma unroll
+            for (int e = 2; e < 16; ++e) mn = __builtin_fminf(mn, __builtin_fabsf(acc[0][e]));
+            ep.mn = mn;
+            ep.sg[0] = ep.sg[1] = 0u;
+            asm volatile("" : "+v"(ep.mn));
+        } else if (k == 1) {
+            if (tile1) {
+                float mn = ep.mn;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) mn = __builtin_fminf(mn, __builtin_fabsf(acc[1][e]));
+                ep.mn = mn;
+            }
+            asm volatile("" : "+v"(ep.mn));
+        } else if (k < 6) {
+            // sign bits (1 = negative) of the 2 x 16 channels of this lane, four per tile and piece
+#pragma unroll
+            for (int e = 15 - 4 * (k - 2); e > 11 - 4 * (k - 2); --e)
+#pragma unroll
+                for (int m = 0; m < 2; ++m)
+                    ep.sg[m] = __builtin_amdgcn_alignbit(ep.sg[m], __float_as_uint(acc[m][e]), 31);
+            asm volatile("" : "+v"(ep.sg[0]), "+v"(ep.sg[1]));
+        } else {
+            const int y = y0 + dn.i;
+            const float T = dn.T;
+            const bool live = xo < W && dn.i >= 0 && dn.i < rows;
+            const bool flag = live && !dn.zero && !(ep.mn > T);
+            // ---- sequential route for the undecided outputs (rare)
+            if (__builtin_amdgcn_ballot_w64(flag) != 0) {
+                if (flag) {
+                    uint32_t fl[2];
+#pragma unroll
+                    for (int m = 0; m < 2; ++m) {
+                        fl[m] = 0;
+#pragma unroll
+                        for (int e = 0; e < 16; ++e)
+                            fl[m] |= (!(__builtin_fabsf(acc[m][e]) > T) ? 1u : 0u) << e;
+                        if (chunk * 64 + m * 32 + 16 * half >= Co) fl[m] = 0;
+                    }
+                    const uint32_t pb = (uint32_t)((((size_t)n * 3 * H + y) * W + xo) * 4);
+#pragma unroll
+                    for (int m = 0; m < 2; ++m) {
+                        const int cb = chunk * 64 + m * 32 + 16 * half;
+                        while (fl[m]) {
+                            const int e = __builtin_ctz(fl[m]);
+                            fl[m] &= fl[m] - 1;
+                            const float *wp = w + (size_t)(cb + e) * KV;
+                            // the sum in its defined order; a tap outside the image is skipped
+                            float sum = 0.0f;
+#pragma unroll
+                            for (int ky = 0; ky < 3; ++ky) {
+                                float pv[9], wv[9];
+                                uint32_t okm = 0;
+#pragma unroll
+                                for (int u = 0; u < 9; ++u) {
+                                    const int kx = u / 3, ci = u - kx * 3;
+                                    const bool ok = !((ky == 0 && y == 0) || (ky == 2 && y == H - 1) ||
+                                                      (kx == 0 && xo == 0) || (kx == 2 && xo == W - 1));
+                                    const uint32_t o =
+                                        pb + (uint32_t)(((long)ci * H * W + (long)(ky - 1) * W + (kx - 1)) * 4);
+                                    pv[u] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, ok ? o : OOB, 0, 0));
+                                    wv[u] = wp[ky * 9 + u];
+                                    okm |= (ok ? 1u : 0u) << u;
+                                }
+#pragma unroll
+                                for (int u = 0; u < 9; ++u) {
+                                    const float f = __builtin_fmaf(wv[u], pv[u], sum);
+                                    sum = ((okm >> u) & 1u) ? f : sum;
+                                }
+                            }
+                            ep.sg[m] = (ep.sg[m] & ~(1u << e)) | ((sum >= 0.0f ? 0u : 1u) << e);   // NaN -> bit 0
+                        }
+                    }
+                }
+            }
+            if (dn.zero) { ep.sg[0] = 0u; ep.sg[1] = 0u; }   // a chain of zero terms ends at +0.0f
+            const uint32_t word = finish_word64(ep.sg[0], ep.sg[1], psel);
+            const uint32_t roff = live && widx < Cow ? (uint32_t)y * out_row_bytes : OOB;
+            __builtin_amdgcn_raw_buffer_store_b32(word, orsrc, out_voff + roff, 0, 0);
+        }
+    };
+
+    // ---- one tile: matrix instructions of row y on planes B, between them the staging of row
+    // y + 1 (rows a[1], a[2] and the row fetched two tiles ago); then decision and store.
+    // (Running the decision of row y - 1 between the matrix instructions as well, with a second
+    // set of accumulators, measured no faster: the kernel is bound by the vector instruction
+    // count, and three waves per SIMD - which the smaller register count allows - hide more.)
+    auto tile = [&](const int i, const Planes &B, Planes &Bn, float (&a)[3][3], uint32_t (&rm)[3],
+                    float (&ld)[3]) {
+        const int y = y0 + i;
+        // the window moves down one row
+#pragma unroll
+        for (int c = 0; c < 3; ++c) {
+            a[0][c] = a[1][c];
+            a[1][c] = a[2][c];
+            a[2][c] = ld[c];
+        }
+        rm[0] = rm[1];
+        rm[1] = rm[2];
+        rm[2] = row_max(a[2]);
+        fetch(y + 4, ld);
+
+        v16f acc[2];
+#pragma unroll
+        for (int m = 0; m < 2; ++m)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[m][e] = 0.0f;
+        Stage st;
+        Epi ep;
+        Done dn;
+        int slot = 0;
+        auto mma = [&](const uint4 (&WP)[2][2], const uint4 (&BP)[2]) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int m = 0; m < 2; ++m) {
+                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_v8h(WP[m][t]), as_v8h(BP[t]), acc[m], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (slot < STAGE_PIECES) stage_piece(slot, a, rm, st, Bn);
+                    ++slot;
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+        };
+        mma(Wl, B.h);      // small terms first
+        mma(Wh, B.l);
+        mma(Wh, B.h);
+        static_assert(STAGE_PIECES <= 12 && EPI_PIECES <= 12, "one piece of each kind per matrix instruction");
+
+        dn.zero = ((B.ob[0] | B.ob[1] | B.ob[2]) << 1) == 0;          // every patch value is +-0
+        // (the hardware square root is good to 1 ulp; KW carries the margin)
+        dn.T = (B.ok && w_sane) ? __builtin_fmaf(KW, __builtin_amdgcn_sqrtf(B.ns[0] + B.ns[1] + B.ns[2]), SR_FLOOR)
+                                : __builtin_inff();
+        dn.i = i;
+#pragma unroll
+        for (int k = 0; k < EPI_PIECES; ++k) epi_piece(k, acc, dn, ep);
+    };
+
+    // ---- prologue: rows y0 - 1 .. y0 + 1 staged for the first tile, rows y0 + 2 and y0 + 3 in flight
+    float a[3][3], ld0[3], ld1[3];
+    uint32_t rm[3];
+    Planes B0, B1;
+#pragma unroll
+    for (int r = 0; r < 3; ++r) fetch(y0 - 1 + r, a[r]);
+    fetch(y0 + 2, ld0);
+    fetch(y0 + 3, ld1);
+#pragma unroll
+    for (int r = 0; r < 3; ++r) rm[r] = row_max(a[r]);
+    {
+        Stage st;
+#pragma unroll
+        for (int k = 0; k < STAGE_PIECES; ++k) stage_piece(k, a, rm, st, B0);
+    }
+    // two rows per trip (operand planes and fetch registers alternate); with an odd row count the
+    // second row of the last trip is computed and dropped
+#pragma unroll 1
+    for (int i = 0; i < rows; i += 2) {
+        tile(i, B0, B1, a, rm, ld0);
+        tile(i + 1, B1, B0, a, rm, ld1);
+    }
+}
+
+static int launch_stem_rows(const float *img, uint32_t bytes, int N, int H, int W, const float *w, int Co,
+                            uint32_t *out_bits, hipStream_t s)
+{
+    const int nchunks = ceil_div(Co, 64);
+    const int strips = ceil_div(W, 32);
+    const long base = (long)N * strips * nchunks;
+    // as many row segments as it takes to give every wave slot of the chip (three per SIMD) one unit
+    const long slots = 3L * 4 * 256;
+    const int want = (int)std::max(1L, slots / base);
+    int seg_rows = ceil_div(H, want);
+    seg_rows = std::max(2, seg_rows + (seg_rows & 1));
+    const int nseg = ceil_div(H, seg_rows);
+    const long units = base * nseg;
+    if (units > 0x7fffffffL) return fail(MBU_ERR_SHAPE, "stem: too many tiles for one launch");
+    MBU_LAUNCH(stem_rows_kernel, dim3((unsigned)((units + 3) / 4)), dim3(256), 0, s, img, bytes, H, W, w, Co,
+               nchunks, strips, nseg, seg_rows, (int)units, out_bits);
+    return check_launch("stem_rows");
+}
+
+int g_stem_gather = 0;   // 1: the per-pixel gather kernel also where the row-walking kernel applies
+
 int launch_stem_mfma(const float *img, int N, int Ci, int H, int W, const float *w, int Co,
                      uint32_t *out_bits, float *out_pre, hipStream_t s)
 {
     const double bytes = (double)N * Ci * H * W * 4.0;
     if (bytes >= 2147483648.0) return fail(MBU_ERR_SHAPE, "stem: image larger than 2 GiB");
+    // (the row-walking kernel addresses the packed output of one image with 31-bit offsets)
+    if (Ci == 3 && !out_pre && !g_stem_gather && (double)(H + 1) * (W + 32) * (Co / 32) * 4.0 < 2147483648.0)
+        return launch_stem_rows(img, (uint32_t)bytes, N, H, W, w, Co, out_bits, s);
     const int tiles_x = ceil_div(W, 32);
     const long ntiles = (long)N * H * tiles_x;
     if (ntiles > 0x7fffffffL) return fail(MBU_ERR_SHAPE, "stem: too many tiles for one launch");

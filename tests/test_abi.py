@@ -190,6 +190,7 @@ def test_stem_and_classifier_argument_validation():
     assert f(img, 64, 3, 4096, 4096, w, 64, o, None, None) == B.MBU_ERR_SHAPE     # > 2 GiB image
     assert L.mbu_set_stem_path(9) == B.MBU_ERR_ARG
     assert L.mbu_set_stem_path(B.STEM_VALU) == B.MBU_OK and L.mbu_get_stem_path() == B.STEM_VALU
+    assert L.mbu_set_stem_path(B.STEM_MFMA_GATHER) == B.MBU_OK and L.mbu_get_stem_path() == B.STEM_MFMA_GATHER
     assert L.mbu_set_stem_path(B.STEM_AUTO) == B.MBU_OK
     g = L.mbu_classifier_fp32
     a, b = 0x50000, 0x60000

@@ -541,7 +541,7 @@ def test_unet_wide_batch8_full_size():
 
 
 # ------------------------------------------------------------------------ float32 ends
-STEM_PATHS = [(B.STEM_VALU, "valu"), (B.STEM_MFMA, "mfma")]
+STEM_PATHS = [(B.STEM_VALU, "valu"), (B.STEM_MFMA, "mfma"), (B.STEM_MFMA_GATHER, "mfma-gather")]
 STEM_KAPPA = 2.0 ** -18      # the matrix path's documented error budget
 
 
@@ -574,6 +574,7 @@ def check_stem(image, w, path, pname, label):
 STEM_SHAPES = [  # N, Ci, H, W, Co
     (1, 3, 37, 45, 64), (2, 3, 64, 100, 64), (1, 1, 33, 70, 32), (1, 3, 130, 257, 128),
     (3, 3, 16, 16, 96), (1, 3, 1, 1, 64), (1, 1, 2, 31, 64), (1, 3, 3, 32, 32),
+    (1, 3, 6200, 40, 64),    # tall: the row-walking kernel's segments are several rows long
 ]
 
 
@@ -632,6 +633,14 @@ def test_stem_degenerate_inputs(path, pname):
         img[:, :, :, 35:] *= np.float32(1e-6)
         w = rng.standard_normal((Co, 3, 3, 3), dtype=np.float32) * np.float32(scale_w)
         check_stem(img, w, path, pname, f"scale {scale_i:g} x {scale_w:g}")
+    # magnitudes that differ from pixel to pixel by up to 2^40, and from row to row: patches that
+    # are tiny against their neighbours (the row-walking kernel shares one scale per window)
+    img = rng.standard_normal((1, 3, H, W), dtype=np.float32)
+    img *= np.exp2(rng.integers(-20, 21, size=(1, 1, H, W))).astype(np.float32)
+    check_stem(img, rng.standard_normal((Co, 3, 3, 3), dtype=np.float32), path, pname, "per-pixel scales")
+    img = rng.standard_normal((1, 3, H, W), dtype=np.float32)
+    img *= np.exp2(rng.integers(-30, 31, size=(1, 1, H, 1))).astype(np.float32)
+    check_stem(img, rng.standard_normal((Co, 3, 3, 3), dtype=np.float32), path, pname, "per-row scales")
     # non-finite pixels: the comparison "sum >= 0" is false for NaN on both sides
     img = rng.standard_normal((1, 3, H, W), dtype=np.float32)
     img[0, 1, 5, 7] = np.nan
