@@ -747,7 +747,7 @@ __global__ __launch_bounds__(256, 3) void stem_rows_kernel(
                             const float *wp = w + (size_t)(cb + e) * KV;
                             // the sum in its defined order; a tap outside the image is skipped
                             float sum = 0.0f;
-#pragma unroll
+#pragma unroll 1
                             for (int ky = 0; ky < 3; ++ky) {
                                 float pv[9], wv[9];
                                 uint32_t okm = 0;
