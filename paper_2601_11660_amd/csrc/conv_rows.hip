@@ -10,9 +10,10 @@
 // whole life and walks down the image one row at a time.  Every row is 18 matrix
 // instructions with one small piece of vector work slotted behind each of them:
 //   - the three activation rows a 3x3 window touches are held in registers as 9 fragments
-//     (3 rows x 3 tap columns); the window moves down by register copies, each fragment row
-//     overwritten right after the 6 instructions of its tap row, and the row that enters is
-//     read from LDS at the end of the row, 12 instructions before its first use;
+//     (3 rows x 3 tap columns); the row that enters is read from LDS into the registers of
+//     the row that left, right after the 6 instructions of that tap row, and the roles of the
+//     three fragment rows rotate (the loop body is six rows long: 3 roles x 2 accumulator
+//     sets; a remainder of 2 or 4 rows moves the window by register copies instead);
 //   - the halo row that enters the window two rows later is expanded from bits to codes and
 //     written to one of two row slots in LDS; its bits were fetched from global memory two
 //     rows earlier;
@@ -90,8 +91,10 @@ __device__ __forceinline__ void store_row(const RowsCtx &c, uint32_t s, int i_ro
 }
 
 // One image row; P = parity of the row index i: accumulator set, ring slots and fetch register.
-// F[k] holds the fragments of halo row i + k (image row y0 + i + k - 1).
-template <bool CW_EVEN, bool POOL, int P>
+// F[(R3 + k) % 3] holds the fragments of halo row i + k (image row y0 + i + k - 1).  With COPY
+// the window moves down by register copies and R3 stays 0; without, the row that enters takes
+// the registers of the row that left and the caller steps R3 (three steps bring it back).
+template <bool CW_EVEN, bool POOL, int P, int R3, bool COPY>
 __device__ __forceinline__ void rows_step(const RowsCtx &c, const int i,
                                           const v4i (&Wg)[3][3][2], const v16f (&init)[2],
                                           v16f (&acc)[2][2], v4i (&F)[3][3], uint2 (&gq)[2], uint32_t &wkeep)
@@ -105,7 +108,7 @@ __device__ __forceinline__ void rows_step(const RowsCtx &c, const int i,
 #pragma unroll
     for (int t = 0; t < 18; ++t) {
         const int ky = t / 6, kx = (t % 6) >> 1, m = t & 1;
-        acc[CUR][m] = mfma_f4(Wg[kx][ky][m], F[ky][kx], ky == 0 && kx == 0 ? init[m] : acc[CUR][m]);
+        acc[CUR][m] = mfma_f4(Wg[kx][ky][m], F[(R3 + ky) % 3][kx], ky == 0 && kx == 0 ? init[m] : acc[CUR][m]);
         RS_FENCE();
         // ---- staging of halo row i + 4 (image row y0 + i + 3): bits fetched two rows ago
         if (t == 0) {
@@ -140,7 +143,7 @@ __device__ __forceinline__ void rows_step(const RowsCtx &c, const int i,
         }
         // ---- the window moves down one row: a fragment row is overwritten as soon as its tap
         // row has been issued
-        if (t == 5 || t == 11) {
+        if (COPY && (t == 5 || t == 11)) {
             const int k = t / 6;   // F[k] <- F[k + 1]
 #pragma unroll
             for (int x = 0; x < 3; ++x) {
@@ -148,11 +151,13 @@ __device__ __forceinline__ void rows_step(const RowsCtx &c, const int i,
                 RS_PIN(F[k][x]);
             }
         }
-        if (t == 17) {
+        // the row that enters the window (staged one row ago): with copies into the last
+        // fragment row once its instructions are issued, without into the first one
+        if (COPY ? t == 17 : t == 5) {
 #pragma unroll
             for (int x = 0; x < 3; ++x) {
                 const uint4 f = c.rd[RD * RS_ROW + x];
-                F[2][x] = (v4i){(int)f.x, (int)f.y, (int)f.z, (int)f.w};
+                F[COPY ? 2 : R3 % 3][x] = (v4i){(int)f.x, (int)f.y, (int)f.z, (int)f.w};
             }
         }
         // ---- signs of the previous row: one chain over the 32 registers, second tile first, so
@@ -311,13 +316,23 @@ __global__ __launch_bounds__(256, WPS) void conv_mfma_rows_kernel(
         }
     RS_PIN(gq[0].x); RS_PIN(gq[0].y); RS_PIN(gq[1].x); RS_PIN(gq[1].y);
 
-    // two rows per trip (the accumulator sets alternate); with an odd row count the second
-    // row of the last trip is computed and dropped
+    // six rows per trip: the accumulator sets alternate and the three fragment rows rotate, so
+    // nothing is copied; what is left (0, 2 or 4 rows, and the odd row's partner, which is
+    // computed and dropped) goes two rows per trip with the window moved by register copies
     int i = 0;
 #pragma unroll 1
+    for (; i + 6 <= rows; i += 6) {
+        rows_step<CW_EVEN, POOL, 0, 0, false>(c, i, Wg, init, acc, F, gq, wkeep);
+        rows_step<CW_EVEN, POOL, 1, 1, false>(c, i + 1, Wg, init, acc, F, gq, wkeep);
+        rows_step<CW_EVEN, POOL, 0, 2, false>(c, i + 2, Wg, init, acc, F, gq, wkeep);
+        rows_step<CW_EVEN, POOL, 1, 0, false>(c, i + 3, Wg, init, acc, F, gq, wkeep);
+        rows_step<CW_EVEN, POOL, 0, 1, false>(c, i + 4, Wg, init, acc, F, gq, wkeep);
+        rows_step<CW_EVEN, POOL, 1, 2, false>(c, i + 5, Wg, init, acc, F, gq, wkeep);
+    }
+#pragma unroll 1
     for (; i < rows; i += 2) {
-        rows_step<CW_EVEN, POOL, 0>(c, i, Wg, init, acc, F, gq, wkeep);
-        rows_step<CW_EVEN, POOL, 1>(c, i + 1, Wg, init, acc, F, gq, wkeep);
+        rows_step<CW_EVEN, POOL, 0, 0, true>(c, i, Wg, init, acc, F, gq, wkeep);
+        rows_step<CW_EVEN, POOL, 1, 0, true>(c, i + 1, Wg, init, acc, F, gq, wkeep);
     }
 
     // ---- the signs of the last odd row, still in accumulator set 1
