@@ -152,6 +152,11 @@ ROWS_SHAPES = [
     (1, 130, 34, 40, 96),      # Cin not a multiple of 32, many row segments
     (3, 6, 200, 64, 64),
     (1, 256, 512, 64, 64),     # every wave slot of the chip busy
+    # wide enough that a wave's row segment is longer than the six-row loop body: segments of
+    # 10 (6 + 4), 8 (6 + 2) and 6 rows with two waves per SIMD, 20, 14 and 12 with one
+    (1, 160, 2048, 64, 128),
+    (1, 110, 2048, 40, 128),
+    (1, 96, 2048, 64, 128),
 ]
 
 
