@@ -70,7 +70,9 @@ int mbu_get_conv_path(void);
  * low-resolution kernel of layers with a 2x up-sampled second input); 3 = persistent
  * wave-private kernel with 3 rows x 64 channels per wave; 6 = the same with 6 rows x 32
  * channels; 7 / 8 = row-streaming kernel for layers with at most 64 input channels, two /
- * one waves per SIMD (7 is what 0 picks for such layers; other layers are not affected).
+ * one waves per SIMD (7 is what 0 picks for such layers; other layers are not affected);
+ * 9 = the row-streaming kernel also for every layer with 65..128 input channels (0 picks it
+ * for such layers only with at most 128 output channels on large frames).
  * `reserved` must be 0.  Results never depend on it.  MBU_ERR_ARG otherwise. */
 int mbu_set_conv_tuning(int kernel, int reserved);
 

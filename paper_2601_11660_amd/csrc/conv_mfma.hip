@@ -689,10 +689,24 @@ static const int32_t *weight_sums(const uint4 *wfrag, const BlobLayout &L)
 }
 
 int g_tune_rw = 0, g_tune_wm = 0;   // 0 = automatic
+
+// Layers with two input steps: the row-streaming kernel (32 output channels per wave) or the
+// block-cooperative one?  Measured on MI355X: 128->128 at 512x1024 30.5 us against 33.1 us,
+// 128->256 at 256x512 21.3 us against 19.2 us - every wave of another channel tile stages the
+// strip again, and short row segments pay the prologue more often.  So: at most four channel
+// tiles, and segments of 24 rows or more when every wave slot has one.
+static bool use_rows2k(int N, int H, int W, const BlobLayout &L, bool wants_bits)
+{
+    if (!conv_rows2k_supported(H, W, L, wants_bits)) return false;
+    if (g_tune_rw == 9) return true;
+    if (g_tune_rw != 0) return false;
+    const long wave_rows = (long)N * H * ceil_div(W, 32) * (L.cout >> 5);
+    return L.cout <= 128 && wave_rows >= 24L * 2048;
+}
 int g_persistent_blocks = 512;       // resident blocks of the block-cooperative kernel (2 per CU)
 
 // waves per SIMD of the row-streaming kernel for single-step layers, 0 = kernel not used
-static int rows_kernel_waves() { return (g_tune_rw == 0 || g_tune_rw == 7) ? 2 : g_tune_rw == 8 ? 1 : 0; }
+static int rows_kernel_waves() { return (g_tune_rw == 0 || g_tune_rw == 7 || g_tune_rw == 9) ? 2 : g_tune_rw == 8 ? 1 : 0; }
 
 bool conv_writes_pooled(int H, int W, const BlobLayout &L)
 {
@@ -815,7 +829,9 @@ int launch_conv_mfma(const uint32_t *act, int N, int H, int W, const BlobLayout 
     // wave-private tile kernel, which remains for shapes the streaming kernel does not take);
     // with several steps the block-cooperative kernel stages least per wave and wins.
     const int mode = g_tune_rw;   // 0 = automatic; see mbu_set_conv_tuning
-    const bool want_block = mode == 1 || (mode == 0 && L.ksteps > 1);
+    if (use_rows2k(N, H, W, L, out_bits != nullptr))
+        return launch_conv_mfma_rows2k(act, N, H, W, L, blob, thresh, out_bits, nullptr, s);
+    const bool want_block = mode == 1 || ((mode == 0 || mode == 9) && L.ksteps > 1);
     if (want_block) {
         ConvIO io{act, nullptr, 0, L.cin_words, 0, out_bits, nullptr};
         return launch_block_auto(io, N, H, W, L, wfrag, thresh, s);
@@ -837,6 +853,8 @@ int launch_conv_mfma_two(const uint32_t *act, int Ca, const uint32_t *low, int C
         return launch_conv_mfma_upcat(act, Ca, low, Clow, N, H, W, L, blob, thresh, out_bits, s);
     if (!low && rows_kernel_waves() && conv_rows_supported(H, W, L, out_bits != nullptr))
         return launch_conv_mfma_rows(act, N, H, W, L, blob, thresh, out_bits, out_pool, rows_kernel_waves(), s);
+    if (!low && use_rows2k(N, H, W, L, out_bits != nullptr))
+        return launch_conv_mfma_rows2k(act, N, H, W, L, blob, thresh, out_bits, out_pool, s);
     const uint4 *wfrag = (const uint4 *)((const uint8_t *)blob + L.off_f4);
     ConvIO io{act, low, low ? low_shift : 0, ceil_div(Ca, 32), low ? ceil_div(Clow, 32) : 0,
               out_bits, out_pool};

@@ -1,5 +1,6 @@
 // Masked-binary 3x3 convolution on the matrix cores for layers with at most 64 input
-// channels (one 64-channel step): row-streaming kernel.
+// channels (one 64-channel step): row-streaming kernel.  A second kernel at the end of the file
+// applies the scheme to layers with two steps.
 //
 // With a single input step the contraction of a tile is short (18 matrix instructions per
 // image row of 32 pixels x 64 channels) and the vector work around it - expanding the staged
@@ -345,6 +346,311 @@ __global__ __launch_bounds__(256, WPS) void conv_mfma_rows_kernel(
     store_row<POOL, true>(c, s, i - 1 < rows ? i - 1 : -1, wkeep);
 }
 
+// ---------------------------------------------------------------------------------------
+// The same scheme for layers with TWO 64-channel input steps (65..128 input channels): a wave
+// owns a strip of 32 pixel columns and 32 output channels, so that the weights (2 steps x 9 taps
+// = 18 fragments, as above) and the window (2 x 9 fragments) still fit in registers next to two
+// accumulator sets.  A row is again 18 matrix instructions (tap row, tap column, input step),
+// all on one accumulator tile; the staging expands four words per pixel, the sign collection
+// covers 16 channels per lane, and the waves of the other channel tiles stage the same strip
+// again (the price of keeping a wave self-contained).
+constexpr int R2_ROW = 2 * RS_ROW;      // uint4 entries per staged row: [step][half][pixel]
+
+struct Rows2Stream {
+    v16f acc[2];
+    v4i F[2][3][3];     // [step][window row][tap column]
+    uint4 gq[2];
+    uint32_t wkeep;
+};
+struct Rows2Tmp {
+    uint32_t w[4], m2[4], p1[4];   // fetched words and the masks of expand_word_masked() per word
+    uint4 e[4];
+    uint32_t s;
+};
+
+// the (three or) four packed words of this lane's halo pixel in image row yy (clamped)
+__device__ __forceinline__ void fetch_row4(const RowsCtx &c, int yy, uint4 &g, bool four)
+{
+    const int yc = min(max(yy, 0), c.H - 1);
+    const int soff = yc * c.in_row_bytes;
+    if (four) {
+        const auto v = __builtin_amdgcn_raw_buffer_load_b128(c.in, c.in_voff, soff, 0);
+        g = make_uint4(v[0], v[1], v[2], v[3]);
+    } else {
+        const auto v = __builtin_amdgcn_raw_buffer_load_b96(c.in, c.in_voff, soff, 0);
+        g = make_uint4(v[0], v[1], v[2], 0u);
+    }
+}
+
+// sign word of one finished row (16 channels per lane, both halves complete it to 32)
+template <bool POOL, bool ODD>
+__device__ __forceinline__ void store_row32(const RowsCtx &c, uint32_t s, int i_row, uint32_t &wkeep)
+{
+    const uint32_t word = finish_word32(s);
+    const uint32_t roff = i_row >= 0 ? (uint32_t)((c.y0 + i_row) * c.out_row_bytes) : RS_BAD_ROW;
+    __builtin_amdgcn_raw_buffer_store_b32(word, c.out, c.out_voff + roff, 0, 0);
+    if (POOL) {
+        if (!ODD) {
+            wkeep = word;
+        } else {
+            uint32_t v = wkeep | word;
+            v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, true);
+            const uint32_t poff =
+                i_row >= 0 ? (uint32_t)(((c.y0 + i_row) >> 1) * c.pool_row_bytes) : RS_BAD_ROW;
+            __builtin_amdgcn_raw_buffer_store_b32(v, c.pool, c.pool_voff + poff, 0, 0);
+        }
+    }
+}
+
+// Matrix instruction t (of 18) of one image row and the vector work behind it; P, R3, COPY as
+// in rows_step above.
+template <bool CW4, bool POOL, int P, int R3, bool COPY>
+__device__ __forceinline__ void rows2_step(const RowsCtx &c, const int i, const v4i (&Wg)[2][3][3],
+                                           const v16f &init, Rows2Stream &st)
+{
+    constexpr int CUR = P, PRV = P ^ 1;
+    constexpr int RD = P ^ 1, WR = P;      // ring slot of halo row i + 3 / i + 4
+    Rows2Tmp tm;
+#pragma unroll
+    for (int t = 0; t < 18; ++t) {
+        const int ky = t / 6, kx = (t % 6) >> 1, ks = t & 1;
+        st.acc[CUR] = mfma_f4(Wg[ks][kx][ky], st.F[ks][(R3 + ky) % 3][kx], t == 0 ? init : st.acc[CUR]);
+        RS_FENCE();
+        // ---- staging of halo row i + 4 (image row y0 + i + 3): bits fetched two rows ago;
+        // dword d of word k in slot 1 + (4 k + d) / 2
+        if (t == 0) {
+            const bool rin = c.y0 + i + 3 < c.H;
+            const uint32_t m2 = rin ? c.mx2 : 0u, p1 = (~m2 >> 1) & 0x11111111u;
+            tm.w[0] = st.gq[P].x; tm.w[1] = st.gq[P].y; tm.w[2] = st.gq[P].z; tm.w[3] = st.gq[P].w;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                tm.m2[k] = (k < 3 || CW4) ? m2 : 0u;
+                tm.p1[k] = (k < 3 || CW4) ? p1 : 0u;
+            }
+            tm.s = 0;
+        }
+        if (t >= 1 && t <= 8) {
+#pragma unroll
+            for (int q = 2 * (t - 1); q < 2 * t; ++q) {
+                const int k = q >> 2, d = q & 3;
+                const uint32_t sh = d == 0 ? tm.w[k] << 1 : d == 1 ? tm.w[k] : tm.w[k] >> (d - 1);
+                const uint32_t v = (sh & tm.m2[k]) | tm.p1[k];
+                if (d == 0) tm.e[k].x = v; else if (d == 1) tm.e[k].y = v; else if (d == 2) tm.e[k].z = v; else tm.e[k].w = v;
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) { RS_PIN(tm.e[k].x); RS_PIN(tm.e[k].y); RS_PIN(tm.e[k].z); RS_PIN(tm.e[k].w); }
+        }
+        if (t == 8) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k) c.wr[WR * R2_ROW + (k >> 1) * RS_ROW + (k & 1) * RS_HW] = tm.e[k];
+            // halo row i + 6 into the register just consumed
+            fetch_row4(c, c.y0 + i + 5, st.gq[P], CW4);
+        }
+        if (COPY && (t == 5 || t == 11)) {
+            const int k = t / 6;   // F[.][k] <- F[.][k + 1]
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int x = 0; x < 3; ++x) {
+                    st.F[u][k][x] = st.F[u][k + 1][x];
+                    RS_PIN(st.F[u][k][x]);
+                }
+        }
+        if (COPY ? t == 17 : t == 5) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int x = 0; x < 3; ++x) {
+                    const uint4 f = c.rd[RD * R2_ROW + u * RS_ROW + x];
+                    st.F[u][COPY ? 2 : R3 % 3][x] = (v4i){(int)f.x, (int)f.y, (int)f.z, (int)f.w};
+                }
+        }
+        // ---- signs of the previous row, register 15 first: bit k of the result is register k
+        if (t >= 9 && t < 17) {
+#pragma unroll
+            for (int e = 2 * (t - 9); e < 2 * (t - 8); ++e)
+                tm.s = __builtin_amdgcn_alignbit(tm.s, __float_as_uint(st.acc[PRV][15 - e]), 31);
+            RS_PIN(tm.s);
+        }
+        if (t == 17) {
+            const bool valid = P == 1 || i > 0;
+            store_row32<POOL, P == 0>(c, tm.s, valid ? i - 1 : -1, st.wkeep);
+        }
+        RS_FENCE();
+    }
+}
+
+template <bool CW4, bool POOL>
+__global__ __launch_bounds__(256, 2) void conv_mfma_rows2k_kernel(
+    const uint32_t *__restrict__ act, int H, int W, int Cw, const uint4 *__restrict__ wfrag, int Cout,
+    int ctiles, int strips, int nseg, int seg_rows, int units, const int32_t *__restrict__ thresh,
+    const int32_t *__restrict__ wsum, uint32_t *__restrict__ out_bits, uint32_t *__restrict__ out_pool)
+{
+    __shared__ uint4 lds[4][RS_RING * R2_ROW];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int gw = blockIdx.x * 4 + wave;
+    if (gw >= units) return;                  // whole wave leaves; nothing is shared
+    int q = gw;
+    const int ct = q % ctiles; q /= ctiles;   // 32-channel output tile
+    const int sx = q % strips; q /= strips;   // strip of 32 pixel columns
+    const int sg = q % nseg;                  // segment of seg_rows image rows
+    const int n = q / nseg;
+    const int col = lane & 31, half = lane >> 5;
+    const int Cow = Cout >> 5;
+    const int y0 = sg * seg_rows;
+    const int rows = min(H, y0 + seg_rows) - y0;
+
+    RowsCtx c;
+    c.H = H;
+    c.y0 = y0;
+    c.in_row_bytes = W * Cw * 4;
+    c.out_row_bytes = W * Cow * 4;
+    c.pool_row_bytes = (W >> 1) * Cow * 4;
+    c.in = __builtin_amdgcn_make_buffer_rsrc((void *)(act + (size_t)n * H * W * Cw), 0, H * c.in_row_bytes,
+                                             0x00020000);
+    c.out = __builtin_amdgcn_make_buffer_rsrc((void *)(out_bits + (size_t)n * H * W * Cow), 0,
+                                              H * c.out_row_bytes, 0x00020000);
+    c.pool = __builtin_amdgcn_make_buffer_rsrc(
+        (void *)(POOL ? out_pool + (size_t)n * (H >> 1) * (W >> 1) * Cow : out_bits), 0,
+        POOL ? (H >> 1) * c.pool_row_bytes : 0, 0x00020000);
+    {
+        const int p = min(lane, RS_HW - 1);   // surplus lanes duplicate the last halo pixel
+        const int xx = sx * 32 + p - 1;
+        c.in_voff = (uint32_t)(min(max(xx, 0), W - 1) * Cw * 4);
+        c.mx2 = (xx >= 0 && xx < W) ? 0x22222222u : 0u;
+        c.wr = lds[wave] + p;
+        c.rd = lds[wave] + half * RS_HW + col;
+        const int x = sx * 32 + col;
+        const bool ok = x < W && half == 0;   // both halves hold the finished word: one stores it
+        c.out_voff = ok ? (uint32_t)((x * Cow + ct) * 4) : RS_BAD_LANE;
+        c.pool_voff = (ok && (col & 1) == 0) ? (uint32_t)(((x >> 1) * Cow + ct) * 4) : RS_BAD_LANE;
+        c.psel = 0;
+    }
+
+    // ---- start values of the 16 channels of this lane
+    v16f init;
+    {
+        const int cbase = ct * 32 + 16 * half;   // < Cout: ct < Cout / 32
+        const int4 *tp = reinterpret_cast<const int4 *>(thresh + cbase);
+        const int4 *sp = reinterpret_cast<const int4 *>(wsum + cbase);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int4 t = tp[k], u = sp[k];
+            init[4 * k] = start_value(t.x, u.x); init[4 * k + 1] = start_value(t.y, u.y);
+            init[4 * k + 2] = start_value(t.z, u.z); init[4 * k + 3] = start_value(t.w, u.w);
+        }
+    }
+
+    // ---- weights: [tile64][step][tap][m][lane], resident for the whole strip
+    v4i Wg[2][3][3];   // [step][kx][ky]
+    {
+        const uint4 *wk = wfrag + (size_t)(ct >> 1) * (2 * 18 * 64) + (ct & 1) * 64 + lane;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int kx = 0; kx < 3; ++kx)
+#pragma unroll
+                for (int ky = 0; ky < 3; ++ky) {
+                    const uint4 w = wk[(ks * 9 + ky * 3 + kx) * 128];
+                    Wg[ks][kx][ky] = (v4i){(int)w.x, (int)w.y, (int)w.z, (int)w.w};
+                }
+    }
+
+    // ---- prologue: halo rows 0..3 through the two ring slots, rows 0..2 into the window, row 3
+    // left in the ring, rows 4 and 5 in flight
+    Rows2Stream st;
+    {
+        uint4 g4[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) fetch_row4(c, y0 - 1 + j, g4[j], CW4);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) fetch_row4(c, y0 + 3 + j, st.gq[j], CW4);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int yy = y0 - 1 + j;
+            const uint32_t m2 = (yy >= 0 && yy < H) ? c.mx2 : 0u, p1 = (~m2 >> 1) & 0x11111111u;
+            const uint32_t wv[4] = {g4[j].x, g4[j].y, g4[j].z, g4[j].w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                c.wr[(j & 1) * R2_ROW + (k >> 1) * RS_ROW + (k & 1) * RS_HW] =
+                    expand_word_masked(wv[k], (k < 3 || CW4) ? m2 : 0u, (k < 3 || CW4) ? p1 : 0u);
+            __builtin_amdgcn_wave_barrier();
+            if (j < 3) {
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int x = 0; x < 3; ++x) {
+                        const uint4 f = c.rd[(j & 1) * R2_ROW + u * RS_ROW + x];
+                        st.F[u][j][x] = (v4i){(int)f.x, (int)f.y, (int)f.z, (int)f.w};
+                    }
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+    }
+    st.acc[1] = init;     // "previous row" of row 0: collected, never stored
+    st.wkeep = 0;
+
+    // (everything fetched so far complete before the loop, as in the kernel above)
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int kx = 0; kx < 3; ++kx)
+#pragma unroll
+            for (int ky = 0; ky < 3; ++ky) RS_PIN(Wg[ks][kx][ky]);
+    RS_PIN(st.gq[0].x); RS_PIN(st.gq[0].y); RS_PIN(st.gq[0].z); RS_PIN(st.gq[0].w);
+    RS_PIN(st.gq[1].x); RS_PIN(st.gq[1].y); RS_PIN(st.gq[1].z); RS_PIN(st.gq[1].w);
+
+    int i = 0;
+#pragma unroll 1
+    for (; i + 6 <= rows; i += 6) {
+        rows2_step<CW4, POOL, 0, 0, false>(c, i, Wg, init, st);
+        rows2_step<CW4, POOL, 1, 1, false>(c, i + 1, Wg, init, st);
+        rows2_step<CW4, POOL, 0, 2, false>(c, i + 2, Wg, init, st);
+        rows2_step<CW4, POOL, 1, 0, false>(c, i + 3, Wg, init, st);
+        rows2_step<CW4, POOL, 0, 1, false>(c, i + 4, Wg, init, st);
+        rows2_step<CW4, POOL, 1, 2, false>(c, i + 5, Wg, init, st);
+    }
+#pragma unroll 1
+    for (; i < rows; i += 2) {
+        rows2_step<CW4, POOL, 0, 0, true>(c, i, Wg, init, st);
+        rows2_step<CW4, POOL, 1, 0, true>(c, i + 1, Wg, init, st);
+    }
+
+    // ---- the signs of the last odd row, still in accumulator set 1
+    uint32_t s = 0;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s = __builtin_amdgcn_alignbit(s, __float_as_uint(st.acc[1][15 - e]), 31);
+    store_row32<POOL, true>(c, s, i - 1 < rows ? i - 1 : -1, st.wkeep);
+}
+
+template <bool POOL>
+static int launch_rows2k_t(const uint32_t *act, int N, int H, int W, const BlobLayout &L, const uint4 *wfrag,
+                           const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, hipStream_t s)
+{
+    const int32_t *wsum =
+        (const int32_t *)((const uint8_t *)wfrag - L.off_f4 + L.off_cnt) + (size_t)10 * L.cout_pad64;
+    const int ctiles = L.cout >> 5;           // 32-channel tiles (cout is a multiple of 32)
+    const int strips = ceil_div(W, 32);
+    const long base = (long)N * strips * ctiles;
+    const long slots = 2L * 4 * 256;
+    const int want = (int)std::max(1L, slots / base);
+    int seg_rows = ceil_div(H, want);
+    seg_rows = std::max(2, seg_rows + (seg_rows & 1));        // even: 2x2 windows stay inside a segment
+    const int nseg = ceil_div(H, seg_rows);
+    const long units = base * nseg;
+    if (units > 0x7fffffffL) return fail(MBU_ERR_SHAPE, "too many tiles for one launch");
+    const int grid = (int)((units + 3) / 4);
+    if (L.cin_words == 4)
+        MBU_LAUNCH((conv_mfma_rows2k_kernel<true, POOL>), dim3(grid), dim3(256), 0, s, act, H, W, L.cin_words,
+                   wfrag, L.cout, ctiles, strips, nseg, seg_rows, (int)units, thresh, wsum, out_bits, out_pool);
+    else
+        MBU_LAUNCH((conv_mfma_rows2k_kernel<false, POOL>), dim3(grid), dim3(256), 0, s, act, H, W, L.cin_words,
+                   wfrag, L.cout, ctiles, strips, nseg, seg_rows, (int)units, thresh, wsum, out_bits, out_pool);
+    return check_launch("conv_mfma_rows2k");
+}
+
 template <bool POOL, int WPS>
 static int launch_rows_t(const uint32_t *act, int N, int H, int W, const BlobLayout &L, const uint4 *wfrag,
                   const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, hipStream_t s)
@@ -380,6 +686,24 @@ bool conv_rows_supported(int H, int W, const BlobLayout &L, bool wants_bits)
     // one input step, packed output wanted, every image below 2^30 bytes on both sides
     return L.ksteps == 1 && wants_bits && (double)H * W * L.cin_words * 4 < 1073741824.0 &&
            (double)H * W * (L.cout >> 5) * 4 < 1073741824.0;
+}
+
+bool conv_rows2k_supported(int H, int W, const BlobLayout &L, bool wants_bits)
+{
+    // two input steps (three or four words per pixel), otherwise as above
+    return L.ksteps == 2 && L.cin_words >= 3 && wants_bits && (double)H * W * L.cin_words * 4 < 1073741824.0 &&
+           (double)H * W * (L.cout >> 5) * 4 < 1073741824.0;
+}
+
+int launch_conv_mfma_rows2k(const uint32_t *act, int N, int H, int W, const BlobLayout &L, const void *blob,
+                            const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, hipStream_t s)
+{
+    if (!conv_rows2k_supported(H, W, L, out_bits != nullptr))
+        return fail(MBU_ERR_SHAPE, "row-streaming kernel for two input steps: layer not supported");
+    if (out_pool && ((H & 1) || (W & 1))) return fail(MBU_ERR_SHAPE, "pooled output needs even H and W");
+    const uint4 *wfrag = (const uint4 *)((const uint8_t *)blob + L.off_f4);
+    if (out_pool) return launch_rows2k_t<true>(act, N, H, W, L, wfrag, thresh, out_bits, out_pool, s);
+    return launch_rows2k_t<false>(act, N, H, W, L, wfrag, thresh, out_bits, out_pool, s);
 }
 
 int launch_conv_mfma_rows(const uint32_t *act, int N, int H, int W, const BlobLayout &L, const void *blob,

@@ -253,8 +253,8 @@ int mbu_classifier_fp32(const uint32_t *act, int N, int H, int W, int C, const f
 int mbu_set_conv_tuning(int rows_per_wave, int reserved)
 {
     if ((rows_per_wave != 0 && rows_per_wave != 1 && rows_per_wave != 3 && rows_per_wave != 6 &&
-         rows_per_wave != 7 && rows_per_wave != 8) || reserved != 0)
-        return fail(MBU_ERR_ARG, "mbu_set_conv_tuning: kernel in {0,1,3,6,7,8}, second argument 0");
+         rows_per_wave != 7 && rows_per_wave != 8 && rows_per_wave != 9) || reserved != 0)
+        return fail(MBU_ERR_ARG, "mbu_set_conv_tuning: kernel in {0,1,3,6,7,8,9}, second argument 0");
     g_tune_rw = rows_per_wave;
     g_tune_wm = 0;
     return MBU_OK;

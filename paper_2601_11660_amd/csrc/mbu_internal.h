@@ -88,6 +88,10 @@ int launch_conv_mfma_two(const uint32_t *act, int Ca, const uint32_t *low, int C
 // row-streaming kernel for layers with a single 64-channel input step (optional 2x2-pooled
 // second output); waves_per_simd = 1 or 2
 bool conv_rows_supported(int H, int W, const BlobLayout &L, bool wants_bits);
+// the same scheme for layers with two 64-channel input steps, 32 output channels per wave
+bool conv_rows2k_supported(int H, int W, const BlobLayout &L, bool wants_bits);
+int launch_conv_mfma_rows2k(const uint32_t *act, int N, int H, int W, const BlobLayout &L, const void *blob,
+                            const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, hipStream_t s);
 int launch_conv_mfma_rows(const uint32_t *act, int N, int H, int W, const BlobLayout &L, const void *blob,
                           const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, int waves_per_simd,
                           hipStream_t s);

@@ -130,7 +130,7 @@ def test_conv_degenerate_masks_and_ties(path, pname):
         assert np.array_equal(bits, bitref.pack_pm1(O.threshold(acc_ref, th)))
 
 
-@pytest.mark.parametrize("kernel", [1, 3, 6, 7, 8])
+@pytest.mark.parametrize("kernel", [1, 3, 6, 7, 8, 9])
 @pytest.mark.parametrize("shape", SMALL_SHAPES + [(1, 100, 100, 128, 128, 0.6), (2, 31, 67, 64, 192, 0.5)])
 def test_every_matrix_kernel_variant_matches_oracle(shape, kernel):
     """The library picks a kernel variant per layer shape; each variant must be exact on
@@ -170,6 +170,37 @@ def test_row_streaming_kernel_with_pooled_output(shape, kernel):
     case = synth.conv_case(11, 0, N, H, W, Cin, Cout, 0.6)
     _, out_ref = O.masked_binary_layer(case.a, case.w, case.theta)
     B.set_conv_tuning(kernel)
+    pa = B.pack_act(dev(case.a))
+    blob = B.pack_weights(dev(case.w))
+    bits, pool = B.conv3x3_masked_binary_fused(pa, Cin, None, 0, blob, Cout, dev(case.theta), True, True)
+    torch.cuda.synchronize()
+    assert np.array_equal(host_u32(bits), bitref.pack_pm1(out_ref))
+    assert np.array_equal(host_u32(pool), bitref.pack_pm1(O.maxpool2x2(out_ref)))
+    bits2, _ = run_layer(case, B.PATH_MFMA, want_acc=False)
+    assert np.array_equal(bits2, bitref.pack_pm1(out_ref))
+
+
+ROWS2K_SHAPES = [
+    # N, H, W, Cin, Cout: two 64-channel input steps (three or four words per pixel)
+    (1, 64, 64, 128, 128),
+    (2, 38, 70, 128, 64),      # ragged strip, two images
+    (1, 2, 2, 96, 32),         # three words in, one output tile
+    (1, 130, 34, 100, 96),     # Cin not a multiple of 32, many row segments, odd tile count
+    (3, 6, 200, 128, 128),
+    (1, 160, 2048, 128, 128),  # row segments of 20 rows (6-row loop body + remainder)
+    (1, 110, 2048, 96, 64),    # ... 8 rows
+]
+
+
+@pytest.mark.parametrize("shape", ROWS2K_SHAPES)
+def test_row_streaming_kernel_for_two_input_steps(shape):
+    """The row-streaming kernel for layers with 65..128 input channels (32 output channels per
+    wave): packed output and the 2x2-pooled output of the same pass against the oracle."""
+    N, H, W, Cin, Cout = shape
+    say(f"conv rows2k N={N} H={H} W={W} Cin={Cin} Cout={Cout}")
+    case = synth.conv_case(12, 0, N, H, W, Cin, Cout, 0.6)
+    _, out_ref = O.masked_binary_layer(case.a, case.w, case.theta)
+    B.set_conv_tuning(9)
     pa = B.pack_act(dev(case.a))
     blob = B.pack_weights(dev(case.w))
     bits, pool = B.conv3x3_masked_binary_fused(pa, Cin, None, 0, blob, Cout, dev(case.theta), True, True)
