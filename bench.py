@@ -339,7 +339,7 @@ def main():
     mfma = path != B.PATH_VALU
     achieved = conv_ops / conv_ms / 1e9   # T op/s over all conv launches of a step
     roof = {"bound": "mfma" if mfma else "alu",
-            "kernel": ("conv_mfma_block_kernel + conv_mfma_rows_kernel (the 18 conv launches of a pass)"
+            "kernel": ("conv_mfma_block / rows / rows2k / upcat kernels (the 18 conv launches of a pass)"
                        if mfma else "conv_valu_kernel"),
             "achieved": round(achieved, 1),
             "peak": PEAK_FP4_TFLOPS if mfma else PEAK_VALU_BIT_TOPS,
