@@ -519,3 +519,29 @@ def test_upsampled_channels_collapse_to_2x2_kernels_at_low_resolution():
                     win = pad[:, dy + a:dy + a + Hl, dx + b:dx + b + Wl]
                     got += np.einsum("nyxc,oc->nyxo", win, k2[:, a, b])
             assert np.array_equal(got, acc[:, dy::2, dx::2]), (dy, dx)
+
+
+def test_bit_valued_activations_with_half_valued_padding_reproduce_the_layer():
+    """Identity the matrix-path kernels of the library rely on (a property of Eq. 1 with zero
+    padding, Sec. 3.1.1): with a' = (a + 1) / 2 - the packed bit itself, and 1/2 for a pixel
+    outside the image, whose value 0 lies half way between -1 and +1 - the accumulator is
+    sum w a = 2 sum w a' - sum w, the last sum over ALL taps and channels of the output channel,
+    borders included.  All terms are multiples of 1/2 and every partial sum is exactly
+    representable, so a threshold comparison R >= theta is the sign test of
+    sum w a' - (theta + sum w) / 2.  Checked on the oracle's accumulators."""
+    rng = np.random.default_rng(9)
+    N, H, W, C, Co = 2, 4, 5, 7, 6
+    a = synth.pm1_bits(rng, (N, H, W, C))
+    w = rng.integers(-1, 2, size=(Co, 3, 3, C)).astype(np.int8)
+    theta = rng.integers(-10, 11, size=Co).astype(np.int32)
+    acc, out = O.masked_binary_layer(a, w, theta)
+    half = np.full((N, H + 2, W + 2, C), 0.5)
+    half[:, 1:-1, 1:-1] = (a.astype(np.float64) + 1.0) / 2.0
+    got = np.zeros((N, H, W, Co))
+    for ky in range(3):
+        for kx in range(3):
+            got += np.einsum("nyxc,oc->nyxo", half[:, ky:ky + H, kx:kx + W], w[:, ky, kx].astype(np.float64))
+    wsum = w.astype(np.int64).reshape(Co, -1).sum(1)
+    assert np.array_equal(2.0 * got - wsum, acc.astype(np.float64))
+    start = -(theta.astype(np.float64) + wsum) / 2.0
+    assert np.array_equal(np.where(got + start >= 0, 1, -1), out)
