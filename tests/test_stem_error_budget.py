@@ -1,0 +1,69 @@
+"""CPU check of the error budget behind the first layer's matrix-core estimate (Sec. 4.1 keeps
+the first convolution in full precision; the library decides the SIGN of its float32 sums from
+a split-fp16 estimate and recomputes what the estimate cannot decide).
+
+The row-walking kernel scales a whole window (3 rows x 34 pixels x 3 channels) by one power of
+two s that brings its largest magnitude into [2^13, 2^14), splits every scaled value v into two
+fp16 terms v = h + l + r, does the same with every weight row (scaled to a Euclidean norm in
+[2^12, 2^13)), and sums the products wh*xh + wh*xl + wl*xh.  Its decision threshold assumes
+    |estimate - exact| <= 3 * 2^-22 * ||w|| * ||x||  +  sqrt(27) * 2^13 * 2^-25
+for the terms the split drops (the rounding of the accumulation and of the reference chain are
+budgeted separately).  This test emulates the split with numpy's float16 (round to nearest
+even, subnormals kept, like the GPU's conversion) and checks that inequality on data whose
+magnitudes vary by up to 2^40 inside a window - the case in which the absolute term matters."""
+import numpy as np
+
+
+def split16(v32):
+    h = v32.astype(np.float16)
+    r = (v32 - h.astype(np.float32)).astype(np.float32)       # exact in float32
+    l = r.astype(np.float16)
+    return h.astype(np.float64), l.astype(np.float64)
+
+
+def pow2_scale(target_exp, x):
+    """power of two that brings x into [2^target_exp, 2^(target_exp + 1))"""
+    return np.exp2(target_exp - np.floor(np.log2(x)))
+
+
+def test_dropped_terms_of_the_window_scaled_split_stay_inside_the_budget():
+    rng = np.random.default_rng(3)
+    worst_rel, worst_abs_used = 0.0, False
+    for trial in range(40):
+        Co = 16
+        win = rng.standard_normal((3, 34, 3)).astype(np.float32)
+        style = trial % 4
+        if style == 1:
+            win *= np.exp2(rng.integers(-20, 21, size=(3, 34, 1))).astype(np.float32)
+        elif style == 2:
+            win[:, 10:, :] *= np.float32(2.0 ** -30)           # a dark region next to a bright one
+        elif style == 3:
+            win *= np.float32(2.0 ** float(rng.integers(-100, 100)))
+        w = rng.standard_normal((Co, 3, 3, 3)).astype(np.float32)
+        w *= np.exp2(rng.integers(-30, 31, size=(Co, 1, 1, 1))).astype(np.float32)
+        s = np.float32(pow2_scale(13, float(np.abs(win).max())))
+        t = (win * s).astype(np.float32)                        # exact: a power of two
+        assert 2.0 ** 13 <= np.abs(t).max() < 2.0 ** 14
+        th, tl = split16(t)
+        wn = np.sqrt((w.astype(np.float64) ** 2).reshape(Co, -1).sum(1))
+        sw = pow2_scale(12, wn).astype(np.float32)
+        ws = (w * sw[:, None, None, None]).astype(np.float32)
+        wh, wl = split16(ws)
+        for x in range(32):
+            ph, pl = th[:, x:x + 3], tl[:, x:x + 3]             # [ky][kx][ci]
+            pt = t[:, x:x + 3].astype(np.float64)
+            est = np.einsum("oyxc,yxc->o", wh, ph) + np.einsum("oyxc,yxc->o", wh, pl) + \
+                np.einsum("oyxc,yxc->o", wl, ph)
+            exact = np.einsum("oyxc,yxc->o", ws.astype(np.float64), pt)
+            wnorm = np.sqrt((ws.astype(np.float64) ** 2).reshape(Co, -1).sum(1))
+            xnorm = np.sqrt((pt ** 2).sum())
+            rel = 3.0 * 2.0 ** -22 * wnorm * xnorm
+            floor = np.sqrt(27.0) * 2.0 ** 13 * 2.0 ** -25
+            err = np.abs(est - exact)
+            assert (err <= rel + floor).all(), (trial, x, float((err / (rel + floor)).max()))
+            worst_rel = max(worst_rel, float((err / (rel + floor)).max()))
+            worst_abs_used |= bool((err > rel).any())
+    # the absolute term is needed on this data (the relative bound alone is violated somewhere),
+    # and the kernel's constant 2^-9 covers it
+    assert worst_abs_used and np.sqrt(27.0) * 2.0 ** 13 * 2.0 ** -25 < 2.0 ** -9
+    assert worst_rel <= 1.0
