@@ -394,6 +394,208 @@ __global__ __launch_bounds__(256, RG == 2 ? 4 : 2) void tconv_bits_kernel(
     }
 }
 
+// Weights resident, activations through LDS.  The kernel above lets every lane fetch its own
+// packed word of every step: 8 useful bytes per 32-byte sector and request, the same sectors
+// again for every step and for each of the four position waves - the address and cache path
+// of the compute unit is busy four times as long as the matrix cores, which ran at a sixth of
+// their rate.  Here the block fetches the words of a pixel group once, coalesced (16 bytes per
+// thread, a row of 32 pixels is contiguous), and passes them through LDS ([row][word][pixel]:
+// a wave's reads are conflict-free); the fetch of the next group is in flight while the current
+// one multiplies, one barrier per group.  With KS <= 16 input steps the weights of a wave's
+// position and channel tile are only 8 KS registers: loaded once.  A group's first step takes
+// -theta as the addend of its matrix instructions.  RGX rows of 32 pixels per group, so that a group is 1024 words (512 for KS = 2): one fetch per thread.
+// Needs an even word count (Cin a multiple of 64).
+template <int KS, int RGX>
+__global__ __launch_bounds__(256, 2) void tconv_res_kernel(
+    const uint32_t *__restrict__ act, int N, int H, int W, const uint4 *__restrict__ wfrag, int Cout,
+    int groups, int groups_x, int groups_y, const int32_t *__restrict__ thresh, uint32_t *__restrict__ out_bits)
+{
+    constexpr uint32_t BAD = 0x40000000u;   // beyond any tensor this kernel accepts (< 2^30 bytes)
+    constexpr int CW = 2 * KS;              // words per pixel
+    constexpr int TILE = RGX * CW * 32;     // words per pixel group
+    constexpr int PW = TILE / 256;          // words per thread and group: 4 (2 for KS = 2)
+    static_assert(PW == 4 || PW == 2, "one 16- or 8-byte fetch per thread");
+    __shared__ float4 init_tab[2][2][4];    // [half][m][4 x 4 channels]: -theta
+    __shared__ uint32_t words[2][TILE];     // [buffer][row][word][pixel]
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int p = __builtin_amdgcn_readfirstlane(tid >> 6);           // position of this wave
+    const int ct = blockIdx.y;                                        // 64-channel output tile
+    const int col = lane & 31, half = lane >> 5;
+    const int Cow = Cout >> 5;
+    const int dy = p >> 1, dx = p & 1;
+    const uint32_t psel = half ? 0x07060302u : 0x05040100u;
+
+    if (tid < 16) {   // thread (h, m, q) writes one float4 of the table (visible after the first barrier)
+        const int h = tid >> 3, m = (tid >> 2) & 1, q = tid & 3;
+        const int cbase = ct * 64 + m * 32 + 16 * h + 4 * q;
+        int4 t = make_int4(0, 0, 0, 0);
+        if (cbase < Cout) t = *reinterpret_cast<const int4 *>(thresh + cbase);
+        float4 f;
+        f.x = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.x));
+        f.y = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.y));
+        f.z = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.z));
+        f.w = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.w));
+        init_tab[h][m][q] = f;
+    }
+
+    const __amdgpu_buffer_rsrc_t ars =
+        __builtin_amdgcn_make_buffer_rsrc((void *)act, 0, N * H * W * CW * 4, 0x00020000);
+    const __amdgpu_buffer_rsrc_t ors =
+        __builtin_amdgcn_make_buffer_rsrc((void *)out_bits, 0, N * H * W * 4 * Cow * 4, 0x00020000);
+    const uint32_t out_lane = (ct * 2 + half < Cow) ? (uint32_t)(((2 * col + dx) * Cow + ct * 2 + half) * 4) : BAD;
+
+    // ---- the weights of this wave: [tile64][step][position][m][lane]
+    v4i Wt[KS][2];
+    {
+        const uint4 *wk = wfrag + (size_t)ct * KS * 8 * 64 + lane;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int m = 0; m < 2; ++m) {
+                const uint4 a = wk[((ks * 4 + p) * 2 + m) * 64];
+                Wt[ks][m] = (v4i){(int)a.x, (int)a.y, (int)a.z, (int)a.w};
+            }
+    }
+
+    // ---- staging: thread tid fetches words k0 .. k0 + PW - 1 of pixel spx of row sr of the group
+    constexpr int PIECES = CW / PW;                    // fetches per pixel
+    const int sr = tid / (32 * PIECES);
+    const int spx = (tid / PIECES) % 32;
+    const int k0 = (tid % PIECES) * PW;
+    uint32_t *const swr = &words[0][(sr * CW + k0) * 32 + spx];     // + buffer * TILE, + 32 per word
+    // ---- this lane's reads: word 2 ks + half of pixel col of row r
+    const uint32_t *const srd = &words[0][half * 32 + col];         // + (r * CW + 2 ks) * 32
+
+    struct Plan { int gx, gy, n; };
+    auto plan = [&](int g) {
+        Plan P;
+        P.gx = g % groups_x;
+        const int q = g / groups_x;
+        P.gy = q % groups_y;
+        P.n = q / groups_y;
+        return P;
+    };
+    // the fetched words of a group, two groups ahead of the one being multiplied (two register
+    // sets alternate): a fetch has two group times to arrive
+    auto fetch = [&](const Plan &P, uint32_t (&st)[PW]) {
+        const int x = P.gx * 32 + spx, y = P.gy * RGX + sr;
+        // a pixel outside the image: any offset beyond the tensor (reads 0; masked at expansion)
+        const uint32_t off = (x < W && y < H) ? (uint32_t)((((P.n * H + y) * W + x) * CW + k0) * 4) : BAD;
+        if (PW == 4) {
+            const auto v = __builtin_amdgcn_raw_buffer_load_b128(ars, off, 0, 0);
+#pragma unroll
+            for (int i = 0; i < PW; ++i) st[i] = v[i];
+        } else {
+            const auto v = __builtin_amdgcn_raw_buffer_load_b64(ars, off, 0, 0);
+#pragma unroll
+            for (int i = 0; i < PW; ++i) st[i] = v[i];
+        }
+    };
+    auto commit = [&](int buf, const uint32_t (&st)[PW]) {
+#pragma unroll
+        for (int i = 0; i < PW; ++i) swr[buf * TILE + i * 32] = st[i];
+    };
+
+    // every thread of the block walks over the same groups (and reaches the same barriers)
+    const int stride = gridDim.x;
+    int g = blockIdx.x;               // < groups: the grid is not larger
+    Plan cur = plan(g);
+    // a group index past the last one: the words of the block's first group again, unused
+    auto plan_or_first = [&](int gi) { return plan(gi < groups ? gi : (int)blockIdx.x); };
+    uint32_t sa[PW], sb[PW];
+    fetch(cur, sa);
+    Plan nxt = plan_or_first(g + stride);
+    fetch(nxt, sb);
+    commit(0, sa);
+    __syncthreads();
+    int buf = 0;
+
+    // one group: fetch of group g + 2 stride into sf, matrix work of group g from LDS buffer
+    // `buf`, words of group g + stride (in sc since the previous group) into the other buffer.
+    // Returns false after the block's last group (the same decision in every thread).
+    auto group = [&](const uint32_t (&sc)[PW], uint32_t (&sf)[PW]) -> bool {
+        const Plan nn = plan_or_first(g + 2 * stride);
+        fetch(nn, sf);
+        v16f acc[RGX][2];
+#pragma unroll
+        for (int m = 0; m < 2; ++m)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const float4 f = init_tab[half][m][q];
+#pragma unroll
+                for (int r = 0; r < RGX; ++r) {
+                    acc[r][m][4 * q] = f.x; acc[r][m][4 * q + 1] = f.y;
+                    acc[r][m][4 * q + 2] = f.z; acc[r][m][4 * q + 3] = f.w;
+                }
+            }
+        uint32_t k8[RGX];
+#pragma unroll
+        for (int r = 0; r < RGX; ++r)
+            k8[r] = (cur.gx * 32 + col < W && cur.gy * RGX + r < H) ? 0x88888888u : 0u;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            v4i B[RGX];
+#pragma unroll
+            for (int r = 0; r < RGX; ++r) {
+                const uint32_t m8 = k8[r], m2 = m8 >> 2;
+                const uint32_t word = srd[buf * TILE + (r * CW + 2 * ks) * 32];
+                B[r] = (v4i){(int)(((word << 3) & m8) | m2), (int)(((word << 2) & m8) | m2),
+                             (int)(((word << 1) & m8) | m2), (int)((word & m8) | m2)};
+            }
+#pragma unroll
+            for (int r = 0; r < RGX; ++r)
+#pragma unroll
+                for (int m = 0; m < 2; ++m) acc[r][m] = mfma_f4(Wt[ks][m], B[r], acc[r][m]);
+        }
+        // ---- epilogue: input pixel (y, x) -> output pixel (2y + dy, 2x + dx)
+        const uint32_t lane_off = (cur.gx * 32 + col < W) ? out_lane + (uint32_t)(cur.gx * 64 * Cow * 4) : BAD;
+#pragma unroll
+        for (int r = 0; r < RGX; ++r) {
+            const int y = cur.gy * RGX + r;
+            uint32_t s0 = 0, s1 = 0;
+#pragma unroll
+            for (int i = 15; i >= 0; --i) {
+                s0 = __builtin_amdgcn_alignbit(s0, __float_as_uint(acc[r][0][i]), 31);
+                s1 = __builtin_amdgcn_alignbit(s1, __float_as_uint(acc[r][1][i]), 31);
+            }
+            const uint32_t word = finish_word64(s0, s1, psel);
+            if (y < H) {
+                const uint32_t row_off = (uint32_t)((((cur.n * 2 * H + 2 * y + dy) * 2 * W) * Cow) * 4);
+                __builtin_amdgcn_raw_buffer_store_b32(word, ors, lane_off + row_off, 0, 0);
+            }
+        }
+        g += stride;
+        if (g >= groups) return false;
+        buf ^= 1;
+        commit(buf, sc);       // the buffer the block read one group ago: every wave has passed
+        __syncthreads();       // the barrier since
+        cur = nxt;
+        nxt = nn;
+        return true;
+    };
+#pragma unroll 1
+    for (;;) {
+        if (!group(sb, sa)) break;
+        if (!group(sa, sb)) break;
+    }
+}
+
+template <int KS, int RGX>
+static int launch_tconv_res(const uint32_t *act, int N, int H, int W, const TconvLayout &L, const uint4 *wfrag,
+                            const int32_t *thresh, uint32_t *out_bits, hipStream_t s)
+{
+    const int groups_x = ceil_div(W, 32), groups_y = ceil_div(H, RGX);
+    const long groups = (long)N * groups_y * groups_x;
+    if (groups > 0x7fffffffL) return fail(MBU_ERR_SHAPE, "too many pixel groups for one launch");
+    const int tiles64 = L.cout_pad64 / 64;
+    // two blocks per compute unit in total, spread over the 64-channel tiles
+    const int per_tile = (int)std::min(groups, (long)std::max(1, 512 / tiles64));
+    MBU_LAUNCH((tconv_res_kernel<KS, RGX>), dim3((unsigned)per_tile, (unsigned)tiles64), dim3(256), 0, s, act, N, H,
+               W, wfrag, L.cout, (int)groups, groups_x, groups_y, thresh, out_bits);
+    return check_launch("tconv2x2_masked_binary");
+}
+
 int launch_tconv_mfma(const uint32_t *act, int N, int H, int W, const TconvLayout &L,
                       const void *blob, const int32_t *thresh, uint32_t *out_bits, int32_t *out_acc,
                       hipStream_t s)
@@ -406,8 +608,15 @@ int launch_tconv_mfma(const uint32_t *act, int N, int H, int W, const TconvLayou
     // kernel, two blocks per compute unit spread over the 64-channel tiles
     const int tiles64 = L.cout_pad64 / 64;
     const double GiB = 1073741824.0;
-    if (!out_acc && L.ksteps >= 2 && (double)N * H * W * L.cin_words * 4 < GiB && (double)N * H * W * 4 * (L.cout >> 5) * 4 < GiB &&
-        (double)L.ksteps * 8 * 1024 < GiB) {
+    const bool small = (double)N * H * W * L.cin_words * 4 < GiB && (double)N * H * W * 4 * (L.cout >> 5) * 4 < GiB;
+    // 128, 256, 512 or 1024 input channels (an even word count): weights resident
+    if (!out_acc && small && L.cin_words == 2 * L.ksteps) {
+        if (L.ksteps == 2) return launch_tconv_res<2, 4>(act, N, H, W, L, wfrag, thresh, out_bits, s);
+        if (L.ksteps == 4) return launch_tconv_res<4, 4>(act, N, H, W, L, wfrag, thresh, out_bits, s);
+        if (L.ksteps == 8) return launch_tconv_res<8, 2>(act, N, H, W, L, wfrag, thresh, out_bits, s);
+        if (L.ksteps == 16) return launch_tconv_res<16, 1>(act, N, H, W, L, wfrag, thresh, out_bits, s);
+    }
+    if (!out_acc && L.ksteps >= 2 && small && (double)L.ksteps * 8 * 1024 < GiB) {
         constexpr int RGF = RG;
         const int gy2 = ceil_div(H, RGF);
         const long groups2 = (long)N * gy2 * groups_x;

@@ -306,6 +306,9 @@ TCONV_SHAPES = [
     (1, 1, 1, 32, 64),
     (1, 6, 9, 40, 96),        # Cin not a multiple of 32
     (1, 16, 16, 1024, 512),
+    (2, 5, 37, 256, 96),      # four input steps: weights-resident kernel, ragged groups, two images
+    (1, 7, 70, 512, 64),      # eight steps, groups of two rows
+    (1, 9, 33, 128, 128),     # two steps, groups of four rows with a ragged last group
 ]
 
 
