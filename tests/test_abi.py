@@ -122,6 +122,9 @@ def test_packed_weight_size_and_path_switch():
     assert B.lib().mbu_set_conv_path(9) == B.MBU_ERR_ARG
     assert B.lib().mbu_set_conv_tuning(5, 0) == B.MBU_ERR_ARG
     assert B.lib().mbu_set_conv_tuning(3, 1) == B.MBU_ERR_ARG
+    for k in (1, 3, 6, 7, 8, 9):
+        assert B.lib().mbu_set_conv_tuning(k, 0) == 0
+    assert B.lib().mbu_set_conv_tuning(10, 0) == B.MBU_ERR_ARG
     assert B.lib().mbu_set_conv_tuning(0, 0) == 0
     B.set_conv_path(B.PATH_VALU)
     assert B.get_conv_path() == B.PATH_VALU
