@@ -111,7 +111,9 @@ void orc_threshold(const int32_t *acc, const int32_t *theta, long pixels, int C,
             out[p * C + o] = acc[p * C + o] >= theta[o] ? 1 : -1;
 }
 
-/* 2x2 stride-2 max pooling on +-1 values (Sec. 3.2.2 calls it trivial). */
+/* 2x2 stride-2 max pooling on +-1 values (Sec. 3.2.2 calls it trivial).  The output has
+ * floor(H/2) x floor(W/2) pixels: the last row / column of an odd-sized input belongs to no
+ * window and is dropped (the paper's Carvana frames are 959 pixels wide, Appendix A.3). */
 void orc_maxpool2x2(const int8_t *in, int N, int H, int W, int C, int8_t *out)
 {
     int Ho = H / 2, Wo = W / 2;
@@ -139,6 +141,26 @@ void orc_upsample2x(const int8_t *in, int N, int H, int W, int C, int8_t *out)
                 for (int c = 0; c < C; ++c)
                     out[(((size_t)n * Ho + y) * Wo + x) * C + c] =
                         in[(((size_t)n * H + y / 2) * W + x / 2) * C + c];
+}
+
+/* Zero padding of a feature map to a larger size (decoder of a U-Net on frames whose sizes
+ * are not multiples of 2^levels, Appendix A.3: after floor pooling the up-sampled tensor is
+ * smaller than the encoder feature it is concatenated with, and is padded to that size
+ * first).  out[n][y+top][x+left][c] = in[n][y][x][c]; every other element of out is 0, a
+ * value that contributes nothing to the layer that follows.  in is [N][H][W][C], out is
+ * [N][Ho][Wo][C] with Ho >= top + H and Wo >= left + W. */
+void orc_zero_pad(const int8_t *in, int N, int H, int W, int C, int top, int left,
+                  int Ho, int Wo, int8_t *out)
+{
+    for (int n = 0; n < N; ++n)
+        for (int y = 0; y < Ho; ++y)
+            for (int x = 0; x < Wo; ++x) {
+                int yi = y - top, xi = x - left;
+                int inside = yi >= 0 && yi < H && xi >= 0 && xi < W;
+                for (int c = 0; c < C; ++c)
+                    out[(((size_t)n * Ho + y) * Wo + x) * C + c] =
+                        inside ? in[(((size_t)n * H + yi) * W + xi) * C + c] : 0;
+            }
 }
 
 /* Skip concatenation (Sec. 2.1): channels of a first, then channels of b. */

@@ -105,9 +105,9 @@ def masked_binary_tconv_layer(a, w, theta):
 
 
 def maxpool2x2(a):
+    """2x2 stride-2 max pooling; an odd last row / column is dropped (floor)."""
     a = _chk(a, np.int8, 4)
     N, H, W, C = a.shape
-    assert H % 2 == 0 and W % 2 == 0
     out = np.empty((N, H // 2, W // 2, C), np.int8)
     lib().orc_maxpool2x2(_p(a), N, H, W, C, _p(out))
     return out
@@ -118,6 +118,18 @@ def upsample2x(a):
     N, H, W, C = a.shape
     out = np.empty((N, 2 * H, 2 * W, C), np.int8)
     lib().orc_upsample2x(_p(a), N, H, W, C, _p(out))
+    return out
+
+
+def zero_pad_to(a, Ho, Wo):
+    """Pads a feature map with zeros to Ho x Wo, splitting the difference like the usual U-Net
+    decoder does: floor(d/2) rows on top / columns on the left, the rest at the bottom / right
+    (with floor pooling d is 0 or 1, so the padding sits at the bottom and on the right)."""
+    a = _chk(a, np.int8, 4)
+    N, H, W, C = a.shape
+    assert Ho >= H and Wo >= W
+    out = np.empty((N, Ho, Wo, C), np.int8)
+    lib().orc_zero_pad(_p(a), N, H, W, C, (Ho - H) // 2, (Wo - W) // 2, Ho, Wo, _p(out))
     return out
 
 
@@ -169,8 +181,10 @@ def unet_forward(image, stem_w, convs, cls_w, cls_b, levels=4, up_convs=None):
 
     convs: list of (w, theta) in execution order: two per encoder level (level 1 ..
     `levels`), two for the bottleneck, two per decoder level (`levels` .. 1);
-    2*(2*levels+1) entries.  Down-sampling is 2x2 max pooling, up-sampling is 2x
-    nearest neighbour, and the skip feature is placed before the up-sampled one.
+    2*(2*levels+1) entries.  Down-sampling is 2x2 max pooling (floor), up-sampling is 2x
+    nearest neighbour, and the skip feature is placed before the up-sampled one, which is
+    zero-padded to the skip feature's size when the two differ (odd frame sizes; the padded
+    elements are 0, not +-1, and add nothing to the next layer's sums).
     Returns (logits, taps) where taps is the list of every intermediate +-1 tensor
     in execution order as (name, array).
     """
@@ -201,7 +215,12 @@ def unet_forward(image, stem_w, convs, cls_w, cls_b, levels=4, up_convs=None):
             wu, tu = up_convs[levels - l]
             _, x = masked_binary_tconv_layer(x, wu, tu)
         taps.append((f"up{l}", x))
-        x = concat(skips[l - 1], x)
+        sk = skips[l - 1]
+        if x.shape[1:3] != sk.shape[1:3]:
+            # frame size not a multiple of 2^levels: pooling dropped a row / column on the way
+            # down, the up-sampled tensor is padded with zeros to the skip feature's size
+            x = zero_pad_to(x, sk.shape[1], sk.shape[2])
+        x = concat(sk, x)
         taps.append((f"cat{l}", x))
         x = double_conv(x, f"dec{l}")
     logits = classifier(x, cls_w, cls_b)

@@ -688,7 +688,6 @@ static const int32_t *weight_sums(const uint4 *wfrag, const BlobLayout &L)
     return (const int32_t *)(blob + L.off_cnt) + (size_t)10 * L.cout_pad64;
 }
 
-int g_tune_rw = 0, g_tune_wm = 0;   // 0 = automatic
 
 // Layers with two input steps: the row-streaming kernel (32 output channels per wave) or the
 // block-cooperative one?  Measured on MI355X: 128->128 at 512x1024 30.5 us against 33.1 us,
@@ -698,15 +697,19 @@ int g_tune_rw = 0, g_tune_wm = 0;   // 0 = automatic
 static bool use_rows2k(int N, int H, int W, const BlobLayout &L, bool wants_bits)
 {
     if (!conv_rows2k_supported(H, W, L, wants_bits)) return false;
-    if (g_tune_rw == 9) return true;
-    if (g_tune_rw != 0) return false;
+    if (t_cfg.tune_rw == 9) return true;
+    if (t_cfg.tune_rw != 0) return false;
     const long wave_rows = (long)N * H * ceil_div(W, 32) * (L.cout >> 5);
     return L.cout <= 128 && wave_rows >= 24L * 2048;
 }
-int g_persistent_blocks = 512;       // resident blocks of the block-cooperative kernel (2 per CU)
+static const int kPersistentBlocks = 512;   // resident blocks of the block-cooperative kernel (2 per CU)
 
 // waves per SIMD of the row-streaming kernel for single-step layers, 0 = kernel not used
-static int rows_kernel_waves() { return (g_tune_rw == 0 || g_tune_rw == 7 || g_tune_rw == 9) ? 2 : g_tune_rw == 8 ? 1 : 0; }
+static int rows_kernel_waves()
+{
+    const int m = t_cfg.tune_rw;
+    return (m == 0 || m == 7 || m == 9) ? 2 : m == 8 ? 1 : 0;
+}
 
 bool conv_writes_pooled(int H, int W, const BlobLayout &L)
 {
@@ -760,7 +763,7 @@ static int launch_block_t(const ConvIO &io, int N, int H, int W, const BlobLayou
     // persistent blocks: two per compute unit in total, spread over the output-channel
     // groups; each strides over the pixel tiles
     const int groups = ceil_div(tiles64, WN);
-    const long per_group = max(1, g_persistent_blocks / groups);
+    const long per_group = max(1, kPersistentBlocks / groups);
     dim3 grid((unsigned)min(tiles, per_group), (unsigned)groups);
     const TileStep tstep = tile_step((int)grid.x, ceil_div(W, TW), ceil_div(H, RW * WM));
     const bool even = (io.cwa % 2 == 0) && (!TWO_SRC || io.cwb % 2 == 0);
@@ -828,7 +831,7 @@ int launch_conv_mfma(const uint32_t *act, int N, int H, int W, const BlobLayout 
     // row-streaming kernel hides it (64->64 at 1024x2048: 25 us against 31 us for the
     // wave-private tile kernel, which remains for shapes the streaming kernel does not take);
     // with several steps the block-cooperative kernel stages least per wave and wins.
-    const int mode = g_tune_rw;   // 0 = automatic; see mbu_set_conv_tuning
+    const int mode = t_cfg.tune_rw;   // 0 = automatic; see mbu_set_conv_tuning
     if (use_rows2k(N, H, W, L, out_bits != nullptr))
         return launch_conv_mfma_rows2k(act, N, H, W, L, blob, thresh, out_bits, nullptr, s);
     const bool want_block = mode == 1 || ((mode == 0 || mode == 9) && L.ksteps > 1);
@@ -849,7 +852,7 @@ int launch_conv_mfma_two(const uint32_t *act, int Ca, const uint32_t *low, int C
                          int N, int H, int W, const BlobLayout &L, const void *blob,
                          const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, hipStream_t s)
 {
-    if (low && low_shift == 1 && g_tune_rw != 1 && conv_upcat_supported(Ca, Clow, N, H, W, L, out_bits, out_pool))
+    if (low && low_shift == 1 && t_cfg.tune_rw != 1 && conv_upcat_supported(Ca, Clow, N, H, W, L, out_bits, out_pool))
         return launch_conv_mfma_upcat(act, Ca, low, Clow, N, H, W, L, blob, thresh, out_bits, s);
     if (!low && rows_kernel_waves() && conv_rows_supported(H, W, L, out_bits != nullptr))
         return launch_conv_mfma_rows(act, N, H, W, L, blob, thresh, out_bits, out_pool, rows_kernel_waves(), s);

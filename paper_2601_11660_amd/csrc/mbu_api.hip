@@ -1,4 +1,5 @@
 // C-ABI entry points: argument validation, dispatch, and the network walk.
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -8,8 +9,21 @@
 namespace mbu {
 
 static thread_local char g_err[512] = "";
-static int g_conv_path = MBU_PATH_AUTO;
-static int g_stem_path = MBU_STEM_AUTO;
+// process-wide settings; read only through begin_call()
+static std::atomic<int> g_conv_path{MBU_PATH_AUTO};
+static std::atomic<int> g_stem_path{MBU_STEM_AUTO};
+static std::atomic<int> g_tune_rw{0};
+
+thread_local CallCfg t_cfg = {MBU_PATH_AUTO, MBU_STEM_AUTO, 0, false, ""};
+
+void begin_call(bool dry_run)
+{
+    t_cfg.conv_path = g_conv_path.load(std::memory_order_relaxed);
+    t_cfg.stem_path = g_stem_path.load(std::memory_order_relaxed);
+    t_cfg.tune_rw = g_tune_rw.load(std::memory_order_relaxed);
+    t_cfg.dry_run = dry_run;
+    t_cfg.kernel = "";
+}
 
 int fail(int code, const char *fmt, ...)
 {
@@ -22,6 +36,7 @@ int fail(int code, const char *fmt, ...)
 
 int check_launch(const char *what)
 {
+    if (t_cfg.dry_run) return MBU_OK;
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(MBU_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
     return MBU_OK;
@@ -157,7 +172,7 @@ static int build_plan(const mbu_unet_desc *d, int N, int H, int W, std::vector<S
 // Does step i launch a kernel of its own under the descriptor's fusion setting?
 static bool step_launches(const mbu_unet_desc *d, const std::vector<Step> &steps, size_t i)
 {
-    const bool fuse = d->fuse != 0 && g_conv_path != MBU_PATH_VALU;
+    const bool fuse = d->fuse != 0 && t_cfg.conv_path != MBU_PATH_VALU;
     if (!fuse) return true;
     const Step &st = steps[i];
     if (st.kind == Step::UPCAT || st.kind == Step::CAT) return false;
@@ -174,7 +189,7 @@ static int run_conv(const uint32_t *act, int N, int H, int W, int Cin, const voi
                     hipStream_t s)
 {
     BlobLayout L = blob_layout(Cout, Cin);
-    int path = g_conv_path;
+    int path = t_cfg.conv_path;
     if (path == MBU_PATH_AUTO) path = MBU_PATH_MFMA;
     if (path == MBU_PATH_VALU)
         return launch_conv_valu(act, N, H, W, L, packed_w, thresh, out_bits, out_acc, s);
@@ -184,7 +199,7 @@ static int run_conv(const uint32_t *act, int N, int H, int W, int Cin, const voi
 static int run_stem(const float *img, int N, int Ci, int H, int W, const float *w, int Co,
                     uint32_t *out_bits, float *out_pre, hipStream_t s)
 {
-    const bool valu = g_stem_path == MBU_STEM_VALU || (g_stem_path == MBU_STEM_AUTO && out_pre);
+    const bool valu = t_cfg.stem_path == MBU_STEM_VALU || (t_cfg.stem_path == MBU_STEM_AUTO && out_pre);
     if (valu) return launch_stem_valu(img, N, Ci, H, W, w, Co, out_bits, out_pre, s);
     return launch_stem_mfma(img, N, Ci, H, W, w, Co, out_bits, out_pre, s);
 }
@@ -201,22 +216,21 @@ int mbu_set_conv_path(int path)
 {
     if (path != MBU_PATH_AUTO && path != MBU_PATH_VALU && path != MBU_PATH_MFMA)
         return fail(MBU_ERR_ARG, "mbu_set_conv_path: unknown path %d", path);
-    g_conv_path = path;
+    g_conv_path.store(path, std::memory_order_relaxed);
     return MBU_OK;
 }
 
-int mbu_get_conv_path(void) { return g_conv_path; }
+int mbu_get_conv_path(void) { return g_conv_path.load(std::memory_order_relaxed); }
 
 int mbu_set_stem_path(int path)
 {
     if (path != MBU_STEM_AUTO && path != MBU_STEM_VALU && path != MBU_STEM_MFMA && path != MBU_STEM_MFMA_GATHER)
         return fail(MBU_ERR_ARG, "mbu_set_stem_path: unknown path %d", path);
-    g_stem_path = path;
-    g_stem_gather = path == MBU_STEM_MFMA_GATHER;
+    g_stem_path.store(path, std::memory_order_relaxed);
     return MBU_OK;
 }
 
-int mbu_get_stem_path(void) { return g_stem_path; }
+int mbu_get_stem_path(void) { return g_stem_path.load(std::memory_order_relaxed); }
 
 int mbu_stem_fp32(const float *image_nchw, int N, int Ci, int H, int W, const float *w, int Co,
                   uint32_t *out_bits, float *out_pre, void *stream)
@@ -255,8 +269,7 @@ int mbu_set_conv_tuning(int rows_per_wave, int reserved)
     if ((rows_per_wave != 0 && rows_per_wave != 1 && rows_per_wave != 3 && rows_per_wave != 6 &&
          rows_per_wave != 7 && rows_per_wave != 8 && rows_per_wave != 9) || reserved != 0)
         return fail(MBU_ERR_ARG, "mbu_set_conv_tuning: kernel in {0,1,3,6,7,8,9}, second argument 0");
-    g_tune_rw = rows_per_wave;
-    g_tune_wm = 0;
+    g_tune_rw.store(rows_per_wave, std::memory_order_relaxed);
     return MBU_OK;
 }
 

@@ -11,12 +11,31 @@ namespace mbu {
 int fail(int code, const char *fmt, ...);
 // Turn the HIP error state after a launch into a status.
 int check_launch(const char *what);
-// Launch wrapper: drops any stale error left by earlier, unrelated runtime calls so that
-// check_launch() reports this launch only.
+
+// Settings of one call.  The process-wide settings (mbu_set_conv_path, mbu_set_conv_tuning,
+// mbu_set_stem_path) live in atomics; every entry point copies them ONCE into this
+// thread-local snapshot (begin_call) and everything below the entry point reads the copy, so
+// a setter that runs on another thread cannot change a call that has started.
+struct CallCfg {
+    int conv_path;      // mbu_conv_path
+    int stem_path;      // mbu_stem_path
+    int tune_rw;        // kernel variant of the matrix-path convolution, 0 = automatic
+    bool dry_run;       // true: launchers choose their kernel and record its name, launch nothing
+    const char *kernel; // source name of the last kernel chosen by a launcher on this thread
+};
+extern thread_local CallCfg t_cfg;
+void begin_call(bool dry_run = false);
+
+// Launch wrapper: records which kernel was chosen; unless the call is a dry run it drops any
+// stale error left by earlier, unrelated runtime calls (so that check_launch() reports this
+// launch only) and launches.
 #define MBU_LAUNCH(kernel, grid, block, shmem, stream, ...)                         \
     do {                                                                            \
-        (void)hipGetLastError();                                                    \
-        hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);        \
+        mbu::t_cfg.kernel = #kernel;                                                \
+        if (!mbu::t_cfg.dry_run) {                                                  \
+            (void)hipGetLastError();                                                \
+            hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);    \
+        }                                                                           \
     } while (0)
 
 inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -65,8 +84,6 @@ __host__ __device__ inline int tile_channel_to_row(int c) {
     return 8 * g + 4 * h + j;
 }
 
-// block-shape override of the matrix-path convolution (0 = automatic)
-extern int g_tune_rw, g_tune_wm;
 
 // ---- kernel launchers (arguments already validated) ----
 int launch_pack_act(const void *src, int dtype, long pixels, int C, uint32_t *dst, hipStream_t s);
@@ -120,7 +137,6 @@ int launch_upcat(const uint32_t *skip, int Csw, const uint32_t *low, int Clw,
 // sequential chain for undecided signs; out_pre (NHWC float32) may be NULL
 int launch_stem_valu(const float *img, int N, int Ci, int H, int W, const float *w, int Co,
                      uint32_t *out_bits, float *out_pre, hipStream_t s);
-extern int g_stem_gather;   // set with the stem path: the per-pixel gather kernel everywhere
 int launch_stem_mfma(const float *img, int N, int Ci, int H, int W, const float *w, int Co,
                      uint32_t *out_bits, float *out_pre, hipStream_t s);
 int launch_classifier(const uint32_t *act, int N, int H, int W, int C, const float *w,

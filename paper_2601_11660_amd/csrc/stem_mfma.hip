@@ -878,7 +878,6 @@ static int launch_stem_rows(const float *img, uint32_t bytes, int N, int H, int 
     return check_launch("stem_rows");
 }
 
-int g_stem_gather = 0;   // 1: the per-pixel gather kernel also where the row-walking kernel applies
 
 int launch_stem_mfma(const float *img, int N, int Ci, int H, int W, const float *w, int Co,
                      uint32_t *out_bits, float *out_pre, hipStream_t s)
@@ -886,7 +885,7 @@ int launch_stem_mfma(const float *img, int N, int Ci, int H, int W, const float 
     const double bytes = (double)N * Ci * H * W * 4.0;
     if (bytes >= 2147483648.0) return fail(MBU_ERR_SHAPE, "stem: image larger than 2 GiB");
     // (the row-walking kernel addresses the packed output of one image with 31-bit offsets)
-    if (Ci == 3 && !out_pre && !g_stem_gather && (double)(H + 1) * (W + 32) * (Co / 32) * 4.0 < 2147483648.0)
+    if (Ci == 3 && !out_pre && t_cfg.stem_path != MBU_STEM_MFMA_GATHER && (double)(H + 1) * (W + 32) * (Co / 32) * 4.0 < 2147483648.0)
         return launch_stem_rows(img, (uint32_t)bytes, N, H, W, w, Co, out_bits, s);
     const int tiles_x = ceil_div(W, 32);
     const long ntiles = (long)N * H * tiles_x;

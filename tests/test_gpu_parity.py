@@ -394,12 +394,11 @@ def test_layer_sweep_full_size(C, keep):
         outs[pname] = bits
     assert np.array_equal(outs["valu"], outs["mfma"])
     bits = outs["mfma"]
-    if C <= 128:
-        _, out_ref = O.masked_binary_layer(case.a, case.w, case.theta)
-        assert np.array_equal(bits, bitref.pack_pm1(out_ref))
-    else:
-        for r0, r1 in [(0, 3), (254, 258), (509, 512)]:
-            check_conv_rows(act, C, case.w, case.theta, bits, 0, r0, r1, f"C={C}")
+    # the whole tensor against the oracle for every shape of the sweep
+    _, out_ref = O.masked_binary_layer(case.a, case.w, case.theta)
+    exp = bitref.pack_pm1_fast(out_ref)
+    bad = int((bits != exp).sum())
+    assert bad == 0, f"C={C} keep={keep}: {bad} packed words differ"
 
 
 # --------------------------------------------------------------------------- glue
@@ -428,27 +427,32 @@ def build_unet(case, fuse=True):
 TAP_OF_STEP = {"stem": "stem", "classifier": None}
 
 
-def compare_unet_all_taps(case, N, H, W, fuse=True):
+def compare_unet_all_taps(case, N, H, W, fuse=True, images=None):
+    """Every element of every step's output and of the logits against the oracle's network.
+    images: which images of the batch to compare (default all); the oracle runs on those
+    images only, the GPU on the whole batch (images are independent)."""
     net = build_unet(case, fuse)
     fused_away = fuse and B.get_conv_path() != B.PATH_VALU
     logits = net.forward(dev(case.image))
     torch.cuda.synchronize()
-    ref_logits, taps = O.unet_forward(case.image, case.stem_w, case.convs, case.cls_w,
-                                      case.cls_b, levels=case.levels, up_convs=case.up_convs)
-    taps = dict(taps)
-    rename = {"mida": "mida", "midb": "midb"}
-    for s in range(net.num_steps - 1):
-        name, _, h, w, c = net.step_info(N, H, W, s)
-        ref = taps[rename.get(name, name)]
-        assert ref.shape == (N, h, w, c), name
-        if fused_away and name.startswith("cat"):
-            continue      # folded into the layer that reads it; never written
-        got = host_u32(net.step_output(N, H, W, s))
-        bad = int((got != bitref.pack_pm1(ref)).sum())
-        assert bad == 0, f"step {s} ({name}): {bad} packed words differ"
-    got = host(logits)
-    err = np.abs(got - ref_logits)
-    assert (err <= 1e-4 * np.maximum(1.0, np.abs(ref_logits))).all(), float(err.max())
+    got_logits = host(logits)
+    pack = bitref.pack_pm1_fast if case.base % 32 == 0 else bitref.pack_pm1
+    for n in (range(N) if images is None else images):
+        ref_logits, taps = O.unet_forward(case.image[n:n + 1], case.stem_w, case.convs, case.cls_w,
+                                          case.cls_b, levels=case.levels, up_convs=case.up_convs)
+        taps = dict(taps)
+        for s in range(net.num_steps - 1):
+            name, _, h, w, c = net.step_info(N, H, W, s)
+            ref = taps.pop(name)
+            assert ref.shape == (1, h, w, c), name
+            if fused_away and name.startswith("cat"):
+                continue      # folded into the layer that reads it; never written
+            got = host_u32(net.step_output(N, H, W, s)[n:n + 1])
+            bad = int((got != pack(ref)).sum())
+            assert bad == 0, f"image {n} step {s} ({name}): {bad} packed words differ"
+            del ref
+        err = np.abs(got_logits[n:n + 1] - ref_logits)
+        assert (err <= 1e-4 * np.maximum(1.0, np.abs(ref_logits))).all(), float(err.max())
 
 
 @pytest.mark.parametrize("fuse", [True, False])
@@ -556,27 +560,44 @@ def test_unet_1024x2048_by_induction(fuse):
     check_unet_by_induction(case, 1, 1024, 2048, fuse=fuse)
 
 
-@pytest.mark.parametrize("mean_zero", [0.2, 0.6, 0.8])
-def test_unet_wide_batch_by_induction(mean_zero):
-    """Sparsity-stress shape: channels widened 2x, cost-aware per-layer zero fractions.
-    Batch 2 here keeps host memory and time moderate; the batch-8 run of the same
-    network is exercised by the benchmark's sparsity sweep."""
-    say(f"unet wide mean_zero={mean_zero}")
+def test_unet_1024x2048_every_element():
+    """The shape the benchmark times (batch 1, 3x1024x2048, keep 0.6, glue folded into the
+    layers as in the timed run): every element of every layer's output and every logit against
+    the oracle's whole-network forward pass."""
+    say("unet 1024x2048 every element")
+    case = synth.unet_case(3, 0, 1, 1024, 2048, keep=0.6)
+    compare_unet_all_taps(case, 1, 1024, 2048, True)
+
+
+def wide_case(mean_zero, n, h, w):
     plan = synth.unet_channel_plan(128, 4)
     zf = synth.cost_aware_zero_fractions(plan, 1024, 1024, mean_zero)
-    case = synth.unet_case(4, 0, 2, 256, 256, base=128, keeps=[1.0 - z for z in zf])
-    check_unet_by_induction(case, 2, 256, 256)
+    return synth.unet_case(4, 0, n, h, w, base=128, keeps=[1.0 - z for z in zf])
 
 
-def test_unet_wide_batch8_full_size():
+@pytest.mark.parametrize("mean_zero", [0.2, 0.4, 0.6, 0.8])
+def test_unet_wide_batch_by_induction(mean_zero):
+    """Sparsity-stress network (channels widened 2x, cost-aware per-layer zero fractions) on a
+    small batch: ragged row strips, two images."""
+    say(f"unet wide mean_zero={mean_zero}")
+    check_unet_by_induction(wide_case(mean_zero, 2, 256, 256), 2, 256, 256)
+
+
+@pytest.mark.parametrize("mean_zero", [0.2, 0.4, 0.6, 0.8])
+def test_unet_wide_batch8_full_size(mean_zero):
     """The sparsity-stress workload at its full size: batch 8, 3x1024x1024, channels widened
-    2x (128..2048, decoder inputs 384..3072), cost-aware zero pattern around 60 % zeros.
-    Checked by induction on sampled rows of the first and the last image."""
-    say("unet wide batch 8 at 1024x1024")
-    plan = synth.unet_channel_plan(128, 4)
-    zf = synth.cost_aware_zero_fractions(plan, 1024, 1024, 0.6)
-    case = synth.unet_case(4, 0, 8, 1024, 1024, base=128, keeps=[1.0 - z for z in zf])
-    check_unet_by_induction(case, 8, 1024, 1024, rows_per_layer=2)
+    2x (128..2048, decoder inputs 384..3072), cost-aware zero pattern around each of the four
+    mean zero fractions.  Checked by induction on sampled rows of the first and the last image."""
+    say(f"unet wide batch 8 at 1024x1024 mean_zero={mean_zero}")
+    check_unet_by_induction(wide_case(mean_zero, 8, 1024, 1024), 8, 1024, 1024, rows_per_layer=2)
+
+
+def test_unet_wide_batch8_first_and_last_image_every_element():
+    """The same batch-8 run at mean zero fraction 0.4: every element of every layer and every
+    logit of image 0 against the oracle's forward pass of that image (the batch's images are
+    independent), and of image 7 the same (the last tiles of the persistent kernels' walk)."""
+    say("unet wide batch 8 at 1024x1024 mean_zero=0.4, images 0 and 7 every element")
+    compare_unet_all_taps(wide_case(0.4, 8, 1024, 1024), 8, 1024, 1024, True, images=(0, 7))
 
 
 # ------------------------------------------------------------------------ float32 ends

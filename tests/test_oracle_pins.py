@@ -233,6 +233,18 @@ def test_threshold_tie_goes_to_plus_one():
     assert np.array_equal(out, np.where(acc >= th, 1, -1))
 
 
+def test_fast_packing_helper_equals_the_plain_one():
+    """tests/bitref.pack_pm1_fast (numpy packbits, used on full-size tensors) gives the words of
+    pack_pm1 (explicit sum of bit * 2^i), including on hand-built words."""
+    rng = np.random.default_rng(3)
+    for C in (32, 64, 96, 512):
+        a = synth.pm1_bits(rng, (2, 3, 5, C))
+        assert np.array_equal(bitref.pack_pm1_fast(a), bitref.pack_pm1(a))
+    one = -np.ones((1, 64), np.int8)
+    one[0, 0] = one[0, 31] = one[0, 33] = 1
+    assert bitref.pack_pm1_fast(one).tolist() == [[0x80000001, 0x00000002]]
+
+
 # ------------------------------------------------------------------------ glue
 def test_pool_upsample_concat_match_torch():
     rng = np.random.default_rng(5)
@@ -545,3 +557,107 @@ def test_bit_valued_activations_with_half_valued_padding_reproduce_the_layer():
     assert np.array_equal(2.0 * got - wsum, acc.astype(np.float64))
     start = -(theta.astype(np.float64) + wsum) / 2.0
     assert np.array_equal(np.where(got + start >= 0, 1, -1), out)
+
+
+# ------------------------------------------------- frame sizes that are not multiples of 2^levels
+def test_floor_pooling_and_zero_padding_match_torch():
+    """Odd sizes (Appendix A.3 lists 959-pixel-wide frames): pooling drops the last row / column
+    like the library routine's default (floor) mode, and the decoder's padding is the library's
+    constant padding with the difference split floor(d/2) before, the rest after."""
+    rng = np.random.default_rng(31)
+    for H, W in ((7, 9), (6, 9), (7, 8), (2, 5), (3, 3)):
+        a = synth.pm1_bits(rng, (2, H, W, 5))
+        t = torch.from_numpy(a).double().permute(0, 3, 1, 2)
+        ref = F.max_pool2d(t, 2).permute(0, 2, 3, 1).numpy().astype(np.int8)
+        got = O.maxpool2x2(a)
+        assert got.shape == (2, H // 2, W // 2, 5) and np.array_equal(got, ref)
+    a = synth.pm1_bits(rng, (2, 4, 6, 3))
+    t = torch.from_numpy(a).double().permute(0, 3, 1, 2)
+    for Ho, Wo in ((4, 6), (5, 6), (4, 7), (5, 7), (7, 9)):
+        dy, dx = Ho - 4, Wo - 6
+        ref = F.pad(t, [dx // 2, dx - dx // 2, dy // 2, dy - dy // 2]).permute(0, 2, 3, 1).numpy()
+        assert np.array_equal(O.zero_pad_to(a, Ho, Wo), ref.astype(np.int8))
+    # one missing row / column: the padding is the last row / column, all zeros
+    p = O.zero_pad_to(a, 5, 7)
+    assert np.array_equal(p[:, :4, :6], a) and not p[:, 4].any() and not p[:, :, 6].any()
+
+
+def test_layer_on_zero_padded_activations():
+    """A padded element (value 0) adds nothing: the layer on a tensor with zero-valued elements
+    equals the library convolution in float64 and the scatter-form brute force, and equals the
+    layer with the weights that meet those elements masked."""
+    rng = np.random.default_rng(32)
+    a = synth.pm1_bits(rng, (1, 4, 5, 6))
+    a[:, :, 4, 3:] = 0          # last column of the last three channels was padded
+    a[:, 3, :, 3:] = 0
+    w = synth.ternary_weights(98, 0, 0, 4, 6, 0.7)
+    acc = O.conv3x3(a, w)
+    ref = F.conv2d(torch.from_numpy(a).double().permute(0, 3, 1, 2),
+                   torch.from_numpy(w).double().permute(0, 3, 1, 2), padding=1).permute(0, 2, 3, 1).numpy()
+    assert np.array_equal(acc.astype(np.float64), ref)
+    assert np.array_equal(acc, scatter_conv(a, w))
+    # same sums when the zero elements are replaced by +1 and excluded through the image border
+    # instead: rows 0..2, columns 0..3 of the padded channels as an image of their own
+    lo = O.conv3x3(a[:, :3, :4, 3:], w[..., 3:])
+    hi = O.conv3x3(a[..., :3], w[..., :3])
+    assert np.array_equal(acc[:, :3, :4], hi[:, :3, :4] + lo)
+
+
+def torch_unet_any_size(case):
+    """The network recomposed from PyTorch-CPU float64 library ops for any frame size: floor
+    pooling, decoder feature padded to the skip feature's size before the concatenation."""
+    def t(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).double()
+    x = F.conv2d(t(case.image), t(case.stem_w).permute(0, 3, 1, 2), padding=1)
+    x = torch.where(x >= 0, 1.0, -1.0).double()
+    it = iter(case.convs)
+
+    def dconv(x):
+        for _ in range(2):
+            w, th = next(it)
+            acc = F.conv2d(x, t(w).permute(0, 3, 1, 2), padding=1)
+            x = torch.where(acc >= t(th)[None, :, None, None], 1.0, -1.0).double()
+        return x
+    skips = []
+    for _ in range(case.levels):
+        x = dconv(x)
+        skips.append(x)
+        x = F.max_pool2d(x, 2)
+    x = dconv(x)
+    for j, l in enumerate(range(case.levels, 0, -1)):
+        if case.up_convs is None:
+            x = F.interpolate(x, scale_factor=2, mode="nearest")
+        else:
+            wu, tu = case.up_convs[j]
+            acc = F.conv_transpose2d(x, t(wu).permute(3, 0, 1, 2), stride=2)
+            x = torch.where(acc >= t(tu)[None, :, None, None], 1.0, -1.0).double()
+        sk = skips[l - 1]
+        dy, dx = sk.shape[2] - x.shape[2], sk.shape[3] - x.shape[3]
+        x = F.pad(x, [dx // 2, dx - dx // 2, dy // 2, dy - dy // 2])
+        x = torch.cat([sk, x], 1)
+        x = dconv(x)
+    logits = F.conv2d(x, t(case.cls_w)[:, :, None, None], t(case.cls_b))
+    return logits.numpy(), x.permute(0, 2, 3, 1).numpy().astype(np.int8)
+
+
+@pytest.mark.parametrize("transposed", [False, True])
+@pytest.mark.parametrize("H,W,levels", [(21, 27, 2), (23, 38, 3), (16, 31, 2)])
+def test_unet_on_odd_frame_sizes_matches_torch(H, W, levels, transposed):
+    for seed in range(4):
+        case = synth.unet_case(13, seed, 1, H, W, base=32, levels=levels, n_classes=2,
+                               transposed=transposed)
+        pre, _ = O.stem(case.image, case.stem_w)
+        if np.abs(pre).min() > 2e-5:      # float64 and float32 first layers agree on every sign
+            break
+    else:
+        raise AssertionError("no seed without a near-zero first-layer sum")
+    logits, taps = O.unet_forward(case.image, case.stem_w, case.convs, case.cls_w, case.cls_b,
+                                  levels=levels, up_convs=case.up_convs)
+    ref_logits, ref_last = torch_unet_any_size(case)
+    assert np.array_equal(taps[-1][1], ref_last)
+    assert (np.abs(logits - ref_logits) <= 1e-4 * np.maximum(1.0, np.abs(ref_logits))).all()
+    shapes = {n: v.shape[1:3] for n, v in taps}
+    assert shapes[f"pool{levels}"] == (H >> levels, W >> levels)
+    assert shapes["up1"] == (2 * (H // 2), 2 * (W // 2)) and shapes["cat1"] == (H, W)
+    if W % 2:
+        assert not taps[[n for n, _ in taps].index("cat1")][1][0, :, W - 1, 32:].any()
