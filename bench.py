@@ -5,11 +5,12 @@ A step is one whole forward pass (stem, 18 masked-binary 3x3 layers, pooling,
 up-sampling + concatenation, classifier) at 1x3x1024x2048 on seeded synthetic data
 already resident in device memory.  Prints ONE JSON line:
   value      frames/s of the whole forward pass
-  roofline   the masked-binary convolution kernel (dominant), timed with HIP events
-             recorded on the launch stream inside the timed region
+  roofline   the convolution kernel with the largest share of the pass (matrix-core work it
+             executes / its event-timed duration / FP4 peak); roofline_all_conv = all 18
+             convolution launches; HIP events recorded on the launch stream
   cpu_baseline  the CPU oracle timed on the host cores on a bounded sample
   conv_sweep effective GOPS of single layers (512x512, C in 64..512, three mask densities)
-  per_layer  time and effective TOPS of every step of the forward pass
+  per_layer  kernel, time, bound and roofline fraction of every step of the forward pass
 
 Effective operations count every tap, masked and padded ones included, multiply and
 add separately: 2*N*H*W*9*Cin*Cout per layer.
@@ -29,6 +30,8 @@ METRIC = "masked-binary conv effective GOPS (+ % roofline); U-Net frames/s @1024
 # MI355X dense peaks: FP4 matrix cores and the two-instruction bit path on the vector ALU
 PEAK_FP4_TFLOPS = 10100.0
 PEAK_VALU_BIT_TOPS = 1258.0   # 256 CU * 4 SIMD * 16 lanes * 2.4 GHz * 32 taps / 2 instr * 2 ops
+PEAK_HBM_GBS = 8000.0
+PEAK_FP32_VALU_TFLOPS = 157.3
 
 
 def parse():
@@ -41,9 +44,13 @@ def parse():
     ap.add_argument("--width", type=int, default=2048)
     ap.add_argument("--no-sweep", action="store_true", help="skip the single-layer sweep")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--sparsity-sweep", action="store_true",
-                    help="run the batch-8 wide network for all four mean zero fractions "
-                         "(default: 0.6 only)")
+    ap.add_argument("--settle-ms", type=float, default=300.0,
+                    help="untimed forward passes for about this many milliseconds before the "
+                         "warm-up passes, so that the shader clock has reached its sustained "
+                         "value when the timed region starts (0 = none)")
+    ap.add_argument("--ramp", type=int, default=0, metavar="PASSES",
+                    help="instead of the benchmark: idle for 3 s, then time each of the first "
+                         "PASSES forward passes with an event pair of its own; prints a table")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (3x) so that a counter pass of "
                          "this command can scale FETCH_SIZE / WRITE_SIZE by a known transfer")
@@ -55,17 +62,35 @@ def parse():
     return ap.parse_args()
 
 
-def traffic_from_profile():
-    """HBM bytes per convolution launch measured by the two counter passes recorded in
-    profiles/conv_mfma_unet_1024x2048_hbm_traffic.md (None if that file is absent)."""
-    path = os.path.join(ROOT, "profiles", "conv_mfma_unet_1024x2048_hbm_traffic.md")
+def csrc_digest():
+    """sha256 over the kernel sources (names and contents): the build a counter pass measured."""
+    import hashlib
+    h = hashlib.sha256()
+    d = os.path.join(ROOT, "paper_2601_11660_amd", "csrc")
+    for name in sorted(os.listdir(d)):
+        h.update(name.encode())
+        with open(os.path.join(d, name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def traffic_from_profile(kernel):
+    """HBM bytes per launch of `kernel` from the two counter passes summarised in
+    profiles/unet_1024x2048_hbm_traffic.md - only if that summary was made from the kernel
+    sources of this tree (its csrc_sha256 line), else None: a stale figure is no figure."""
+    path = os.path.join(ROOT, "profiles", "unet_1024x2048_hbm_traffic.md")
+    val, digest = None, None
     try:
         for line in open(path):
-            if line.startswith("conv_traffic_bytes_per_launch:"):
-                return float(line.split(":")[1])
+            if line.startswith("csrc_sha256:"):
+                digest = line.split(":")[1].strip()
+            if line.startswith(f"traffic_bytes_per_launch[{kernel}]:"):
+                val = float(line.split(":")[1])
     except OSError:
-        pass
-    return None
+        return None, "no counter summary under profiles/"
+    if digest != csrc_digest():
+        return None, f"counter summary was measured on other kernel sources ({digest})"
+    return val, f"measured on kernel sources {digest}"
 
 
 def single_layer(args, B, torch, synth):
@@ -121,7 +146,8 @@ def conv_sweep(B, torch, synth):
 
 def wide_batch(B, torch, synth, mean_zeros):
     """Sparsity-stress workload: batch 8, 3x1024x1024, channels widened 2x, cost-aware per-layer
-    zero fractions around each mean; images/s of the whole forward pass."""
+    zero fractions around each of the four mean zero fractions; images/s of the whole forward
+    pass and the matrix-core fraction of its convolution launches."""
     rows = []
     plan = synth.unet_channel_plan(128, 4)
     n, h, w = 8, 1024, 1024
@@ -142,10 +168,29 @@ def wide_batch(B, torch, synth, mean_zeros):
             net.forward(image, logits)
         e1.record()
         ms = e0.elapsed_ms(e1) / iters
+        # per-kernel events on 5 more passes: time and issued work of the convolution launches
+        sets = [net.new_event_set() for _ in range(5)]
+        for es in sets:
+            net.use_event_set(es)
+            net.forward(image, logits)
+        torch.cuda.synchronize()
+        t = np.mean([net.step_times_ms(n, h, w, es) for es in sets], axis=0)
+        net.use_event_set(None)
+        conv_ms = issued = 0.0
+        ci = 0
+        for s_ in range(net.num_steps):
+            name, _, hh, ww, c = net.step_info(n, h, w, s_)
+            if name[:3] in ("enc", "mid", "dec"):
+                _, cin, cout, _ = plan[ci]
+                ci += 1
+                conv_ms += t[s_]
+                issued += issued_ops(net.step_kernel(n, h, w, s_), n, hh, ww, cin, cout)
         ops = 2.0 * synth.unet_conv_macs(plan, n, h, w)
         rows.append({"mean_zero_fraction": z, "ms_per_batch": round(ms, 3),
                      "images_per_s": round(n * 1e3 / ms, 1),
-                     "conv_eff_tops_incl_other_layers": round(ops / ms / 1e9, 1)})
+                     "conv_ms_raw_events": round(float(conv_ms), 3),
+                     "conv_effective_tops": round(ops / conv_ms / 1e9, 1),
+                     "conv_frac_issued_raw_events": round(issued / conv_ms / 1e9 / PEAK_FP4_TFLOPS, 4)})
         del net, image, logits, case
         torch.cuda.empty_cache()
     return rows
@@ -191,13 +236,25 @@ def transposed_decoder(B, torch, synth, steps):
             "conv3x3_macs_per_frame": conv_macs, "transposed_layers": ups}
 
 
+def issued_ops(kernel, n, h, w, cin, cout):
+    """Operations the matrix cores execute for one 3x3 layer launch.  The low-resolution decoder
+    kernel contracts the up-sampled channels (two thirds of its input) with 4 summed taps
+    instead of 9; every other kernel issues the layer's nominal 2 * 9 * Cin per output."""
+    if kernel == "conv_mfma_upcat_kernel":
+        ca = cin // 3                      # [skip | 2x up-sampled low], low has 2 * skip channels
+        return 2.0 * n * h * w * cout * (9.0 * ca + 4.0 * (cin - ca))
+    return 2.0 * n * h * w * cout * 9.0 * cin
+
+
 def paper_shapes(B, torch, synth, steps):
-    """The paper's own inference shapes (Appendix A.3: Carvana 959x640 padded to 960x640, ISIC
-    640x480, Nuclei 512x512; binary segmentation, batched) on the network with the paper's
-    transposed decoder, synthetic inputs: images/s."""
+    """The paper's own inference shapes (Appendix A.3: Carvana 959 wide x 640 high, ISIC 640x480,
+    Nuclei 512x512; binary segmentation; batch sizes of Appendix A.2's MBU-Net columns for the
+    A100: 64 / 128 / 128, and batch 32) on the network with the paper's transposed decoder,
+    synthetic inputs: images/s."""
     rows = []
-    n = 8
-    for name, h, w in (("carvana-like", 640, 960), ("isic-like", 480, 640), ("nuclei-like", 512, 512)):
+    for name, h, w, n in (("carvana-like", 640, 959, 32), ("carvana-like", 640, 959, 64),
+                          ("isic-like", 480, 640, 32), ("isic-like", 480, 640, 128),
+                          ("nuclei-like", 512, 512, 32), ("nuclei-like", 512, 512, 128)):
         case = synth.unet_case(7, 0, n, h, w, keep=0.6, transposed=True, n_classes=2)
 
         def dev(a):
@@ -241,6 +298,26 @@ def cpu_baseline(synth):
             "effective_gops": round(2.0 * macs / dt / 1e9, 1)}
 
 
+def ramp_table(args, net, image, logits, B, torch):
+    """Pass time against pass index after an idle period: every pass gets an event pair of its
+    own (so each reading includes about one event record's cost)."""
+    n = args.ramp
+    for _ in range(3):
+        net.forward(image, logits)
+    torch.cuda.synchronize()
+    time.sleep(3.0)
+    ev = [B.Event() for _ in range(n + 1)]
+    ev[0].record()
+    for k in range(n):
+        net.forward(image, logits)
+        ev[k + 1].record()
+    torch.cuda.synchronize()
+    ms = [ev[k].elapsed_ms(ev[k + 1]) for k in range(n)]
+    print(json.dumps({"ramp_ms_per_pass": [round(v, 4) for v in ms],
+                      "mean_first_20": round(float(np.mean(ms[:20])), 4),
+                      "mean_last_20": round(float(np.mean(ms[-20:])), 4)}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -270,6 +347,21 @@ def main():
                  dev(case.cls_b), levels=4)
     image = dev(case.image)
     logits = torch.empty((N, case.n_classes, H, W), dtype=torch.float32, device="cuda")
+    if args.ramp:
+        ramp_table(args, net, image, logits, B, torch)
+        return
+    # Untimed passes until the device has been busy for about settle_ms: after an idle period
+    # the first passes run 10-15 % slower (the shader clock has not reached its sustained
+    # value); the metric is sustained throughput, so the timed region starts after that.
+    settle_passes = 0
+    if args.settle_ms > 0:
+        torch.cuda.synchronize()
+        t_s = time.perf_counter()
+        while (time.perf_counter() - t_s) * 1e3 < args.settle_ms:
+            for _ in range(20):
+                net.forward(image, logits)
+            torch.cuda.synchronize()
+            settle_passes += 20
     for _ in range(args.warmup):
         net.forward(image, logits)
     torch.cuda.synchronize()
@@ -289,10 +381,10 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / K
     ms_per_step_events = e_begin.elapsed_ms(e_end) / K
 
-    # ---- min(K, 200) more passes with one HIP event per launched kernel (recorded by the
-    # library on the launch stream): per-layer breakdown and the dominant kernel's duration.
-    # Kept out of the region above because 28 event records per pass cost about a tenth of it.
-    KP = min(K, 200)      # passes with per-kernel events (directly after the timed region: same state)
+    # ---- KP more passes with one HIP event per launched kernel (recorded by the library on
+    # the launch stream): per-layer breakdown and the dominant kernel's duration.  Kept out of
+    # the region above because 28 event records per pass cost about a tenth of it.
+    KP = max(20, min(K, 200))      # directly after the timed region: same device state
     ev_sets = [net.new_event_set() for _ in range(KP)]
     torch.cuda.synchronize()
     t2 = time.perf_counter()
@@ -303,6 +395,7 @@ def main():
     ms_per_step_profiled = (time.perf_counter() - t2) * 1e3 / KP
 
     infos = [net.step_info(N, H, W, s) for s in range(net.num_steps)]
+    kernels = [net.step_kernel(N, H, W, s) for s in range(net.num_steps)]
     step_ms = np.zeros(net.num_steps)
     for k in range(KP):
         step_ms += np.array(net.step_times_ms(N, H, W, ev_sets[k]))
@@ -311,67 +404,104 @@ def main():
     # An event between two kernels measures from the end of the kernel before to the end of
     # its own, so every record adds its cost to the kernel it closes.  The kernels run back to
     # back in the timed region (rocprofv3: sum of kernel durations = pass time), so that cost is
-    # what the instrumented pass took longer, spread over its event-closed launches.
+    # what the instrumented pass took longer, spread over its event-closed launches.  Both
+    # readings are reported: "raw" is the event interval as measured, "adj" has the cost taken off.
     step_ms_raw = step_ms.copy()
     launched = int((step_ms > 0).sum())
     event_cost = max(0.0, ms_per_step_profiled - ms_per_step) / max(1, launched)
-    step_ms = np.where(step_ms > 0, np.maximum(step_ms - event_cost, 0.0), 0.0)
+    step_ms = np.where(step_ms > 0, np.maximum(step_ms - event_cost, 1e-6), 0.0)
 
-    per_layer, conv_ms, conv_ops, conv_bytes, conv_issued = [], 0.0, 0.0, 0.0, 0.0
-    path_is_mfma = B.get_conv_path() != B.PATH_VALU
+    path = B.get_conv_path()
+    mfma = path != B.PATH_VALU
+    conv_peak = PEAK_FP4_TFLOPS if mfma else PEAK_VALU_BIT_TOPS
+    per_layer = []
+    conv = []          # (kernel, ms_adj, ms_raw, nominal ops, issued ops, algorithmic bytes)
     ci = 0
-    for (name, _, h, w, c), ms in zip(infos, step_ms):
-        row = {"step": name, "ms": round(float(ms), 4)}
-        is_conv = name[:3] in ("enc", "mid", "dec")
-        if is_conv:
+    for (name, _, h, w, c), kern, ms, raw in zip(infos, kernels, step_ms, step_ms_raw):
+        row = {"step": name, "kernel": kern, "ms": round(float(ms), 4), "ms_raw_event": round(float(raw), 4)}
+        if name[:3] in ("enc", "mid", "dec"):
             _, cin, cout, _ = case.plan[ci]
             ci += 1
             ops = 2.0 * synth.conv_macs(N, h, w, cin, cout)
-            row.update({"cin": cin, "cout": cout, "hw": [h, w],
-                        "eff_tops": round(ops / ms / 1e9, 1)})
-            conv_ms += ms
-            conv_ops += ops
-            # What the matrix cores execute: a decoder layer over [skip | up-sampled low]
-            # contracts the low channels at low resolution, 4 summed taps instead of 9.
-            if path_is_mfma and name.startswith("dec") and name.endswith("a") and cin == 3 * cout \
-                    and cout % 64 == 0:
-                issued = 2.0 * N * h * w * cout * (9.0 * cout + 4.0 * (cin - cout))
-                row["issued_fraction"] = round(issued / ops, 4)
-            else:
-                issued = ops
-            conv_issued += issued
+            iss = issued_ops(kern, N, h, w, cin, cout) if mfma else ops
             # input bits + output bits + the 4-bit weight codes, each once
-            conv_bytes += N * h * w * (cin + cout) / 8.0 + 9.0 * cin * cout / 2.0
+            nbytes = N * h * w * (cin + cout) / 8.0 + 9.0 * cin * cout / 2.0
+            conv.append((kern, float(ms), float(raw), ops, iss, nbytes))
+            row.update({"cin": cin, "cout": cout, "hw": [h, w],
+                        "bound": "mfma" if mfma else "alu",
+                        "frac": round(iss / ms / 1e9 / conv_peak, 4),
+                        "frac_raw_event": round(iss / raw / 1e9 / conv_peak, 4),
+                        "issued_tops": round(iss / ms / 1e9, 1),
+                        "effective_tops": round(ops / ms / 1e9, 1),
+                        "issued_over_nominal": round(iss / ops, 4)})
+        elif name == "stem" and ms > 0:
+            flops = 2.0 * N * h * w * c * 9 * 3
+            nbytes = N * h * w * (3 * 4 + c / 8.0)
+            row.update({"bound": "alu", "peak_tflops": PEAK_FP32_VALU_TFLOPS,
+                        "frac": round(flops / ms / 1e9 / PEAK_FP32_VALU_TFLOPS, 4),
+                        "frac_raw_event": round(flops / raw / 1e9 / PEAK_FP32_VALU_TFLOPS, 4),
+                        "hbm_gbs": round(nbytes / ms / 1e6, 1),
+                        "hbm_frac": round(nbytes / ms / 1e6 / PEAK_HBM_GBS, 4),
+                        "note": "algorithmic work: the 27-term float32 sum of every output "
+                                "(2*27 flops) against the fp32 vector peak; the kernel decides most "
+                                "signs from a split-fp16 estimate on the matrix cores instead"})
+        elif ms > 0:
+            # bandwidth-bound steps: classifier (bits in, float32 logits out), pooling, concatenation
+            if name == "classifier":
+                nbytes = N * h * w * (case.base / 8.0 + 4.0 * c)
+            elif name.startswith("pool"):
+                nbytes = N * h * w * (c / 8.0) * 5.0
+            else:
+                nbytes = N * h * w * (c / 8.0) * 2.0
+            row.update({"bound": "hbm", "hbm_gbs": round(nbytes / ms / 1e6, 1),
+                        "frac": round(nbytes / ms / 1e6 / PEAK_HBM_GBS, 4),
+                        "frac_raw_event": round(nbytes / raw / 1e6 / PEAK_HBM_GBS, 4)})
         per_layer.append(row)
-    n_conv = ci
-    path = B.get_conv_path()
-    mfma = path != B.PATH_VALU
-    achieved = conv_ops / conv_ms / 1e9   # T op/s over all conv launches of a step
-    roof = {"bound": "mfma" if mfma else "alu",
-            "kernel": ("conv_mfma_block / rows / rows2k / upcat kernels (the 18 conv launches of a pass)"
-                       if mfma else "conv_valu_kernel"),
-            "achieved": round(achieved, 1),
-            "peak": PEAK_FP4_TFLOPS if mfma else PEAK_VALU_BIT_TOPS,
-            "unit": "TFLOP/s" if mfma else "TOP/s",
-            "frac": round(achieved / (PEAK_FP4_TFLOPS if mfma else PEAK_VALU_BIT_TOPS), 4),
-            "traffic": traffic_from_profile() if mfma else None,
-            "algorithmic_bytes_per_launch": round(conv_bytes / n_conv),
-            "launches_per_step": n_conv,
-            "avg_launch_ms": round(conv_ms / n_conv, 4),
-            "algorithmic_ops_per_step": conv_ops,
-            "issued_ops_per_step": conv_issued,
-            "achieved_issued": round(conv_issued / conv_ms / 1e9, 1),
-            "frac_issued": round(conv_issued / conv_ms / 1e9 / (PEAK_FP4_TFLOPS if mfma else PEAK_VALU_BIT_TOPS), 4),
-            "note": "achieved = algorithmic ops (2 per tap of the layer as defined, masked and padded "
-                    "taps counted) / sum of the event-timed durations of the conv launches, from a "
-                    "second pass of min(K, 200) steps with one event per kernel, less the cost of an event record (how much longer that pass takes per launch: event_cost_ms_per_launch); achieved_issued "
-                    "counts what the matrix cores execute: the four decoder layers over "
-                    "[skip | up-sampled low] contract the up-sampled channels at low resolution "
-                    "(4 summed taps instead of 9, same result)"}
+
+    def roof(rows, label):
+        ms = sum(r[1] for r in rows)
+        raw = sum(r[2] for r in rows)
+        ops = sum(r[3] for r in rows)
+        iss = sum(r[4] for r in rows)
+        nb = sum(r[5] for r in rows)
+        n = len(rows)
+        return {"bound": "mfma" if mfma else "alu", "kernel": label,
+                "achieved": round(iss / ms / 1e9, 1), "peak": conv_peak,
+                "unit": "TFLOP/s" if mfma else "TOP/s",
+                "frac": round(iss / ms / 1e9 / conv_peak, 4),
+                "frac_raw_events": round(iss / raw / 1e9 / conv_peak, 4),
+                "effective": round(ops / ms / 1e9, 1),
+                "frac_effective": round(ops / ms / 1e9 / conv_peak, 4),
+                "launches_per_step": n, "avg_launch_ms": round(ms / n, 5),
+                "avg_launch_ms_raw_events": round(raw / n, 5),
+                "issued_ops_per_launch": iss / n, "algorithmic_ops_per_launch": ops / n,
+                "algorithmic_bytes_per_launch": round(nb / n),
+                "share_of_step_time": round(ms / float(step_ms.sum()), 4)}
+
+    by_kernel = {}
+    for r in conv:
+        by_kernel.setdefault(r[0], []).append(r)
+    dominant = max(by_kernel, key=lambda k: sum(r[1] for r in by_kernel[k]))
+    roofline = roof(by_kernel[dominant], dominant)
+    traffic, traffic_note = traffic_from_profile(dominant) if mfma else (None, "not measured")
+    roofline["traffic"] = traffic
+    roofline["traffic_note"] = traffic_note
+    roofline["note"] = (
+        "the convolution kernel with the largest share of the pass.  achieved / frac = operations the "
+        "matrix cores EXECUTE per launch / the kernel's event-timed average duration (event record "
+        "cost taken off; frac_raw_events leaves it in); effective / frac_effective count the "
+        "layer's nominal work, 2 ops per tap of the 3x3 layer as defined (masked and padded taps "
+        "included; Sec. 3.1.2 counts multiplies and adds), which is more than issued where the "
+        "up-sampled channels are contracted at low resolution with summed taps (same result)")
+    all_conv = roof(conv, "all convolution launches of a pass: " + ", ".join(
+        f"{k} x{len(v)}" for k, v in sorted(by_kernel.items())))
+    conv_ms = sum(r[1] for r in conv)
+    conv_ops = sum(r[3] for r in conv)
 
     out = {
         "metric": METRIC, "value": round(1e3 / ms_per_step, 2), "unit": "frames/s",
         "n_gpus": 1, "steps": K, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "clock_settle_passes_before_warmup": settle_passes,
         "ms_per_step_stream_events": round(ms_per_step_events, 4),
         "ms_per_step_with_per_kernel_events": round(ms_per_step_profiled, 4),
         "event_cost_ms_per_launch": round(event_cost, 5),
@@ -385,7 +515,8 @@ def main():
                    "conv_path": {B.PATH_AUTO: "auto", B.PATH_VALU: "valu", B.PATH_MFMA: "mfma"}[path]},
         "conv_effective_gops": round(conv_ops / conv_ms / 1e6, 1),
         "conv_ms_per_step": round(conv_ms, 4),
-        "roofline": roof,
+        "roofline": roofline,
+        "roofline_all_conv": all_conv,
         "per_layer": per_layer,
     }
     del net, image, logits
@@ -400,9 +531,8 @@ def main():
     if not args.no_sweep:
         out["conv_sweep"] = conv_sweep(B, torch, synth)
         out["transposed_decoder"] = transposed_decoder(B, torch, synth, min(K, 300))
-        out["paper_shapes"] = paper_shapes(B, torch, synth, min(K, 50))
-        out["wide_batch8"] = wide_batch(B, torch, synth,
-                                        (0.2, 0.4, 0.6, 0.8) if args.sparsity_sweep else (0.6,))
+        out["paper_shapes"] = paper_shapes(B, torch, synth, min(K, 30))
+        out["wide_batch8"] = wide_batch(B, torch, synth, (0.2, 0.4, 0.6, 0.8))
     out["cpu_baseline"] = None if args.no_cpu else cpu_baseline(synth)
     out["paper_context"] = ("paper reports 2.04x speed-up and 3.54x lower energy vs FP16 U-Net on "
                             "A100/H100/Jetson Orin Nano/RTX 2080 Ti (1-bit tensor cores); no "

@@ -60,7 +60,14 @@ typedef enum mbu_conv_path {
  * owned by the library, valid until the next failing call on the thread. */
 const char *mbu_last_error(void);
 
-/* Select the convolution implementation process-wide.  MBU_ERR_ARG on a bad value. */
+/* Select the convolution implementation process-wide.  MBU_ERR_ARG on a bad value.
+ * Thread safety of this and the other setters (mbu_set_conv_tuning, mbu_set_stem_path): the
+ * settings are process-wide atomics; every other entry point reads them ONCE when it is
+ * entered, so a call that has started is not affected by a setter that runs meanwhile, and
+ * all other entry points may be called from several threads at once (on different streams).
+ * A sequence of calls that must see the same setting - a forward pass and the
+ * mbu_unet_step_launches / mbu_unet_step_kernel queries that describe it - must not be
+ * interleaved with a setter on another thread; the library does not serialise that. */
 int mbu_set_conv_path(int path);
 int mbu_get_conv_path(void);
 
@@ -124,14 +131,16 @@ int mbu_conv3x3_masked_binary(const uint32_t *act, int N, int H, int W, int Cin,
  * decoder layer (Sec. 2.1) are read in place instead of being materialised, and the 2x2
  * pooling that follows an encoder layer (Sec. 3.2.2) is written as a second output.
  *   act       packed [N][H][W][Ca/32]; Ca % 32 == 0 when `low` is given
- *   low       packed [N][H/2][W/2][ceil(Clow/32)] or NULL (then Clow must be 0); the layer's
- *             input is the channel concatenation [act | low up-sampled 2x nearest], i.e.
- *             input pixel (y, x) takes its last Clow channels from low[y/2][x/2]
+ *   low       packed [N][H/2][W/2][ceil(Clow/32)] (sizes rounded down) or NULL (then Clow must
+ *             be 0); the layer's input is the channel concatenation [act | low up-sampled 2x
+ *             nearest], i.e. input pixel (y, x) takes its last Clow channels from
+ *             low[y/2][x/2]; for odd H / W the last row / column has no such pixel and its
+ *             last Clow channels are the value 0 (they add nothing)
  *   packed_w  blob packed for (Cout, Cin = Ca + Clow)
  *   out_bits  packed [N][H][W][Cout/32], or NULL
  *   out_pool  packed [N][H/2][W/2][Cout/32] = bitwise OR of each 2x2 window of the layer's
  *             output, or NULL
- * H and W must be even when `low` or `out_pool` is given; at least one output non-NULL.
+ * H and W must be even when `out_pool` is given; at least one output non-NULL.
  * Errors as for mbu_conv3x3_masked_binary. */
 int mbu_conv3x3_masked_binary_fused(const uint32_t *act, int Ca, const uint32_t *low, int Clow,
                                     int N, int H, int W, const void *packed_w, int Cout,
@@ -146,6 +155,20 @@ int mbu_conv3x3_masked_binary_concat(const uint32_t *a, int Ca, const uint32_t *
                                      int H, int W, const void *packed_w, int Cout,
                                      const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool,
                                      void *stream);
+
+/* General form of the two calls above, for decoder levels of frames whose size is not a multiple
+ * of 2^levels (Appendix A.3 lists 959 x 640 frames; Sec. 2.1 for the decoder): pooling drops an
+ * odd last row / column on the way down, so the up-sampled feature is smaller than the skip
+ * feature and is zero-padded to its size before the concatenation.  The layer's input is
+ * [a | b'] where b' is b (Hb x Wb pixels, Cb channels) - read 2x nearest-neighbour up-sampled when
+ * upsample = 1 - placed at the top left of the H x W frame; where b' has no pixel its channels
+ * are the value 0 and add nothing to the sums (like taps outside the image).  Matrix path only.
+ *   a [N][H][W][Ca/32], Ca % 32 == 0;  b [N][Hb][Wb][ceil(Cb/32)], (Hb, Wb) << upsample <= (H, W)
+ *   packed_w packed for (Cout, Ca + Cb); outputs as for mbu_conv3x3_masked_binary_fused. */
+int mbu_conv3x3_masked_binary_two_inputs(const uint32_t *a, int Ca, const uint32_t *b, int Cb, int Hb,
+                                         int Wb, int upsample, int N, int H, int W, const void *packed_w,
+                                         int Cout, const int32_t *thresh, uint32_t *out_bits,
+                                         uint32_t *out_pool, void *stream);
 
 /* Masked-binary transposed convolution, kernel 2x2, stride 2, with the threshold / sign /
  * bit-pack epilogue: the decoder's up-sampling layer (Sec. 2.1; Sec. 3.2.2 notes it is
@@ -165,7 +188,8 @@ int mbu_tconv2x2_masked_binary(const uint32_t *act, int N, int H, int W, int Cin
                                uint32_t *out_bits, int32_t *out_acc, void *stream);
 
 /* 2x2 stride-2 max pooling on +-1 values = bitwise OR of the four packed words
- * (Sec. 3.2.2 lists pooling as trivial).  H and W must be even.
+ * (Sec. 3.2.2 lists pooling as trivial).  H, W >= 2; H/2 and W/2 round down: an odd last
+ * row / column belongs to no window and is dropped.
  *   in [N][H][W][Cw] -> out [N][H/2][W/2][Cw], Cw = ceil(C/32). */
 int mbu_maxpool2x2_bits(const uint32_t *in, int N, int H, int W, int C,
                         uint32_t *out, void *stream);
@@ -303,6 +327,13 @@ int mbu_unet_step_info(const mbu_unet_desc *d, int N, int H, int W, int step,
  * step_events is not recorded), negative status on error. */
 int mbu_unet_step_launches(const mbu_unet_desc *d, int N, int H, int W, int step);
 
+/* Name of the kernel that step `step` launches for this shape under the current settings
+ * (the kernel's name in the library's sources, as a profiler shows it without template
+ * arguments; "" for a step that launches none).  Nothing is launched and no device pointer of
+ * the descriptor is read.  *kernel is a host string owned by the library, valid until the next
+ * call of this function on the thread. */
+int mbu_unet_step_kernel(const mbu_unet_desc *d, int N, int H, int W, int step, const char **kernel);
+
 /* Workspace size (bytes) mbu_unet_forward needs for this shape. */
 int mbu_unet_workspace_bytes(const mbu_unet_desc *d, int N, int H, int W, size_t *bytes);
 
@@ -312,7 +343,13 @@ int mbu_unet_workspace_bytes(const mbu_unet_desc *d, int N, int H, int W, size_t
  * can be inspected afterwards through mbu_unet_step_info.
  *   image_nchw   float32 [N][in_channels][H][W]
  *   logits_nchw  float32 [N][n_classes][H][W]
- * H and W must be multiples of 2^levels. */
+ * H, W >= 2^levels.  Sizes that are not multiples of 2^levels (Appendix A.3: 959 x 640 frames)
+ * follow the usual U-Net reading, on which the paper is silent: pooling rounds the size down
+ * (an odd last row / column is dropped), and in the decoder the up-sampled feature, smaller by
+ * that row / column, is zero-padded at the bottom / right to the skip feature's size before the
+ * concatenation; the padded elements are the value 0.  Packed bits cannot hold a 0, so such a
+ * concatenation is never written to the workspace (whatever `fuse` says): the layer after it
+ * reads both tensors in place.  On the vector-ALU path such sizes give MBU_ERR_SHAPE. */
 int mbu_unet_forward(const mbu_unet_desc *d, const float *image_nchw, int N, int H, int W,
                      float *logits_nchw, void *workspace, size_t workspace_bytes,
                      void *stream);

@@ -25,6 +25,7 @@ EXPORTS = [
     "mbu_fold_batchnorm", "mbu_cost_rank",
     "mbu_packed_weights_bytes", "mbu_pack_weights", "mbu_conv3x3_masked_binary",
     "mbu_conv3x3_masked_binary_fused", "mbu_conv3x3_masked_binary_concat",
+    "mbu_conv3x3_masked_binary_two_inputs", "mbu_unet_step_kernel",
     "mbu_packed_tconv_weights_bytes", "mbu_pack_tconv_weights", "mbu_tconv2x2_masked_binary",
     "mbu_maxpool2x2_bits", "mbu_upsample2x_bits", "mbu_concat_bits", "mbu_unet_num_steps",
     "mbu_unet_step_info", "mbu_unet_step_launches", "mbu_unet_workspace_bytes", "mbu_unet_forward",
@@ -71,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.mbu_conv3x3_masked_binary.argtypes = [vp, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp]
         L.mbu_conv3x3_masked_binary_fused.argtypes = [vp, ci, vp, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp]
         L.mbu_conv3x3_masked_binary_concat.argtypes = [vp, ci, vp, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp]
+        L.mbu_conv3x3_masked_binary_two_inputs.argtypes = [vp, ci, vp, ci, ci, ci, ci, ci, ci, ci, vp, ci,
+                                                           vp, vp, vp, vp]
         L.mbu_packed_tconv_weights_bytes.argtypes = [ci, ci, ctypes.POINTER(ctypes.c_size_t)]
         L.mbu_pack_tconv_weights.argtypes = [vp, ci, ci, vp, vp]
         L.mbu_tconv2x2_masked_binary.argtypes = [vp, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp]
@@ -89,6 +92,8 @@ def lib() -> ctypes.CDLL:
                                          ctypes.POINTER(ctypes.c_size_t),
                                          ctypes.POINTER(ci), ctypes.POINTER(ci), ctypes.POINTER(ci)]
         L.mbu_unet_step_launches.argtypes = [ctypes.POINTER(UNetDesc), ci, ci, ci, ci]
+        L.mbu_unet_step_kernel.argtypes = [ctypes.POINTER(UNetDesc), ci, ci, ci, ci,
+                                           ctypes.POINTER(ctypes.c_char_p)]
         L.mbu_unet_workspace_bytes.argtypes = [ctypes.POINTER(UNetDesc), ci, ci, ci,
                                                ctypes.POINTER(ctypes.c_size_t)]
         L.mbu_unet_forward.argtypes = [ctypes.POINTER(UNetDesc), vp, ci, ci, ci, vp, vp,
@@ -285,6 +290,23 @@ def conv3x3_masked_binary_concat(a: torch.Tensor, ca: int, b: torch.Tensor, cb: 
     return out_bits, out_pool
 
 
+def conv3x3_masked_binary_two_inputs(a: torch.Tensor, ca: int, b: torch.Tensor, cb: int,
+                                     upsample: bool, packed_w: torch.Tensor, cout: int,
+                                     thresh: torch.Tensor, want_pool: bool = False):
+    """mbu_conv3x3_masked_binary_two_inputs: b [N,Hb,Wb,ceil(cb/32)] may cover less than the
+    frame of a -> (packed bits, pooled packed bits or None)."""
+    N, H, W, _ = a.shape
+    out_bits = torch.empty((N, H, W, cout // 32), dtype=torch.int32, device=a.device)
+    out_pool = (torch.empty((N, H // 2, W // 2, cout // 32), dtype=torch.int32, device=a.device)
+                if want_pool else None)
+    check(lib().mbu_conv3x3_masked_binary_two_inputs(
+        _dev(a, (torch.int32,)), ca, _dev(b, (torch.int32,)), cb, b.shape[1], b.shape[2],
+        1 if upsample else 0, N, H, W, _dev(packed_w, (torch.uint8,)), cout,
+        _dev(thresh, (torch.int32,)), out_bits.data_ptr(),
+        out_pool.data_ptr() if out_pool is not None else None, _stream()))
+    return out_bits, out_pool
+
+
 def pack_tconv_weights(w: torch.Tensor) -> torch.Tensor:
     """mbu_pack_tconv_weights: device int8 [Cout,2,2,Cin] -> opaque blob (uint8 tensor)."""
     cout, kh, kw, cin = w.shape
@@ -440,6 +462,12 @@ class UNet:
         if rc < 0:
             check(rc)
         return rc == 1
+
+    def step_kernel(self, N: int, H: int, W: int, step: int) -> str:
+        """Name of the kernel the step launches for this shape ("" if it launches none)."""
+        name = ctypes.c_char_p()
+        check(lib().mbu_unet_step_kernel(ctypes.byref(self.desc), N, H, W, step, ctypes.byref(name)))
+        return name.value.decode()
 
     def step_times_ms(self, N: int, H: int, W: int, es: Optional["EventSet"] = None) -> List[float]:
         """Per-step durations of the last forward pass recorded into `es`; steps folded into

@@ -303,13 +303,16 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_bits_kernel(
 //           comes from act[y][x][k] for k < Cwa and from the second tensor otherwise - at
 //           low[y/2][x/2][k - Cwa] when it is half size (nearest up-sampling, low_shift = 1)
 //           or at low[y][x][k - Cwa] (low_shift = 0); neither the skip concatenation nor
-//           the up-sampling is ever materialised;
+//           the up-sampling is ever materialised.  The second tensor has Hb x Wb pixels of its
+//           own and may cover less than the image (decoder of a frame whose size is not a
+//           multiple of 2^levels): where it has no pixel its channels are zeros, staged like
+//           pixels outside the image;
 //  POOL     besides its own output the layer writes the 2x2 OR-pooled output (max pooling
 //           of +-1 values): rows pair up inside a lane, columns with the neighbouring lane.
 template <int RW, int WM, int WN, bool CW_EVEN, bool TWO_SRC, bool POOL>
 __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
     const uint32_t *__restrict__ act, const uint32_t *__restrict__ low, int N, int H, int W,
-    int Cwa, int Cwb, int low_shift, int ksteps, const uint4 *__restrict__ wfrag, int Cout,
+    int Cwa, int Cwb, int low_shift, int Hb, int Wb, int ksteps, const uint4 *__restrict__ wfrag, int Cout,
     int tiles64, int ptiles, TileStep tstep, const int32_t *__restrict__ thresh,
     const int32_t *__restrict__ wsum, uint32_t *__restrict__ out_bits, uint32_t *__restrict__ out_pool)
 {
@@ -357,13 +360,15 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
         __builtin_amdgcn_make_buffer_rsrc((void *)act, 0, (int)((size_t)N * H * W * Cwa * 4), 0x00020000);
     const __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc(
         (void *)(TWO_SRC ? low : act), 0,
-        TWO_SRC ? (int)((size_t)N * (H >> low_shift) * (W >> low_shift) * Cwb * 4) : 0, 0x00020000);
+        TWO_SRC ? (int)((size_t)N * Hb * Wb * Cwb * 4) : 0, 0x00020000);
     uint32_t offa[NLD];                  // byte offset of the (clamped) pixel in act
     uint32_t offb[TWO_SRC ? NLD : 1];    // ... of the pixel (y/2, x/2) or (y, x) in low
     uint32_t inside = 0;                 // bit j: pixel j lies inside the image
+    uint32_t inside_b = 0;               // bit j: ... and the second tensor has a pixel for it
     auto plan = [&](const TilePos &tp) {
         const int tx = tp.tx, ty = tp.ty, n = tp.n;
         inside = 0;
+        inside_b = 0;
 #pragma unroll
         for (int j = 0; j < NLD; ++j) {
             int p = tid + NT * j;
@@ -374,9 +379,11 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
             const int yc = min(max(yy, 0), H - 1), xc = min(max(xx, 0), W - 1);
             offa[j] = (uint32_t)((((size_t)n * H + yc) * W + xc) * Cwa * 4);
             inside |= (in ? 1u : 0u) << j;
-            if (TWO_SRC)   // second source: same pixel, or pixel (y/2, x/2) of a half-size tensor
-                offb[j] = (uint32_t)((((size_t)n * (H >> low_shift) + (yc >> low_shift)) * (W >> low_shift) +
-                                      (xc >> low_shift)) * Cwb * 4);
+            if (TWO_SRC) {   // second source: same pixel, or pixel (y/2, x/2) of a half-size tensor
+                const int yb = yc >> low_shift, xb = xc >> low_shift;
+                inside_b |= ((in && yb < Hb && xb < Wb) ? 1u : 0u) << j;
+                offb[j] = (uint32_t)((((size_t)n * Hb + min(yb, Hb - 1)) * Wb + min(xb, Wb - 1)) * Cwb * 4);
+            }
         }
     };
     // word k (wave-uniform) of staged pixel j of the virtual input
@@ -419,10 +426,12 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
             const int r = p / HALO_W, c = p - r * HALO_W;
             uint4 *d = buf + (r * 2) * HALO_W + c;
             const uint32_t a = gq[j].x, b = gq[j].y;
-            const bool in = (inside >> j) & 1u;
-            const uint32_t m2 = in ? 0x22222222u : 0u, p1 = in ? 0u : 0x11111111u;
-            d[0] = expand_word_masked(a, m2, p1);
-            d[HALO_W] = expand_word_masked(b, second ? m2 : 0u, second ? p1 : 0u);
+            // each of the step's two words belongs to one source (wave-uniform choice)
+            const bool in0 = ((TWO_SRC && 2 * ks >= Cwa ? inside_b : inside) >> j) & 1u;
+            const bool in1 = ((TWO_SRC && 2 * ks + 1 >= Cwa ? inside_b : inside) >> j) & 1u;
+            d[0] = expand_word_masked(a, in0 ? 0x22222222u : 0u, in0 ? 0u : 0x11111111u);
+            d[HALO_W] = expand_word_masked(b, (second && in1) ? 0x22222222u : 0u,
+                                           (second && !in1) ? 0x11111111u : 0u);
         }
     };
 
@@ -744,7 +753,8 @@ static int launch_bits_t(const uint32_t *act, int N, int H, int W, const BlobLay
 struct ConvIO {
     const uint32_t *act;
     const uint32_t *low;     // NULL = single source
-    int low_shift;           // 1: low is half size (read up-sampled), 0: same size as act
+    int low_shift;           // 1: low is read 2x up-sampled, 0: pixel for pixel
+    int hb, wb;              // pixels of low; its (up-sampled) extent may fall short of the image
     int cwa, cwb;            // words per pixel of act / low
     uint32_t *out_bits;      // may be NULL when out_pool is set
     uint32_t *out_pool;      // NULL = no pooled output
@@ -758,7 +768,7 @@ static int launch_block_t(const ConvIO &io, int N, int H, int W, const BlobLayou
     long tiles = (long)N * ceil_div(H, RW * WM) * ceil_div(W, TW);
     if (tiles > 0x7fffffffL) return fail(MBU_ERR_SHAPE, "too many tiles for one launch");
     if ((double)N * H * W * io.cwa * 4 >= 2147483648.0 ||
-        (TWO_SRC && (double)N * (H >> io.low_shift) * (W >> io.low_shift) * io.cwb * 4 >= 2147483648.0))
+        (TWO_SRC && (double)N * io.hb * io.wb * io.cwb * 4 >= 2147483648.0))
         return fail(MBU_ERR_SHAPE, "input tensor too large for one launch (2 GiB)");
     // persistent blocks: two per compute unit in total, spread over the output-channel
     // groups; each strides over the pixel tiles
@@ -769,11 +779,11 @@ static int launch_block_t(const ConvIO &io, int N, int H, int W, const BlobLayou
     const bool even = (io.cwa % 2 == 0) && (!TWO_SRC || io.cwb % 2 == 0);
     if (even)
         MBU_LAUNCH((conv_mfma_block_kernel<RW, WM, WN, true, TWO_SRC, POOL>), grid, dim3(256), 0, s,
-                   io.act, io.low, N, H, W, io.cwa, io.cwb, io.low_shift, L.ksteps, wfrag, L.cout, tiles64,
+                   io.act, io.low, N, H, W, io.cwa, io.cwb, io.low_shift, io.hb, io.wb, L.ksteps, wfrag, L.cout, tiles64,
                    (int)tiles, tstep, thresh, weight_sums(wfrag, L), io.out_bits, io.out_pool);
     else
         MBU_LAUNCH((conv_mfma_block_kernel<RW, WM, WN, false, TWO_SRC, POOL>), grid, dim3(256), 0, s,
-                   io.act, io.low, N, H, W, io.cwa, io.cwb, io.low_shift, L.ksteps, wfrag, L.cout, tiles64,
+                   io.act, io.low, N, H, W, io.cwa, io.cwb, io.low_shift, io.hb, io.wb, L.ksteps, wfrag, L.cout, tiles64,
                    (int)tiles, tstep, thresh, weight_sums(wfrag, L), io.out_bits, io.out_pool);
     return check_launch("conv_mfma_block");
 }
@@ -836,7 +846,7 @@ int launch_conv_mfma(const uint32_t *act, int N, int H, int W, const BlobLayout 
         return launch_conv_mfma_rows2k(act, N, H, W, L, blob, thresh, out_bits, nullptr, s);
     const bool want_block = mode == 1 || ((mode == 0 || mode == 9) && L.ksteps > 1);
     if (want_block) {
-        ConvIO io{act, nullptr, 0, L.cin_words, 0, out_bits, nullptr};
+        ConvIO io{act, nullptr, 0, 0, 0, L.cin_words, 0, out_bits, nullptr};
         return launch_block_auto(io, N, H, W, L, wfrag, thresh, s);
     }
     if (rows_kernel_waves() && conv_rows_supported(H, W, L, out_bits != nullptr))
@@ -845,30 +855,25 @@ int launch_conv_mfma(const uint32_t *act, int N, int H, int W, const BlobLayout 
     return launch_bits<3, 2>(act, N, H, W, L, wfrag, thresh, out_bits, s);
 }
 
-// Fused form: input = [act (Ca channels) | low (Clow channels)] when low is given - read
-// up-sampled 2x when low_shift = 1 - plus an optional 2x2-pooled second output.  The
-// block-cooperative kernel, or the row-streaming kernel for a single-source single-step layer.
+// Fused form: input = [act (Ca channels) | low (Clow channels)] when low is given - Hb x Wb
+// pixels, read up-sampled 2x when low_shift = 1, zeros where its extent falls short of H x W -
+// plus an optional 2x2-pooled second output.  The low-resolution decoder kernel, the
+// row-streaming kernels for a single source, else the block-cooperative kernel.
 int launch_conv_mfma_two(const uint32_t *act, int Ca, const uint32_t *low, int Clow, int low_shift,
-                         int N, int H, int W, const BlobLayout &L, const void *blob,
+                         int Hb, int Wb, int N, int H, int W, const BlobLayout &L, const void *blob,
                          const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, hipStream_t s)
 {
-    if (low && low_shift == 1 && t_cfg.tune_rw != 1 && conv_upcat_supported(Ca, Clow, N, H, W, L, out_bits, out_pool))
+    if (low && low_shift == 1 && 2 * Hb == H && 2 * Wb == W && t_cfg.tune_rw != 1 &&
+        conv_upcat_supported(Ca, Clow, N, H, W, L, out_bits, out_pool))
         return launch_conv_mfma_upcat(act, Ca, low, Clow, N, H, W, L, blob, thresh, out_bits, s);
     if (!low && rows_kernel_waves() && conv_rows_supported(H, W, L, out_bits != nullptr))
         return launch_conv_mfma_rows(act, N, H, W, L, blob, thresh, out_bits, out_pool, rows_kernel_waves(), s);
     if (!low && use_rows2k(N, H, W, L, out_bits != nullptr))
         return launch_conv_mfma_rows2k(act, N, H, W, L, blob, thresh, out_bits, out_pool, s);
     const uint4 *wfrag = (const uint4 *)((const uint8_t *)blob + L.off_f4);
-    ConvIO io{act, low, low ? low_shift : 0, ceil_div(Ca, 32), low ? ceil_div(Clow, 32) : 0,
-              out_bits, out_pool};
+    ConvIO io{act, low, low ? low_shift : 0, low ? Hb : 0, low ? Wb : 0, ceil_div(Ca, 32),
+              low ? ceil_div(Clow, 32) : 0, out_bits, out_pool};
     return launch_block_auto(io, N, H, W, L, wfrag, thresh, s);
-}
-
-int launch_conv_mfma_fused(const uint32_t *act, int Ca, const uint32_t *low, int Clow, int N, int H,
-                           int W, const BlobLayout &L, const void *blob, const int32_t *thresh,
-                           uint32_t *out_bits, uint32_t *out_pool, hipStream_t s)
-{
-    return launch_conv_mfma_two(act, Ca, low, Clow, 1, N, H, W, L, blob, thresh, out_bits, out_pool, s);
 }
 
 }  // namespace mbu

@@ -15,8 +15,9 @@ __device__ inline uint4 vor(uint4 a, uint4 b)
     return make_uint4(a.x | b.x, a.y | b.y, a.z | b.z, a.w | b.w);
 }
 
+// H x W input pixels, Ho = H / 2, Wo = W / 2 (floor: an odd last row / column is in no window)
 template <typename V>
-__global__ __launch_bounds__(256) void maxpool_kernel(const V *__restrict__ in, long total,
+__global__ __launch_bounds__(256) void maxpool_kernel(const V *__restrict__ in, long total, int H, int W,
                                                       int Wo, int Ho, int Cv, V *__restrict__ out)
 {
     long idx = (long)blockIdx.x * 256 + threadIdx.x;
@@ -27,8 +28,7 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const V *__restrict__ in, 
     long q = p / Wo;
     int y = (int)(q % Ho);
     long n = q / Ho;
-    const int W = 2 * Wo;
-    const V *r0 = in + (((n * 2 * Ho + 2 * y) * W) + 2 * x) * Cv + c;
+    const V *r0 = in + (((n * H + 2 * y) * W) + 2 * x) * Cv + c;
     const V *r1 = r0 + (long)W * Cv;
     out[idx] = vor(vor(r0[0], r0[Cv]), vor(r1[0], r1[Cv]));
 }
@@ -102,7 +102,7 @@ int launch_maxpool(const uint32_t *in, int N, int H, int W, int Cw, uint32_t *ou
     if (total == 0) return MBU_OK;
     unsigned blocks = (unsigned)((total + 255) / 256);
     MBU_DISPATCH_V(v, MBU_LAUNCH(maxpool_kernel<V>, dim3(blocks), dim3(256), 0, s,
-                                         (const V *)in, total, Wo, Ho, Cv, (V *)out));
+                                         (const V *)in, total, H, W, Wo, Ho, Cv, (V *)out));
     return check_launch("maxpool2x2_bits");
 }
 

@@ -111,7 +111,7 @@ static int build_plan(const mbu_unet_desc *d, int N, int H, int W, std::vector<S
     int rc = check_dims4(fn, N, H, W, d->base);
     if (rc) return rc;
     int m = 1 << d->levels;
-    if (H % m || W % m) return fail(MBU_ERR_SHAPE, "%s: H and W must be multiples of %d", fn, m);
+    if (H < m || W < m) return fail(MBU_ERR_SHAPE, "%s: H and W must be at least %d", fn, m);
 
     size_t off = 0;
     auto push = [&](Step::Kind k, const char *name, int conv, int in, int in2, int h, int w, int c) {
@@ -137,7 +137,7 @@ static int build_plan(const mbu_unet_desc *d, int N, int H, int W, std::vector<S
             if (cur < 0) return fail(MBU_ERR_SHAPE, "%s: conv layer %d has inconsistent channels", fn, -1 - cur);
         }
         skips.push_back(cur);
-        h /= 2; w /= 2;
+        h /= 2; w /= 2;      // floor: an odd last row / column is dropped
         cur = push(Step::POOL, kPoolNames[l], -1, cur, -1, h, w, steps[cur].c);
     }
     for (int j = 0; j < 2; ++j) {
@@ -145,14 +145,18 @@ static int build_plan(const mbu_unet_desc *d, int N, int H, int W, std::vector<S
         if (cur < 0) return fail(MBU_ERR_SHAPE, "%s: conv layer %d has inconsistent channels", fn, -1 - cur);
     }
     for (int l = d->levels - 1; l >= 0; --l) {
-        h *= 2; w *= 2;
         int sk = skips[l];
+        // the up-sampled feature has twice the size of the level below, which is the skip
+        // feature's size less the row / column that pooling dropped; the concatenation has
+        // the skip feature's size (the missing elements count as zeros)
+        const int hu = 2 * h, wu = 2 * w;
+        h = steps[sk].h; w = steps[sk].w;
         if (d->up_convs) {
             // transposed decoder: masked transposed layer 2x2 stride 2, then plain concatenation
             const mbu_conv_layer &U = d->up_convs[d->levels - 1 - l];
             if (U.cin != steps[cur].c || U.cout <= 0 || U.cout % 32)
                 return fail(MBU_ERR_SHAPE, "%s: transposed layer %d has inconsistent channels", fn, d->levels - 1 - l);
-            cur = push(Step::TCONV, kUpNames[l], d->levels - 1 - l, cur, -1, h, w, U.cout);
+            cur = push(Step::TCONV, kUpNames[l], d->levels - 1 - l, cur, -1, hu, wu, U.cout);
             cur = push(Step::CAT, kCatNames[l], -1, sk, cur, h, w, steps[sk].c + steps[cur].c);
         } else {
             cur = push(Step::UPCAT, kCatNames[l], -1, sk, cur, h, w, steps[sk].c + steps[cur].c);
@@ -169,19 +173,45 @@ static int build_plan(const mbu_unet_desc *d, int N, int H, int W, std::vector<S
     return MBU_OK;
 }
 
+// Is the second input of this concatenation step smaller than the first (frame size not a
+// multiple of 2^levels)?  Its missing elements are zeros, which packed bits cannot hold, so
+// such a concatenation is never materialised: the layer after it reads both tensors in place.
+static bool cat_needs_padding(const std::vector<Step> &steps, const Step &cat)
+{
+    const Step &a = steps[cat.in], &b = steps[cat.in2];
+    const int sh = cat.kind == Step::UPCAT ? 1 : 0;
+    return (b.h << sh) != a.h || (b.w << sh) != a.w;
+}
+
 // Does step i launch a kernel of its own under the descriptor's fusion setting?
 static bool step_launches(const mbu_unet_desc *d, const std::vector<Step> &steps, size_t i)
 {
-    const bool fuse = d->fuse != 0 && t_cfg.conv_path != MBU_PATH_VALU;
-    if (!fuse) return true;
+    const bool matrix = t_cfg.conv_path != MBU_PATH_VALU;
+    const bool fuse = d->fuse != 0 && matrix;
     const Step &st = steps[i];
-    if (st.kind == Step::UPCAT || st.kind == Step::CAT) return false;
+    if (st.kind == Step::UPCAT || st.kind == Step::CAT)
+        return !fuse && !(matrix && cat_needs_padding(steps, st));
+    if (!fuse) return true;
     if (st.kind == Step::POOL) {
         const Step &in = steps[st.in];
         return !(in.kind == Step::CONV &&
                  conv_writes_pooled(in.h, in.w, blob_layout(d->convs[in.conv].cout, d->convs[in.conv].cin)));
     }
     return true;
+}
+
+// "(conv_mfma_block_kernel<RW, WM, WN, ...>)" as written at the launch site -> "conv_mfma_block_kernel"
+static const char *kernel_base_name(const char *written)
+{
+    static thread_local char name[96];
+    size_t n = 0;
+    for (const char *p = written; *p && n + 1 < sizeof(name); ++p) {
+        if (*p == '(' || *p == ' ') continue;
+        if (*p == '<' || *p == ')') break;
+        name[n++] = *p;
+    }
+    name[n] = 0;
+    return name;
 }
 
 static int run_conv(const uint32_t *act, int N, int H, int W, int Cin, const void *packed_w,
@@ -236,6 +266,7 @@ int mbu_stem_fp32(const float *image_nchw, int N, int Ci, int H, int W, const fl
                   uint32_t *out_bits, float *out_pre, void *stream)
 {
     const char *fn = "mbu_stem_fp32";
+    begin_call();
     MBU_REQ_PTR(fn, image_nchw);
     MBU_REQ_PTR(fn, w);
     MBU_REQ_PTR(fn, out_bits);
@@ -253,6 +284,7 @@ int mbu_classifier_fp32(const uint32_t *act, int N, int H, int W, int C, const f
                         const float *b, int K, float *logits_nchw, void *stream)
 {
     const char *fn = "mbu_classifier_fp32";
+    begin_call();
     MBU_REQ_PTR(fn, act);
     MBU_REQ_PTR(fn, w);
     MBU_REQ_PTR(fn, b);
@@ -277,6 +309,7 @@ int mbu_pack_act(const void *src, int src_dtype, int N, int H, int W, int C, uin
                  void *stream)
 {
     const char *fn = "mbu_pack_act";
+    begin_call();
     MBU_REQ_PTR(fn, src);
     MBU_REQ_PTR(fn, dst);
     if (src_dtype != 0 && src_dtype != 1) return fail(MBU_ERR_ARG, "%s: src_dtype must be 0 (int8) or 1 (float32)", fn);
@@ -298,6 +331,7 @@ int mbu_packed_weights_bytes(int Cout, int Cin, size_t *bytes)
 int mbu_pack_weights(const int8_t *w_ohwi, int Cout, int Cin, void *packed, void *stream)
 {
     const char *fn = "mbu_pack_weights";
+    begin_call();
     MBU_REQ_PTR(fn, w_ohwi);
     MBU_REQ_PTR(fn, packed);
     size_t bytes;
@@ -311,6 +345,7 @@ int mbu_conv3x3_masked_binary(const uint32_t *act, int N, int H, int W, int Cin,
                               uint32_t *out_bits, int32_t *out_acc, void *stream)
 {
     const char *fn = "mbu_conv3x3_masked_binary";
+    begin_call();
     MBU_REQ_PTR(fn, act);
     MBU_REQ_PTR(fn, packed_w);
     MBU_REQ_PTR(fn, thresh);
@@ -334,6 +369,7 @@ int mbu_conv3x3_masked_binary_fused(const uint32_t *act, int Ca, const uint32_t 
                                     void *stream)
 {
     const char *fn = "mbu_conv3x3_masked_binary_fused";
+    begin_call();
     MBU_REQ_PTR(fn, act);
     MBU_REQ_PTR(fn, packed_w);
     MBU_REQ_PTR(fn, thresh);
@@ -349,8 +385,10 @@ int mbu_conv3x3_masked_binary_fused(const uint32_t *act, int Ca, const uint32_t 
     if ((low != nullptr) != (Clow > 0) || Clow < 0)
         return fail(MBU_ERR_SHAPE, "%s: Clow must be positive exactly when low is given (Clow=%d)", fn, Clow);
     if (low && Ca % 32) return fail(MBU_ERR_SHAPE, "%s: Ca must be a multiple of 32 when low is given, got %d", fn, Ca);
-    if ((low || out_pool) && ((H & 1) || (W & 1)))
-        return fail(MBU_ERR_SHAPE, "%s: H and W must be even with low / out_pool (H=%d W=%d)", fn, H, W);
+    if (out_pool && ((H & 1) || (W & 1)))
+        return fail(MBU_ERR_SHAPE, "%s: H and W must be even with out_pool (H=%d W=%d)", fn, H, W);
+    if (low && (H < 2 || W < 2))
+        return fail(MBU_ERR_SHAPE, "%s: H and W must be at least 2 with low (H=%d W=%d)", fn, H, W);
     if (Cout <= 0 || Cout % 32) return fail(MBU_ERR_SHAPE, "%s: Cout must be a positive multiple of 32, got %d", fn, Cout);
     if (Cout > 65536 || Ca + Clow > 65536) return fail(MBU_ERR_SHAPE, "%s: channel count too large", fn);
     rc = check_dims4(fn, N, H, W, Cout);
@@ -359,8 +397,8 @@ int mbu_conv3x3_masked_binary_fused(const uint32_t *act, int Ca, const uint32_t 
     if (rc) return rc;
     // the matrix-path blob stores whole 32-channel words of each source one after the other
     const int cin_blob = Ca + Clow;
-    return launch_conv_mfma_fused(act, Ca, low, Clow, N, H, W, blob_layout(Cout, cin_blob), packed_w,
-                                  thresh, out_bits, out_pool, (hipStream_t)stream);
+    return launch_conv_mfma_two(act, Ca, low, Clow, 1, H / 2, W / 2, N, H, W, blob_layout(Cout, cin_blob),
+                                packed_w, thresh, out_bits, out_pool, (hipStream_t)stream);
 }
 
 int mbu_conv3x3_masked_binary_concat(const uint32_t *a, int Ca, const uint32_t *b, int Cb, int N,
@@ -369,6 +407,7 @@ int mbu_conv3x3_masked_binary_concat(const uint32_t *a, int Ca, const uint32_t *
                                      void *stream)
 {
     const char *fn = "mbu_conv3x3_masked_binary_concat";
+    begin_call();
     MBU_REQ_PTR(fn, a);
     MBU_REQ_PTR(fn, b);
     MBU_REQ_PTR(fn, packed_w);
@@ -391,8 +430,45 @@ int mbu_conv3x3_masked_binary_concat(const uint32_t *a, int Ca, const uint32_t *
     if (rc) return rc;
     rc = check_dims4(fn, N, H, W, Ca + Cb);
     if (rc) return rc;
-    return launch_conv_mfma_two(a, Ca, b, Cb, 0, N, H, W, blob_layout(Cout, Ca + Cb), packed_w, thresh,
+    return launch_conv_mfma_two(a, Ca, b, Cb, 0, H, W, N, H, W, blob_layout(Cout, Ca + Cb), packed_w, thresh,
                                 out_bits, out_pool, (hipStream_t)stream);
+}
+
+int mbu_conv3x3_masked_binary_two_inputs(const uint32_t *a, int Ca, const uint32_t *b, int Cb, int Hb,
+                                         int Wb, int upsample, int N, int H, int W, const void *packed_w,
+                                         int Cout, const int32_t *thresh, uint32_t *out_bits,
+                                         uint32_t *out_pool, void *stream)
+{
+    const char *fn = "mbu_conv3x3_masked_binary_two_inputs";
+    begin_call();
+    MBU_REQ_PTR(fn, a);
+    MBU_REQ_PTR(fn, b);
+    MBU_REQ_PTR(fn, packed_w);
+    MBU_REQ_PTR(fn, thresh);
+    if (!out_bits && !out_pool) return fail(MBU_ERR_NULL, "%s: out_bits and out_pool are both NULL", fn);
+    if (out_bits && !aligned16(out_bits)) return fail(MBU_ERR_ALIGN, "%s: out_bits is not 16-byte aligned", fn);
+    if (out_pool && !aligned16(out_pool)) return fail(MBU_ERR_ALIGN, "%s: out_pool is not 16-byte aligned", fn);
+    if ((const void *)out_bits == (const void *)a || (const void *)out_bits == (const void *)b ||
+        (const void *)out_pool == (const void *)a || (const void *)out_pool == (const void *)b)
+        return fail(MBU_ERR_ARG, "%s: outputs must not alias an input", fn);
+    if (upsample != 0 && upsample != 1) return fail(MBU_ERR_ARG, "%s: upsample must be 0 or 1", fn);
+    int rc = check_dims4(fn, N, H, W, Ca);
+    if (rc) return rc;
+    if (Cb <= 0) return fail(MBU_ERR_SHAPE, "%s: Cb must be positive, got %d", fn, Cb);
+    if (Ca % 32) return fail(MBU_ERR_SHAPE, "%s: Ca must be a multiple of 32, got %d", fn, Ca);
+    if (Hb <= 0 || Wb <= 0 || (Hb << upsample) > H || (Wb << upsample) > W)
+        return fail(MBU_ERR_SHAPE, "%s: the second input (%d x %d pixels%s) must be non-empty and fit into "
+                    "%d x %d", fn, Hb, Wb, upsample ? ", read 2x up-sampled" : "", H, W);
+    if (out_pool && ((H & 1) || (W & 1)))
+        return fail(MBU_ERR_SHAPE, "%s: H and W must be even with out_pool (H=%d W=%d)", fn, H, W);
+    if (Cout <= 0 || Cout % 32) return fail(MBU_ERR_SHAPE, "%s: Cout must be a positive multiple of 32, got %d", fn, Cout);
+    if (Cout > 65536 || Ca + Cb > 65536) return fail(MBU_ERR_SHAPE, "%s: channel count too large", fn);
+    rc = check_dims4(fn, N, H, W, Cout);
+    if (rc) return rc;
+    rc = check_dims4(fn, N, H, W, Ca + Cb);
+    if (rc) return rc;
+    return launch_conv_mfma_two(a, Ca, b, Cb, upsample, Hb, Wb, N, H, W, blob_layout(Cout, Ca + Cb), packed_w,
+                                thresh, out_bits, out_pool, (hipStream_t)stream);
 }
 
 int mbu_packed_tconv_weights_bytes(int Cout, int Cin, size_t *bytes)
@@ -408,6 +484,7 @@ int mbu_packed_tconv_weights_bytes(int Cout, int Cin, size_t *bytes)
 int mbu_pack_tconv_weights(const int8_t *w, int Cout, int Cin, void *packed, void *stream)
 {
     const char *fn = "mbu_pack_tconv_weights";
+    begin_call();
     MBU_REQ_PTR(fn, w);
     MBU_REQ_PTR(fn, packed);
     size_t bytes;
@@ -421,6 +498,7 @@ int mbu_tconv2x2_masked_binary(const uint32_t *act, int N, int H, int W, int Cin
                                uint32_t *out_bits, int32_t *out_acc, void *stream)
 {
     const char *fn = "mbu_tconv2x2_masked_binary";
+    begin_call();
     MBU_REQ_PTR(fn, act);
     MBU_REQ_PTR(fn, packed_w);
     MBU_REQ_PTR(fn, thresh);
@@ -441,17 +519,19 @@ int mbu_tconv2x2_masked_binary(const uint32_t *act, int N, int H, int W, int Cin
 int mbu_maxpool2x2_bits(const uint32_t *in, int N, int H, int W, int C, uint32_t *out, void *stream)
 {
     const char *fn = "mbu_maxpool2x2_bits";
+    begin_call();
     MBU_REQ_PTR(fn, in);
     MBU_REQ_PTR(fn, out);
     int rc = check_dims4(fn, N, H, W, C);
     if (rc) return rc;
-    if ((H & 1) || (W & 1)) return fail(MBU_ERR_SHAPE, "%s: H and W must be even (H=%d W=%d)", fn, H, W);
+    if (H < 2 || W < 2) return fail(MBU_ERR_SHAPE, "%s: H and W must be at least 2 (H=%d W=%d)", fn, H, W);
     return launch_maxpool(in, N, H, W, ceil_div(C, 32), out, (hipStream_t)stream);
 }
 
 int mbu_upsample2x_bits(const uint32_t *in, int N, int H, int W, int C, uint32_t *out, void *stream)
 {
     const char *fn = "mbu_upsample2x_bits";
+    begin_call();
     MBU_REQ_PTR(fn, in);
     MBU_REQ_PTR(fn, out);
     int rc = check_dims4(fn, N, H, W, C);
@@ -464,6 +544,7 @@ int mbu_concat_bits(const uint32_t *a, int Ca, const uint32_t *b, int Cb, int N,
                     uint32_t *out, void *stream)
 {
     const char *fn = "mbu_concat_bits";
+    begin_call();
     MBU_REQ_PTR(fn, a);
     MBU_REQ_PTR(fn, b);
     MBU_REQ_PTR(fn, out);
@@ -500,6 +581,7 @@ int mbu_unet_step_info(const mbu_unet_desc *d, int N, int H, int W, int step, co
 
 int mbu_unet_step_launches(const mbu_unet_desc *d, int N, int H, int W, int step)
 {
+    begin_call();
     std::vector<Step> steps;
     int rc = build_plan(d, N, H, W, steps, nullptr);
     if (rc) return rc;
@@ -514,40 +596,30 @@ int mbu_unet_workspace_bytes(const mbu_unet_desc *d, int N, int H, int W, size_t
     return build_plan(d, N, H, W, steps, bytes);
 }
 
-int mbu_unet_forward(const mbu_unet_desc *d, const float *image_nchw, int N, int H, int W,
-                     float *logits_nchw, void *workspace, size_t workspace_bytes, void *stream)
+}  // extern "C"
+
+namespace mbu {
+
+// The network walk shared by mbu_unet_forward and mbu_unet_step_kernel.  With t_cfg.dry_run
+// set nothing is launched and no event is recorded; the launchers still make their choices and
+// leave the chosen kernel's name in t_cfg.kernel, which is copied to kernel_of_step[i] for every
+// step that launches one ("" for a step folded into a neighbouring layer).
+static int walk(const mbu_unet_desc *d, const std::vector<Step> &steps, const float *image_nchw,
+                int N, int H, int W, float *logits_nchw, uint8_t *ws, hipStream_t s,
+                const char **kernel_of_step)
 {
     const char *fn = "mbu_unet_forward";
-    std::vector<Step> steps;
-    size_t need = 0;
-    int rc = build_plan(d, N, H, W, steps, &need);
-    if (rc) return rc;
-    MBU_REQ_PTR(fn, image_nchw);
-    MBU_REQ_PTR(fn, logits_nchw);
-    MBU_REQ_PTR(fn, workspace);
-    MBU_REQ_PTR(fn, d->stem_w);
-    MBU_REQ_PTR(fn, d->cls_w);
-    MBU_REQ_PTR(fn, d->cls_b);
-    if (workspace_bytes < need)
-        return fail(MBU_ERR_WORKSPACE, "%s: workspace has %zu bytes, %zu needed", fn, workspace_bytes, need);
-    int nconv = 2 * (2 * d->levels + 1);
-    for (int i = 0; i < nconv; ++i) {
-        MBU_REQ_PTR(fn, d->convs[i].packed_w);
-        MBU_REQ_PTR(fn, d->convs[i].thresh);
-    }
-    for (int i = 0; d->up_convs && i < d->levels; ++i) {
-        MBU_REQ_PTR(fn, d->up_convs[i].packed_w);
-        MBU_REQ_PTR(fn, d->up_convs[i].thresh);
-    }
-    hipStream_t s = (hipStream_t)stream;
-    uint8_t *ws = (uint8_t *)workspace;
+    const bool dry = t_cfg.dry_run;
     auto buf = [&](int step) { return (uint32_t *)(ws + steps[step].off); };
-    const bool fuse = d->fuse != 0 && g_conv_path != MBU_PATH_VALU;
+    const bool matrix = t_cfg.conv_path != MBU_PATH_VALU;
+    const bool fuse = d->fuse != 0 && matrix;
+    int rc = MBU_OK;
     for (size_t i = 0; i < steps.size(); ++i) {
         const Step &st = steps[i];
-        if (d->step_events && step_launches(d, steps, i) &&
+        if (!dry && d->step_events && step_launches(d, steps, i) &&
             hipEventRecord((hipEvent_t)d->step_events[i], s) != hipSuccess)
             return fail(MBU_ERR_HIP, "%s: hipEventRecord failed", fn);
+        t_cfg.kernel = "";
         switch (st.kind) {
         case Step::STEM:
             rc = run_stem(image_nchw, N, d->in_channels, H, W, d->stem_w, d->base, buf((int)i), nullptr, s);
@@ -556,7 +628,8 @@ int mbu_unet_forward(const mbu_unet_desc *d, const float *image_nchw, int N, int
             const mbu_conv_layer &L = d->convs[st.conv];
             const Step &in = steps[st.in];
             // fused forms: read [skip | up(low)] in place; write the pooled output as well
-            const bool from_cat = fuse && (in.kind == Step::UPCAT || in.kind == Step::CAT);
+            const bool cat_in = in.kind == Step::UPCAT || in.kind == Step::CAT;
+            const bool from_cat = cat_in && (fuse || cat_needs_padding(steps, in));
             const bool next_pool = fuse && i + 1 < steps.size() && steps[i + 1].kind == Step::POOL &&
                                    conv_writes_pooled(st.h, st.w, blob_layout(L.cout, L.cin));
             if (from_cat || next_pool) {
@@ -564,7 +637,8 @@ int mbu_unet_forward(const mbu_unet_desc *d, const float *image_nchw, int N, int
                 const int ca = from_cat ? steps[in.in].c : L.cin;
                 const uint32_t *lo = from_cat ? buf(in.in2) : nullptr;
                 const int clo = from_cat ? steps[in.in2].c : 0;
-                rc = launch_conv_mfma_two(a, ca, lo, clo, in.kind == Step::UPCAT ? 1 : 0, N, st.h, st.w,
+                const int hb = from_cat ? steps[in.in2].h : 0, wb = from_cat ? steps[in.in2].w : 0;
+                rc = launch_conv_mfma_two(a, ca, lo, clo, in.kind == Step::UPCAT ? 1 : 0, hb, wb, N, st.h, st.w,
                                           blob_layout(L.cout, L.cin), L.packed_w, L.thresh,
                                           buf((int)i), next_pool ? buf((int)i + 1) : nullptr, s);
             } else {
@@ -573,16 +647,12 @@ int mbu_unet_forward(const mbu_unet_desc *d, const float *image_nchw, int N, int
             }
             break;
         }
-        case Step::POOL: {
-            const Step &in = steps[st.in];
-            const bool done = fuse && in.kind == Step::CONV &&
-                              conv_writes_pooled(in.h, in.w, blob_layout(d->convs[in.conv].cout, d->convs[in.conv].cin));
-            if (!done)
-                rc = launch_maxpool(buf(st.in), N, st.h * 2, st.w * 2, st.c / 32, buf((int)i), s);
+        case Step::POOL:
+            if (step_launches(d, steps, i))
+                rc = launch_maxpool(buf(st.in), N, steps[st.in].h, steps[st.in].w, st.c / 32, buf((int)i), s);
             break;
-        }
         case Step::UPCAT:
-            if (!fuse)
+            if (step_launches(d, steps, i))
                 rc = launch_upcat(buf(st.in), steps[st.in].c / 32, buf(st.in2), steps[st.in2].c / 32,
                                   N, st.h, st.w, buf((int)i), s);
             break;
@@ -593,7 +663,7 @@ int mbu_unet_forward(const mbu_unet_desc *d, const float *image_nchw, int N, int
             break;
         }
         case Step::CAT:
-            if (!fuse)
+            if (step_launches(d, steps, i))
                 rc = launch_concat(buf(st.in), steps[st.in].c / 32, buf(st.in2), steps[st.in2].c / 32,
                                    (long)N * st.h * st.w, buf((int)i), s);
             break;
@@ -603,10 +673,76 @@ int mbu_unet_forward(const mbu_unet_desc *d, const float *image_nchw, int N, int
             break;
         }
         if (rc) return rc;
+        if (kernel_of_step) kernel_of_step[i] = t_cfg.kernel;
     }
-    if (d->step_events && hipEventRecord((hipEvent_t)d->step_events[steps.size()], s) != hipSuccess)
+    if (!dry && d->step_events && hipEventRecord((hipEvent_t)d->step_events[steps.size()], s) != hipSuccess)
         return fail(MBU_ERR_HIP, "%s: hipEventRecord failed", fn);
     return MBU_OK;
+}
+
+// validation shared by the forward entry points; fills the plan
+static int check_forward(const char *fn, const mbu_unet_desc *d, const float *image_nchw, int N, int H,
+                         int W, float *logits_nchw, std::vector<Step> &steps, size_t *need)
+{
+    int rc = build_plan(d, N, H, W, steps, need);
+    if (rc) return rc;
+    MBU_REQ_PTR(fn, image_nchw);
+    MBU_REQ_PTR(fn, logits_nchw);
+    MBU_REQ_PTR(fn, d->stem_w);
+    MBU_REQ_PTR(fn, d->cls_w);
+    MBU_REQ_PTR(fn, d->cls_b);
+    int nconv = 2 * (2 * d->levels + 1);
+    for (int i = 0; i < nconv; ++i) {
+        MBU_REQ_PTR(fn, d->convs[i].packed_w);
+        MBU_REQ_PTR(fn, d->convs[i].thresh);
+    }
+    for (int i = 0; d->up_convs && i < d->levels; ++i) {
+        MBU_REQ_PTR(fn, d->up_convs[i].packed_w);
+        MBU_REQ_PTR(fn, d->up_convs[i].thresh);
+    }
+    if (t_cfg.conv_path == MBU_PATH_VALU)
+        for (const Step &st : steps)
+            if ((st.kind == Step::UPCAT || st.kind == Step::CAT) && cat_needs_padding(steps, st))
+                return fail(MBU_ERR_SHAPE, "%s: H and W must be multiples of %d on the vector-ALU path "
+                            "(a padded decoder feature is only read in place by the matrix path)", fn, 1 << d->levels);
+    return MBU_OK;
+}
+
+}  // namespace mbu
+
+extern "C" {
+
+int mbu_unet_step_kernel(const mbu_unet_desc *d, int N, int H, int W, int step, const char **kernel)
+{
+    const char *fn = "mbu_unet_step_kernel";
+    begin_call(true);
+    if (!kernel) return fail(MBU_ERR_NULL, "%s: kernel is NULL", fn);
+    std::vector<Step> steps;
+    int rc = build_plan(d, N, H, W, steps, nullptr);
+    if (rc) return rc;
+    if (step < 0 || step >= (int)steps.size()) return fail(MBU_ERR_ARG, "%s: step %d out of range", fn, step);
+    std::vector<const char *> names(steps.size(), "");
+    // a dry run dereferences no device pointer; the workspace is only an address base
+    rc = walk(d, steps, nullptr, N, H, W, nullptr, (uint8_t *)256, nullptr, names.data());
+    t_cfg.dry_run = false;
+    if (rc) return rc;
+    *kernel = kernel_base_name(names[step]);
+    return MBU_OK;
+}
+
+int mbu_unet_forward(const mbu_unet_desc *d, const float *image_nchw, int N, int H, int W,
+                     float *logits_nchw, void *workspace, size_t workspace_bytes, void *stream)
+{
+    const char *fn = "mbu_unet_forward";
+    begin_call();
+    std::vector<Step> steps;
+    size_t need = 0;
+    int rc = check_forward(fn, d, image_nchw, N, H, W, logits_nchw, steps, &need);
+    if (rc) return rc;
+    MBU_REQ_PTR(fn, workspace);
+    if (workspace_bytes < need)
+        return fail(MBU_ERR_WORKSPACE, "%s: workspace has %zu bytes, %zu needed", fn, workspace_bytes, need);
+    return walk(d, steps, image_nchw, N, H, W, logits_nchw, (uint8_t *)workspace, (hipStream_t)stream, nullptr);
 }
 
 int mbu_event_create(void **event)

@@ -29,12 +29,12 @@ void begin_call(bool dry_run = false);
 // Launch wrapper: records which kernel was chosen; unless the call is a dry run it drops any
 // stale error left by earlier, unrelated runtime calls (so that check_launch() reports this
 // launch only) and launches.
-#define MBU_LAUNCH(kernel, grid, block, shmem, stream, ...)                         \
+#define MBU_LAUNCH(KERNEL_, grid, block, shmem, stream, ...)                         \
     do {                                                                            \
-        mbu::t_cfg.kernel = #kernel;                                                \
+        mbu::t_cfg.kernel = #KERNEL_;                                               \
         if (!mbu::t_cfg.dry_run) {                                                  \
             (void)hipGetLastError();                                                \
-            hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);    \
+            hipLaunchKernelGGL(KERNEL_, grid, block, shmem, stream, __VA_ARGS__);    \
         }                                                                           \
     } while (0)
 
@@ -94,13 +94,11 @@ int launch_conv_valu(const uint32_t *act, int N, int H, int W, const BlobLayout 
 int launch_conv_mfma(const uint32_t *act, int N, int H, int W, const BlobLayout &L,
                      const void *blob, const int32_t *thresh, uint32_t *out_bits,
                      int32_t *out_acc, hipStream_t s);
-int launch_conv_mfma_fused(const uint32_t *act, int Ca, const uint32_t *low, int Clow, int N, int H,
-                           int W, const BlobLayout &L, const void *blob, const int32_t *thresh,
-                           uint32_t *out_bits, uint32_t *out_pool, hipStream_t s);
-// low_shift = 1: `low` is half resolution and is read up-sampled; 0: `low` has the layer's own
-// resolution (plain channel concatenation of two tensors)
+// Input = [act | low]: low has Hb x Wb pixels of Clow channels, read 2x up-sampled when
+// low_shift = 1 and pixel for pixel when 0; where its (up-sampled) extent falls short of H x W
+// its channels are zeros.  low = NULL: single input.  out_pool: optional 2x2-pooled output.
 int launch_conv_mfma_two(const uint32_t *act, int Ca, const uint32_t *low, int Clow, int low_shift,
-                         int N, int H, int W, const BlobLayout &L, const void *blob,
+                         int Hb, int Wb, int N, int H, int W, const BlobLayout &L, const void *blob,
                          const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, hipStream_t s);
 // row-streaming kernel for layers with a single 64-channel input step (optional 2x2-pooled
 // second output); waves_per_simd = 1 or 2

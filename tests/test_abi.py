@@ -34,7 +34,7 @@ def test_null_and_alignment_errors():
     assert L.mbu_pack_act(fake, 0, 1, 4, 4, 32, fake2 + 4, None) == B.MBU_ERR_ALIGN
     assert L.mbu_pack_act(fake, 7, 1, 4, 4, 32, fake2, None) == B.MBU_ERR_ARG
     assert L.mbu_pack_act(fake, 0, 0, 4, 4, 32, fake2, None) == B.MBU_ERR_SHAPE
-    assert L.mbu_maxpool2x2_bits(fake, 1, 3, 4, 32, fake2, None) == B.MBU_ERR_SHAPE
+    assert L.mbu_maxpool2x2_bits(fake, 1, 1, 4, 32, fake2, None) == B.MBU_ERR_SHAPE
     assert L.mbu_maxpool2x2_bits(fake, 1, 4, 4, 32, None, None) == B.MBU_ERR_NULL
     assert L.mbu_upsample2x_bits(None, 1, 4, 4, 32, fake2, None) == B.MBU_ERR_NULL
     assert L.mbu_concat_bits(fake, 48, fake2, 32, 1, 4, 4, fake, None) == B.MBU_ERR_SHAPE
@@ -62,7 +62,8 @@ def test_fused_conv_argument_validation():
     assert f(a, 64, None, 128, 1, 8, 8, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
     assert f(a, 64, lo, 0, 1, 8, 8, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
     assert f(a, 48, lo, 128, 1, 8, 8, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
-    assert f(a, 64, lo, 128, 1, 7, 8, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
+    assert f(a, 64, lo, 128, 1, 1, 8, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
+    assert f(a, 64, lo, 128, 1, 7, 8, w, 64, t, o, p, None) == B.MBU_ERR_SHAPE
     assert f(a, 64, None, 0, 1, 8, 9, w, 64, t, o, p, None) == B.MBU_ERR_SHAPE
     assert f(a, 64, lo, 128, 1, 8, 8, w, 64, t, lo, None, None) == B.MBU_ERR_ARG
     assert f(a, 64, lo + 4, 128, 1, 8, 8, w, 64, t, o, None, None) == B.MBU_ERR_ALIGN
@@ -87,6 +88,15 @@ def test_tconv_and_concat_argument_validation():
     assert g(a, 48, b, 64, 1, 8, 8, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
     assert g(a, 64, b, 64, 1, 8, 8, w, 64, t, b, None, None) == B.MBU_ERR_ARG
     assert g(a, 64, b, 0, 1, 8, 8, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
+    h = L.mbu_conv3x3_masked_binary_two_inputs
+    assert h(a, 64, None, 64, 4, 4, 1, 1, 9, 9, w, 64, t, o, None, None) == B.MBU_ERR_NULL
+    assert h(a, 64, b, 64, 5, 4, 1, 1, 9, 9, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE   # 2*5 > 9
+    assert h(a, 64, b, 64, 9, 10, 0, 1, 9, 9, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
+    assert h(a, 64, b, 64, 0, 4, 1, 1, 9, 9, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
+    assert h(a, 64, b, 64, 4, 4, 2, 1, 9, 9, w, 64, t, o, None, None) == B.MBU_ERR_ARG
+    assert h(a, 48, b, 64, 4, 4, 1, 1, 9, 9, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
+    assert h(a, 64, b, 64, 4, 4, 1, 1, 9, 9, w, 64, t, o, a + 64, None) == B.MBU_ERR_SHAPE  # pool, odd
+    assert h(a, 64, b, 64, 4, 4, 1, 1, 9, 9, w, 64, t, b, None, None) == B.MBU_ERR_ARG
 
 
 def test_unet_plan_with_transposed_decoder():
@@ -166,8 +176,33 @@ def test_unet_plan_validation_and_workspace():
         names.append(name.value.decode())
     assert n.value == expect
     assert names[:4] == ["stem", "enc1a", "enc1b", "pool1"] and names[15:19] == ["cat4", "dec4a", "dec4b", "cat3"]
-    # H not a multiple of 16
-    assert L.mbu_unet_workspace_bytes(ctypes.byref(d), 1, 72, 128, ctypes.byref(n)) == B.MBU_ERR_SHAPE
+    # sizes that are not multiples of 16: pooling rounds down, the decoder pads back up
+    assert L.mbu_unet_workspace_bytes(ctypes.byref(d), 1, 75, 131, ctypes.byref(n)) == 0
+    sizes = {}
+    for s in range(28):
+        name = ctypes.c_char_p()
+        h, w = ctypes.c_int(), ctypes.c_int()
+        assert L.mbu_unet_step_info(ctypes.byref(d), 1, 75, 131, s, ctypes.byref(name), None,
+                                    ctypes.byref(h), ctypes.byref(w), None) == 0
+        sizes[name.value.decode()] = (h.value, w.value)
+    assert sizes["pool1"] == (37, 65) and sizes["pool2"] == (18, 32) and sizes["pool4"] == (4, 8)
+    assert sizes["cat4"] == (9, 16) and sizes["cat2"] == (37, 65) and sizes["classifier"] == (75, 131)
+    assert L.mbu_unet_workspace_bytes(ctypes.byref(d), 1, 15, 128, ctypes.byref(n)) == B.MBU_ERR_SHAPE
+    # which kernel a step launches, and which steps launch none (no GPU needed: nothing runs)
+    d.fuse = 1
+    kern = {}
+    for s in range(28):
+        k = ctypes.c_char_p()
+        assert L.mbu_unet_step_kernel(ctypes.byref(d), 1, 1024, 2048, s, ctypes.byref(k)) == 0
+        kern[names[s] if s < 27 else "classifier"] = k.value.decode()
+    assert kern["stem"] == "stem_rows_kernel" and kern["classifier"].startswith("classifier_kernel")
+    assert kern["enc1a"] == "conv_mfma_rows_kernel" and kern["dec1a"] == "conv_mfma_upcat_kernel"
+    assert kern["enc4b"] == "conv_mfma_block_kernel" and kern["cat1"] == "" and kern["pool1"] == ""
+    k = ctypes.c_char_p()
+    assert L.mbu_unet_step_kernel(ctypes.byref(d), 1, 75, 131, 25, ctypes.byref(k)) == 0   # dec1a, padded
+    assert k.value.decode() == "conv_mfma_block_kernel"
+    assert L.mbu_unet_step_kernel(ctypes.byref(d), 1, 64, 128, 99, ctypes.byref(k)) == B.MBU_ERR_ARG
+    d.fuse = 0
     # inconsistent channel plan
     bad = [(ci, co) for _, ci, co, _ in plan]
     bad[10] = (1024, 512)

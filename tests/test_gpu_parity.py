@@ -445,8 +445,9 @@ def compare_unet_all_taps(case, N, H, W, fuse=True, images=None):
             name, _, h, w, c = net.step_info(N, H, W, s)
             ref = taps.pop(name)
             assert ref.shape == (1, h, w, c), name
-            if fused_away and name.startswith("cat"):
-                continue      # folded into the layer that reads it; never written
+            if name.startswith("cat") and (fused_away or (ref == 0).any()):
+                continue      # folded into the layer that reads it (always, when the up-sampled
+                              # part had to be zero-padded); never written
             got = host_u32(net.step_output(N, H, W, s)[n:n + 1])
             bad = int((got != pack(ref)).sum())
             assert bad == 0, f"image {n} step {s} ({name}): {bad} packed words differ"
@@ -598,6 +599,87 @@ def test_unet_wide_batch8_first_and_last_image_every_element():
     independent), and of image 7 the same (the last tiles of the persistent kernels' walk)."""
     say("unet wide batch 8 at 1024x1024 mean_zero=0.4, images 0 and 7 every element")
     compare_unet_all_taps(wide_case(0.4, 8, 1024, 1024), 8, 1024, 1024, True, images=(0, 7))
+
+
+# ------------------------------------------- frame sizes that are not multiples of 2^levels
+PADDED_SHAPES = [
+    # N, H, W, Ca, Cb, Cout, upsample
+    (1, 9, 13, 64, 64, 64, 0),        # b is 8 x 12: one row and one column of zeros
+    (2, 11, 35, 96, 160, 96, 0),      # odd word counts, ragged tiles, two images
+    (1, 8, 33, 32, 40, 64, 0),        # only the column is missing; a step straddles the sources
+    (1, 9, 13, 64, 128, 64, 1),       # nearest up-sampling of a 4 x 6 tensor to 8 x 12 of 9 x 13
+    (2, 7, 70, 64, 128, 128, 1),
+    (1, 37, 65, 128, 256, 64, 1),
+    (1, 16, 64, 64, 128, 64, 1),      # nothing missing: the general entry point on a full extent
+]
+
+
+@pytest.mark.parametrize("shape", PADDED_SHAPES)
+def test_two_input_layer_with_padded_second_input(shape):
+    """Decoder layer of a frame whose size is not a multiple of 2^levels (Appendix A.3): the
+    second input covers the top left of the frame, the rest of its channels are zeros."""
+    N, H, W, Ca, Cb, Cout, ups = shape
+    say(f"conv two inputs N={N} H={H} W={W} Ca={Ca} Cb={Cb} Cout={Cout} upsample={ups}")
+    rng = np.random.default_rng(Ca + Cb + H + W)
+    Hb, Wb = (H // 2, W // 2) if ups else (H - (H & 1), W - (W & 1))
+    a = synth.pm1_bits(rng, (N, H, W, Ca))
+    b = synth.pm1_bits(rng, (N, Hb, Wb, Cb))
+    w = synth.ternary_weights(14, 0, 0, Cout, Ca + Cb, 0.6)
+    th = synth.thresholds(14, 0, 0, Cout, (9 * (Ca + Cb)) // 16)
+    bb = O.upsample2x(b) if ups else b
+    x = O.concat(a, O.zero_pad_to(bb, H, W))
+    _, out_ref = O.masked_binary_layer(x, w, th)
+    bits, _ = B.conv3x3_masked_binary_two_inputs(B.pack_act(dev(a)), Ca, B.pack_act(dev(b)), Cb, bool(ups),
+                                                 B.pack_weights(dev(w)), Cout, dev(th))
+    torch.cuda.synchronize()
+    assert np.array_equal(host_u32(bits), bitref.pack_pm1(out_ref))
+    if ups:
+        # the fused entry point takes the same layer for odd sizes (low = floor(H/2) x floor(W/2))
+        bits2, _ = B.conv3x3_masked_binary_fused(B.pack_act(dev(a)), Ca, B.pack_act(dev(b)), Cb,
+                                                 B.pack_weights(dev(w)), Cout, dev(th), True, False)
+        torch.cuda.synchronize()
+        assert np.array_equal(host_u32(bits2), bitref.pack_pm1(out_ref))
+
+
+@pytest.mark.parametrize("C", [32, 64, 96, 40])
+def test_pool_rounds_odd_sizes_down(C):
+    say(f"pool odd sizes C={C}")
+    rng = np.random.default_rng(C + 1)
+    for H, W in ((7, 9), (6, 9), (7, 8), (3, 2)):
+        a = synth.pm1_bits(rng, (2, H, W, C))
+        got = host_u32(B.maxpool2x2_bits(B.pack_act(dev(a)), C))
+        assert np.array_equal(got, bitref.pack_pm1(O.maxpool2x2(a)))
+
+
+@pytest.mark.parametrize("fuse", [True, False])
+@pytest.mark.parametrize("transposed", [False, True])
+def test_unet_odd_frame_sizes_small_all_layers(transposed, fuse):
+    say(f"unet odd sizes transposed={transposed} fuse={fuse}")
+    case = synth.unet_case(13, 0, 2, 37, 51, base=32, levels=2, n_classes=2, transposed=transposed)
+    compare_unet_all_taps(case, 2, 37, 51, fuse)
+    case = synth.unet_case(13, 1, 1, 75, 131, base=64, levels=4, n_classes=19, transposed=transposed)
+    compare_unet_all_taps(case, 1, 75, 131, fuse)
+    case = synth.unet_case(13, 2, 1, 70, 100, base=64, levels=3, n_classes=2, transposed=transposed)
+    compare_unet_all_taps(case, 1, 70, 100, fuse)
+
+
+def test_unet_odd_frame_sizes_are_refused_on_the_vector_path():
+    say("unet odd sizes valu path")
+    case = synth.unet_case(13, 0, 1, 37, 51, base=32, levels=2, n_classes=2)
+    B.set_conv_path(B.PATH_VALU)
+    net = build_unet(case, True)
+    with pytest.raises(B.MbuError) as e:
+        net.forward(dev(case.image))
+    assert e.value.code == B.MBU_ERR_SHAPE
+
+
+def test_unet_paper_frame_640x959_every_element():
+    """The paper's Carvana frame (Appendix A.3: 959 wide, 640 high), network with the paper's
+    transposed decoder and two classes, synthetic data: every element of every layer and every
+    logit against the oracle."""
+    say("unet 640x959 transposed decoder, 2 classes, every element")
+    case = synth.unet_case(7, 0, 1, 640, 959, keep=0.6, transposed=True, n_classes=2)
+    compare_unet_all_taps(case, 1, 640, 959, True)
 
 
 # ------------------------------------------------------------------------ float32 ends
