@@ -354,6 +354,24 @@ int mbu_unet_forward(const mbu_unet_desc *d, const float *image_nchw, int N, int
                      float *logits_nchw, void *workspace, size_t workspace_bytes,
                      void *stream);
 
+/* For callers that can neither allocate device memory nor bring a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): mbu_unet_forward with
+ * the workspace inside the library - a fixed device array of MBU_STATIC_WORKSPACE_BYTES that
+ * every GPU the library runs on holds until the process ends.  Allocates nothing, frees
+ * nothing, synchronises nothing; the caller still owns image and logits.  The device that owns
+ * `stream`, the image and the logits must be the current device.
+ *   MBU_ERR_WORKSPACE  the shape needs more than MBU_STATIC_WORKSPACE_BYTES
+ *                      (mbu_unet_workspace_bytes tells; 1 x 3 x 512 x 512 with base 64 and four
+ *                      levels fits, the 1024 x 2048 frame does not)
+ *   other errors       as for mbu_unet_forward
+ * All calls on one GPU share that GPU's array: two calls that overlap in time on one GPU
+ * (different streams or threads) race and give wrong results; calls on one stream are safe.
+ * Intermediate activations cannot be inspected (mbu_unet_step_info offsets refer to a caller
+ * workspace); step events in the descriptor work as usual. */
+#define MBU_STATIC_WORKSPACE_BYTES (32u << 20)
+int mbu_unet_forward_static(const mbu_unet_desc *d, const float *image_nchw, int N, int H, int W,
+                            float *logits_nchw, void *stream);
+
 /* Thin helpers over HIP events so that a caller without HIP headers (the Python
  * binding) can time work on the stream the kernels were launched on.  Events are
  * host handles.  mbu_event_elapsed_ms synchronises on `stop`. */

@@ -18,6 +18,7 @@ MBU_OK = 0
 MBU_ERR_NULL, MBU_ERR_SHAPE, MBU_ERR_ALIGN, MBU_ERR_WORKSPACE, MBU_ERR_HIP, MBU_ERR_ARG = -1, -2, -3, -4, -5, -6
 PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
 STEM_AUTO, STEM_VALU, STEM_MFMA, STEM_MFMA_GATHER = 0, 1, 2, 3
+STATIC_WORKSPACE_BYTES = 32 << 20
 
 EXPORTS = [
     "mbu_last_error", "mbu_set_conv_path", "mbu_get_conv_path", "mbu_set_conv_tuning", "mbu_pack_act",
@@ -29,6 +30,7 @@ EXPORTS = [
     "mbu_packed_tconv_weights_bytes", "mbu_pack_tconv_weights", "mbu_tconv2x2_masked_binary",
     "mbu_maxpool2x2_bits", "mbu_upsample2x_bits", "mbu_concat_bits", "mbu_unet_num_steps",
     "mbu_unet_step_info", "mbu_unet_step_launches", "mbu_unet_workspace_bytes", "mbu_unet_forward",
+    "mbu_unet_forward_static",
     "mbu_event_create", "mbu_event_destroy", "mbu_event_record", "mbu_event_elapsed_ms",
 ]
 
@@ -98,6 +100,7 @@ def lib() -> ctypes.CDLL:
                                                ctypes.POINTER(ctypes.c_size_t)]
         L.mbu_unet_forward.argtypes = [ctypes.POINTER(UNetDesc), vp, ci, ci, ci, vp, vp,
                                        ctypes.c_size_t, vp]
+        L.mbu_unet_forward_static.argtypes = [ctypes.POINTER(UNetDesc), vp, ci, ci, ci, vp, vp]
         L.mbu_event_create.argtypes = [ctypes.POINTER(vp)]
         L.mbu_event_destroy.argtypes = [vp]
         L.mbu_event_record.argtypes = [vp, vp]
@@ -499,6 +502,16 @@ class UNet:
         check(lib().mbu_unet_forward(ctypes.byref(self.desc), _dev(image, (torch.float32,)), N, H, W,
                                      logits.data_ptr(), self.workspace.data_ptr(),
                                      self.workspace.numel(), _stream()))
+        return logits
+
+    def forward_static(self, image: torch.Tensor, logits: torch.Tensor) -> torch.Tensor:
+        """mbu_unet_forward_static: the forward pass on the library's own fixed workspace.
+        Nothing is allocated here either: the caller passes the logits tensor."""
+        N, Ci, H, W = image.shape
+        if tuple(logits.shape) != (N, self.n_classes, H, W):
+            raise ValueError("logits must be [N, n_classes, H, W]")
+        check(lib().mbu_unet_forward_static(ctypes.byref(self.desc), _dev(image, (torch.float32,)),
+                                            N, H, W, _dev(logits, (torch.float32,)), _stream()))
         return logits
 
     def step_output(self, N: int, H: int, W: int, step: int) -> torch.Tensor:

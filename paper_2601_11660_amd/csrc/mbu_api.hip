@@ -6,6 +6,11 @@
 #include <vector>
 #include "mbu_internal.h"
 
+// Workspace of mbu_unet_forward_static: device memory that belongs to the loaded library, one
+// copy per GPU, held until the process ends.  In host code this name only stands for the
+// symbol; the device address is looked up once per device (static_workspace()).
+static __device__ __align__(256) unsigned char scratch[MBU_STATIC_WORKSPACE_BYTES];
+
 namespace mbu {
 
 static thread_local char g_err[512] = "";
@@ -708,9 +713,50 @@ static int check_forward(const char *fn, const mbu_unet_desc *d, const float *im
     return MBU_OK;
 }
 
+// Device address of `scratch` on the current device, looked up on the first call per device
+// (with that device current) and kept; every GPU has its own copy at its own address.
+static int static_workspace(const char *fn, void **ptr)
+{
+    static std::atomic<void *> addr[64];
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(MBU_ERR_HIP, "%s: hipGetDevice: %s", fn, hipGetErrorString(e));
+    if (dev < 0 || dev >= 64) return fail(MBU_ERR_HIP, "%s: device index %d not supported", fn, dev);
+    void *p = addr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p)
+            return fail(MBU_ERR_HIP, "%s: hipGetSymbolAddress: %s", fn, hipGetErrorString(e));
+        addr[dev].store(p, std::memory_order_release);   // racing threads store the same address
+    }
+    *ptr = p;
+    return MBU_OK;
+}
+
 }  // namespace mbu
 
 extern "C" {
+
+int mbu_unet_forward_static(const mbu_unet_desc *d, const float *image_nchw, int N, int H, int W,
+                            float *logits_nchw, void *stream)
+{
+    const char *fn = "mbu_unet_forward_static";
+    begin_call();
+    std::vector<Step> steps;
+    size_t need = 0;
+    int rc = check_forward(fn, d, image_nchw, N, H, W, logits_nchw, steps, &need);
+    if (rc) return rc;
+    if (need > (size_t)MBU_STATIC_WORKSPACE_BYTES)
+        return fail(MBU_ERR_WORKSPACE, "%s: this shape needs %zu bytes of workspace, the library's own "
+                    "holds %zu; use mbu_unet_forward with a caller workspace", fn, need,
+                    (size_t)MBU_STATIC_WORKSPACE_BYTES);
+    void *ws = nullptr;
+    rc = static_workspace(fn, &ws);
+    if (rc) return rc;
+    // every region of the workspace is written by the step that owns it before a later step
+    // reads it, so nothing has to be cleared between calls
+    return walk(d, steps, image_nchw, N, H, W, logits_nchw, (uint8_t *)ws, (hipStream_t)stream, nullptr);
+}
 
 int mbu_unet_step_kernel(const mbu_unet_desc *d, int N, int H, int W, int step, const char **kernel)
 {
