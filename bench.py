@@ -229,8 +229,16 @@ def transposed_decoder(B, torch, synth, steps):
         name, _, hh, ww, c = net.step_info(n, h, w, s_)
         if name.startswith("up"):
             macs = n * hh * ww * (2 * c) * c          # one tap per output pixel
-            ups.append({"step": name, "cin": 2 * c, "cout": c, "hw_out": [hh, ww],
-                        "ms": round(t, 4), "eff_tops": round(2.0 * macs / t / 1e9, 1)})
+            nbytes = n * (hh // 2) * (ww // 2) * (2 * c) / 8.0 + n * hh * ww * c / 8.0
+            ups.append({"step": name, "kernel": net.step_kernel(n, h, w, s_), "cin": 2 * c, "cout": c,
+                        "hw_out": [hh, ww], "ms_raw_event": round(t, 4),
+                        "eff_tops": round(2.0 * macs / t / 1e9, 1),
+                        "frac_of_fp4_peak": round(2.0 * macs / t / 1e9 / PEAK_FP4_TFLOPS, 4),
+                        "hbm_gbs": round(nbytes / t / 1e6, 1),
+                        "hbm_frac": round(nbytes / t / 1e6 / PEAK_HBM_GBS, 4),
+                        "bound": "alu (one tap per output pixel: expansion of the packed words and "
+                                 "sign collection outweigh the matrix instructions; neither the "
+                                 "matrix nor the HBM roofline is near)"})
     conv_macs = synth.unet_conv_macs(case.plan, n, h, w)
     return {"frames_per_s": round(1e3 / ms, 1), "ms_per_step": round(ms, 4),
             "conv3x3_macs_per_frame": conv_macs, "transposed_layers": ups}

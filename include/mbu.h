@@ -107,6 +107,26 @@ int mbu_packed_weights_bytes(int Cout, int Cin, size_t *bytes);
 int mbu_pack_weights(const int8_t *w_ohwi, int Cout, int Cin, void *packed,
                      void *stream);
 
+/* The same with only the blob sections that will be read (Sec. 3.2.1 stores masked weights as
+ * two bit planes; the matrix path needs its 4-bit fragments instead, and the 2x2 kernels of
+ * summed taps only for layers whose second input arrives 2x up-sampled):
+ *   MBU_BLOB_MATRIX       the 4-bit fragments and per-channel sums (always written)
+ *   MBU_BLOB_BIT_PLANES   the two bit planes: read by the vector-ALU path (MBU_PATH_VALU)
+ *   MBU_BLOB_SUMMED_TAPS  read by mbu_conv3x3_masked_binary_fused / _two_inputs with an
+ *                         up-sampled second input and by such decoder layers of the network;
+ *                         without it those calls still work, at the 9-tap cost
+ * mbu_pack_weights = MBU_BLOB_ALL.  A blob with fewer sections is smaller (the summed taps are
+ * 1.8x the fragments) and is only valid where its `sections` value travels with it: the
+ * single-layer entry points assume MBU_BLOB_ALL; the network takes it per layer in
+ * mbu_conv_layer.  MBU_ERR_ARG on unknown bits. */
+#define MBU_BLOB_BIT_PLANES 1
+#define MBU_BLOB_SUMMED_TAPS 2
+#define MBU_BLOB_MATRIX 4
+#define MBU_BLOB_ALL 7
+int mbu_packed_weights_bytes_sections(int Cout, int Cin, int sections, size_t *bytes);
+int mbu_pack_weights_sections(const int8_t *w_ohwi, int Cout, int Cin, int sections, void *packed,
+                              void *stream);
+
 /* Masked-binary 3x3 convolution, stride 1, padding 1, with the fused threshold /
  * sign / bit-pack epilogue (Algorithm 1; layer definition in Sec. 3.1.1).
  *   acc[n,y,x,o] = sum_{ky,kx,c} w[o,ky,kx,c] * a[n,y+ky-1,x+kx-1,c]
@@ -229,7 +249,7 @@ int mbu_get_stem_path(void);
  *   out_bits    packed [N][H][W][Co/32]
  *   out_pre     float32 NHWC [N][H][W][Co] or NULL (parity / debugging).  On the VALU path
  *               (and with MBU_STEM_AUTO) these are the chain's values y.  With MBU_STEM_MFMA
- *               they are the matrix-core estimates, within 2^-18 * ||w_o||_2 * ||patch||_2
+ *               they are the matrix-core estimates, within 2^-17 * ||w_o||_2 * ||patch||_2
  *               of y, except for the recomputed outputs, which are y itself.
  * Errors: NULL / misaligned pointers, bad shapes. */
 int mbu_stem_fp32(const float *image_nchw, int N, int Ci, int H, int W, const float *w, int Co,
@@ -271,6 +291,8 @@ typedef struct mbu_conv_layer {
     const int32_t *thresh;   /* int32 [cout]                           */
     int cin;
     int cout;
+    int sections;            /* MBU_BLOB_* bits the blob was packed with; 0 = all of them
+                                (mbu_pack_weights).  Ignored for transposed layers.       */
 } mbu_conv_layer;
 
 /* Network descriptor (host struct).  The network is: float32 3x3 stem

@@ -19,12 +19,14 @@ MBU_ERR_NULL, MBU_ERR_SHAPE, MBU_ERR_ALIGN, MBU_ERR_WORKSPACE, MBU_ERR_HIP, MBU_
 PATH_AUTO, PATH_VALU, PATH_MFMA = 0, 1, 2
 STEM_AUTO, STEM_VALU, STEM_MFMA, STEM_MFMA_GATHER = 0, 1, 2, 3
 STATIC_WORKSPACE_BYTES = 32 << 20
+BLOB_BIT_PLANES, BLOB_SUMMED_TAPS, BLOB_MATRIX, BLOB_ALL = 1, 2, 4, 7
 
 EXPORTS = [
     "mbu_last_error", "mbu_set_conv_path", "mbu_get_conv_path", "mbu_set_conv_tuning", "mbu_pack_act",
     "mbu_set_stem_path", "mbu_get_stem_path", "mbu_stem_fp32", "mbu_classifier_fp32",
     "mbu_fold_batchnorm", "mbu_cost_rank",
     "mbu_packed_weights_bytes", "mbu_pack_weights", "mbu_conv3x3_masked_binary",
+    "mbu_packed_weights_bytes_sections", "mbu_pack_weights_sections",
     "mbu_conv3x3_masked_binary_fused", "mbu_conv3x3_masked_binary_concat",
     "mbu_conv3x3_masked_binary_two_inputs", "mbu_unet_step_kernel",
     "mbu_packed_tconv_weights_bytes", "mbu_pack_tconv_weights", "mbu_tconv2x2_masked_binary",
@@ -43,7 +45,7 @@ class MbuError(RuntimeError):
 
 class ConvLayer(ctypes.Structure):
     _fields_ = [("packed_w", ctypes.c_void_p), ("thresh", ctypes.c_void_p),
-                ("cin", ctypes.c_int), ("cout", ctypes.c_int)]
+                ("cin", ctypes.c_int), ("cout", ctypes.c_int), ("sections", ctypes.c_int)]
 
 
 class UNetDesc(ctypes.Structure):
@@ -71,6 +73,8 @@ def lib() -> ctypes.CDLL:
         L.mbu_pack_act.argtypes = [vp, ci, ci, ci, ci, ci, vp, vp]
         L.mbu_packed_weights_bytes.argtypes = [ci, ci, ctypes.POINTER(ctypes.c_size_t)]
         L.mbu_pack_weights.argtypes = [vp, ci, ci, vp, vp]
+        L.mbu_packed_weights_bytes_sections.argtypes = [ci, ci, ci, ctypes.POINTER(ctypes.c_size_t)]
+        L.mbu_pack_weights_sections.argtypes = [vp, ci, ci, ci, vp, vp]
         L.mbu_conv3x3_masked_binary.argtypes = [vp, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp]
         L.mbu_conv3x3_masked_binary_fused.argtypes = [vp, ci, vp, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp]
         L.mbu_conv3x3_masked_binary_concat.argtypes = [vp, ci, vp, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp]
@@ -226,18 +230,20 @@ def pack_act(x: torch.Tensor) -> torch.Tensor:
     return out
 
 
-def packed_weights_bytes(cout: int, cin: int) -> int:
+def packed_weights_bytes(cout: int, cin: int, sections: int = BLOB_ALL) -> int:
     n = ctypes.c_size_t(0)
-    check(lib().mbu_packed_weights_bytes(cout, cin, ctypes.byref(n)))
+    check(lib().mbu_packed_weights_bytes_sections(cout, cin, sections, ctypes.byref(n)))
     return n.value
 
 
-def pack_weights(w_ohwi: torch.Tensor) -> torch.Tensor:
-    """mbu_pack_weights: device int8 [Cout,3,3,Cin] in {-1,0,+1} -> opaque blob (uint8 tensor)."""
+def pack_weights(w_ohwi: torch.Tensor, sections: int = BLOB_ALL) -> torch.Tensor:
+    """mbu_pack_weights(_sections): device int8 [Cout,3,3,Cin] in {-1,0,+1} -> opaque blob
+    (uint8 tensor) holding the given sections."""
     cout, kh, kw, cin = w_ohwi.shape
     assert kh == 3 and kw == 3
-    blob = torch.empty(packed_weights_bytes(cout, cin), dtype=torch.uint8, device=w_ohwi.device)
-    check(lib().mbu_pack_weights(_dev(w_ohwi, (torch.int8,)), cout, cin, blob.data_ptr(), _stream()))
+    blob = torch.empty(packed_weights_bytes(cout, cin, sections), dtype=torch.uint8, device=w_ohwi.device)
+    check(lib().mbu_pack_weights_sections(_dev(w_ohwi, (torch.int8,)), cout, cin, sections,
+                                          blob.data_ptr(), _stream()))
     return blob
 
 
@@ -394,9 +400,13 @@ class UNet:
 
     def __init__(self, stem_w: torch.Tensor, convs: Sequence[Tuple[torch.Tensor, torch.Tensor]],
                  cls_w: torch.Tensor, cls_b: torch.Tensor, levels: int = 4, fuse: bool = True,
-                 up_convs: Optional[Sequence[Tuple[torch.Tensor, torch.Tensor]]] = None):
+                 up_convs: Optional[Sequence[Tuple[torch.Tensor, torch.Tensor]]] = None,
+                 all_sections: bool = False):
         """stem_w float32 [base,3,3,Ci]; convs: (w int8 OHWI, theta int32) device tensors in
-        execution order; cls_w float32 [K,base]; cls_b float32 [K]."""
+        execution order; cls_w float32 [K,base]; cls_b float32 [K].  Every layer's blob holds
+        only the sections its place in the network reads (the bit planes when the vector-ALU
+        path is selected at construction, the summed taps for the first layer of a decoder level
+        that up-samples nearest-neighbour) unless all_sections is set."""
         self.levels = levels
         self.base = stem_w.shape[0]
         self.in_channels = stem_w.shape[3]
@@ -407,8 +417,14 @@ class UNet:
         self.blobs: List[torch.Tensor] = []
         self.thetas: List[torch.Tensor] = []
         self.shapes: List[Tuple[int, int]] = []
-        for w, th in convs:
-            self.blobs.append(pack_weights(w.contiguous()))
+        self.sections: List[int] = []
+        planes = BLOB_BIT_PLANES if get_conv_path() == PATH_VALU else 0
+        for i, (w, th) in enumerate(convs):
+            first_of_decoder_level = i >= 2 * levels + 2 and i % 2 == 0
+            sec = BLOB_ALL if all_sections else (
+                BLOB_MATRIX | planes | (BLOB_SUMMED_TAPS if first_of_decoder_level and up_convs is None else 0))
+            self.sections.append(sec)
+            self.blobs.append(pack_weights(w.contiguous(), sec))
             self.thetas.append(th.contiguous())
             self.shapes.append((w.shape[3], w.shape[0]))
         n = len(self.blobs)
@@ -417,6 +433,7 @@ class UNet:
             self._layers[i].packed_w = self.blobs[i].data_ptr()
             self._layers[i].thresh = self.thetas[i].data_ptr()
             self._layers[i].cin, self._layers[i].cout = self.shapes[i]
+            self._layers[i].sections = self.sections[i]
         self._up_layers = None
         self.up_blobs: List[torch.Tensor] = []
         self.up_thetas: List[torch.Tensor] = []

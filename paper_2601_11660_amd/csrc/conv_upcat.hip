@@ -395,7 +395,7 @@ bool conv_upcat_supported(int Ca, int Clow, int N, int H, int W, const BlobLayou
                           const uint32_t *out_pool)
 {
     const double lim = 1073741824.0;   // byte offsets are computed in 32 bits
-    return out_bits && !out_pool && Ca > 0 && Clow > 0 && Ca % 64 == 0 && Clow % 128 == 0 && !(H & 1) && !(W & 1) &&
+    return (L.sections & MBU_BLOB_SUMMED_TAPS) && out_bits && !out_pool && Ca > 0 && Clow > 0 && Ca % 64 == 0 && Clow % 128 == 0 && !(H & 1) && !(W & 1) &&
            (double)N * H * W * (Ca / 32) * 4 < lim && (double)N * (H / 2) * (W / 2) * (Clow / 32) * 4 < lim &&
            (double)L.ksteps * 32 * 1024 < lim;
 }

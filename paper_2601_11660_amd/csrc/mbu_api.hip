@@ -47,22 +47,24 @@ int check_launch(const char *what)
     return MBU_OK;
 }
 
-BlobLayout blob_layout(int cout, int cin)
+BlobLayout blob_layout(int cout, int cin, int sections)
 {
     BlobLayout L;
     L.cout = cout;
     L.cin = cin;
+    L.sections = sections;
     L.cin_words = ceil_div(cin, 32);
     L.cout_pad64 = ceil_div(cout, 64) * 64;
     L.ksteps = ceil_div(cin, 64);
     L.cout_tiles32 = L.cout_pad64 / 32;
-    size_t plane = (size_t)9 * L.cin_words * L.cout_pad64 * sizeof(uint32_t);
+    size_t plane = (sections & MBU_BLOB_BIT_PLANES) ? (size_t)9 * L.cin_words * L.cout_pad64 * sizeof(uint32_t) : 0;
     size_t off = 256;  // reserved header room
     L.off_pos = off; off = round_up(off + plane, 256);
     L.off_neg = off; off = round_up(off + plane, 256);
     L.off_cnt = off; off = round_up(off + (size_t)11 * L.cout_pad64 * sizeof(int32_t), 256);
     L.off_f4 = off;  off = round_up(off + (size_t)L.cout_tiles32 * 9 * L.ksteps * 64 * 16, 256);
-    L.off_up = off;  off = round_up(off + (size_t)(L.cout_pad64 / 64) * L.ksteps * 32 * 64 * 16, 256);
+    L.off_up = off;
+    if (sections & MBU_BLOB_SUMMED_TAPS) off = round_up(off + (size_t)(L.cout_pad64 / 64) * L.ksteps * 32 * 64 * 16, 256);
     L.total = off;
     return L;
 }
@@ -81,6 +83,12 @@ static int check_dims4(const char *fn, int N, int H, int W, int C)
         if ((p) == nullptr) return mbu::fail(MBU_ERR_NULL, "%s: %s is NULL", fn, #p); \
         if (!mbu::aligned16(p)) return mbu::fail(MBU_ERR_ALIGN, "%s: %s is not 16-byte aligned", fn, #p); \
     } while (0)
+
+// layout of a network layer's blob: `sections` 0 means a blob from mbu_pack_weights (everything)
+static BlobLayout layer_layout(const mbu_conv_layer &L)
+{
+    return blob_layout(L.cout, L.cin, L.sections ? L.sections : MBU_BLOB_ALL);
+}
 
 // ------------------------------------------------------------------ network plan
 struct Step {
@@ -131,6 +139,7 @@ static int build_plan(const mbu_unet_desc *d, int N, int H, int W, std::vector<S
         const mbu_conv_layer &L = d->convs[ci];
         if (L.cin != cin) return -1 - ci;
         if (L.cout <= 0 || L.cout % 32) return -1 - ci;
+        if (L.sections & ~MBU_BLOB_ALL) return -1 - ci;
         return push(Step::CONV, name, ci++, in, -1, h, w, L.cout);
     };
     int h = H, w = W;
@@ -200,7 +209,7 @@ static bool step_launches(const mbu_unet_desc *d, const std::vector<Step> &steps
     if (st.kind == Step::POOL) {
         const Step &in = steps[st.in];
         return !(in.kind == Step::CONV &&
-                 conv_writes_pooled(in.h, in.w, blob_layout(d->convs[in.conv].cout, d->convs[in.conv].cin)));
+                 conv_writes_pooled(in.h, in.w, layer_layout(d->convs[in.conv])));
     }
     return true;
 }
@@ -219,15 +228,16 @@ static const char *kernel_base_name(const char *written)
     return name;
 }
 
-static int run_conv(const uint32_t *act, int N, int H, int W, int Cin, const void *packed_w,
-                    int Cout, const int32_t *thresh, uint32_t *out_bits, int32_t *out_acc,
-                    hipStream_t s)
+static int run_conv(const uint32_t *act, int N, int H, int W, const BlobLayout &L, const void *packed_w,
+                    const int32_t *thresh, uint32_t *out_bits, int32_t *out_acc, hipStream_t s)
 {
-    BlobLayout L = blob_layout(Cout, Cin);
     int path = t_cfg.conv_path;
     if (path == MBU_PATH_AUTO) path = MBU_PATH_MFMA;
-    if (path == MBU_PATH_VALU)
+    if (path == MBU_PATH_VALU) {
+        if (!(L.sections & MBU_BLOB_BIT_PLANES))
+            return fail(MBU_ERR_ARG, "the vector-ALU path needs a blob packed with MBU_BLOB_BIT_PLANES");
         return launch_conv_valu(act, N, H, W, L, packed_w, thresh, out_bits, out_acc, s);
+    }
     return launch_conv_mfma(act, N, H, W, L, packed_w, thresh, out_bits, out_acc, s);
 }
 
@@ -335,14 +345,31 @@ int mbu_packed_weights_bytes(int Cout, int Cin, size_t *bytes)
 
 int mbu_pack_weights(const int8_t *w_ohwi, int Cout, int Cin, void *packed, void *stream)
 {
+    return mbu_pack_weights_sections(w_ohwi, Cout, Cin, MBU_BLOB_ALL, packed, stream);
+}
+
+int mbu_packed_weights_bytes_sections(int Cout, int Cin, int sections, size_t *bytes)
+{
+    const char *fn = "mbu_packed_weights_bytes_sections";
+    if (sections & ~MBU_BLOB_ALL) return fail(MBU_ERR_ARG, "%s: unknown section bits 0x%x", fn, sections);
+    int rc = mbu_packed_weights_bytes(Cout, Cin, bytes);
+    if (rc) return rc;
+    *bytes = blob_layout(Cout, Cin, sections | MBU_BLOB_MATRIX).total;
+    return MBU_OK;
+}
+
+int mbu_pack_weights_sections(const int8_t *w_ohwi, int Cout, int Cin, int sections, void *packed,
+                              void *stream)
+{
     const char *fn = "mbu_pack_weights";
     begin_call();
     MBU_REQ_PTR(fn, w_ohwi);
     MBU_REQ_PTR(fn, packed);
     size_t bytes;
-    int rc = mbu_packed_weights_bytes(Cout, Cin, &bytes);
+    int rc = mbu_packed_weights_bytes_sections(Cout, Cin, sections, &bytes);
     if (rc) return rc;
-    return launch_pack_weights(w_ohwi, blob_layout(Cout, Cin), packed, (hipStream_t)stream);
+    return launch_pack_weights(w_ohwi, blob_layout(Cout, Cin, sections | MBU_BLOB_MATRIX), packed,
+                               (hipStream_t)stream);
 }
 
 int mbu_conv3x3_masked_binary(const uint32_t *act, int N, int H, int W, int Cin,
@@ -365,7 +392,7 @@ int mbu_conv3x3_masked_binary(const uint32_t *act, int N, int H, int W, int Cin,
     if (Cout > 65536 || Cin > 65536) return fail(MBU_ERR_SHAPE, "%s: channel count too large", fn);
     rc = check_dims4(fn, N, H, W, Cout);
     if (rc) return rc;
-    return run_conv(act, N, H, W, Cin, packed_w, Cout, thresh, out_bits, out_acc, (hipStream_t)stream);
+    return run_conv(act, N, H, W, blob_layout(Cout, Cin), packed_w, thresh, out_bits, out_acc, (hipStream_t)stream);
 }
 
 int mbu_conv3x3_masked_binary_fused(const uint32_t *act, int Ca, const uint32_t *low, int Clow,
@@ -636,7 +663,7 @@ static int walk(const mbu_unet_desc *d, const std::vector<Step> &steps, const fl
             const bool cat_in = in.kind == Step::UPCAT || in.kind == Step::CAT;
             const bool from_cat = cat_in && (fuse || cat_needs_padding(steps, in));
             const bool next_pool = fuse && i + 1 < steps.size() && steps[i + 1].kind == Step::POOL &&
-                                   conv_writes_pooled(st.h, st.w, blob_layout(L.cout, L.cin));
+                                   conv_writes_pooled(st.h, st.w, layer_layout(L));
             if (from_cat || next_pool) {
                 const uint32_t *a = from_cat ? buf(in.in) : buf(st.in);
                 const int ca = from_cat ? steps[in.in].c : L.cin;
@@ -644,10 +671,10 @@ static int walk(const mbu_unet_desc *d, const std::vector<Step> &steps, const fl
                 const int clo = from_cat ? steps[in.in2].c : 0;
                 const int hb = from_cat ? steps[in.in2].h : 0, wb = from_cat ? steps[in.in2].w : 0;
                 rc = launch_conv_mfma_two(a, ca, lo, clo, in.kind == Step::UPCAT ? 1 : 0, hb, wb, N, st.h, st.w,
-                                          blob_layout(L.cout, L.cin), L.packed_w, L.thresh,
+                                          layer_layout(L), L.packed_w, L.thresh,
                                           buf((int)i), next_pool ? buf((int)i + 1) : nullptr, s);
             } else {
-                rc = run_conv(buf(st.in), N, st.h, st.w, L.cin, L.packed_w, L.cout, L.thresh,
+                rc = run_conv(buf(st.in), N, st.h, st.w, layer_layout(L), L.packed_w, L.thresh,
                               buf((int)i), nullptr, s);
             }
             break;

@@ -43,25 +43,27 @@ inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 inline size_t round_up(size_t v, size_t m) { return (v + m - 1) / m * m; }
 
 // ---- layout of the packed-weight blob (all offsets in bytes from the blob start) ----
-// Section V (vector-ALU path): two bit planes, each uint32 [9][cin_words][cout_pad64]
-// (tap-major, output channel fastest so 64 lanes read 64 consecutive words), and the
-// kept-weight counts int32 [11][cout_pad64]: rows 0..8 per tap, row 9 the total, row 10 the
-// sum of the channel's weights.
+// Section V (vector-ALU path, optional: MBU_BLOB_BIT_PLANES): two bit planes, each uint32
+// [9][cin_words][cout_pad64] (tap-major, output channel fastest so 64 lanes read 64
+// consecutive words).  Always present: the kept-weight counts int32 [11][cout_pad64]: rows
+// 0..8 per tap, row 9 the total, row 10 the sum of the channel's weights.
 // Section M (matrix-core path): 4-bit codes, uint4 [cout_pad64/64][ksteps][9 taps][2][64 lanes],
 // one 16-byte fragment per lane and (32 output channels, tap, 64 input channels); the 18
 // fragments one wave needs for a 64-channel step are contiguous (18 KB).
-// Section U (matrix-core path, input channels that arrive 2x up-sampled): the 3x3 kernel summed
+// Section U (matrix-core path, optional: MBU_BLOB_SUMMED_TAPS; input channels that arrive 2x
+// up-sampled): the 3x3 kernel summed
 // over the taps that share a low-resolution pixel, 4-bit codes of sums in -4..4,
 // uint4 [cout_pad64/64][ksteps][4 parity classes][2][2][2][64 lanes].
 struct BlobLayout {
     int cout, cin;
+    int sections;      // MBU_BLOB_* bits: which optional sections the blob holds (absent = size 0)
     int cin_words;     // ceil(cin/32)
     int cout_pad64;    // cout rounded up to 64
     int ksteps;        // ceil(cin/64): 64-channel steps of the matrix path
     int cout_tiles32;  // cout/32
     size_t off_pos, off_neg, off_cnt, off_f4, off_up, total;
 };
-BlobLayout blob_layout(int cout, int cin);
+BlobLayout blob_layout(int cout, int cin, int sections = MBU_BLOB_ALL);
 
 // ---- packed blob of the transposed 2x2 stride-2 layer: 4-bit codes only,
 // uint4 [cout_pad64/64][ksteps][4 positions][2][64 lanes] after 256 bytes of header room

@@ -93,7 +93,7 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const int8_t *__restr
             neg |= (uint32_t)(v < 0) << i;
         }
     }
-    if (k < L.cin_words) {
+    if (k < L.cin_words && (L.sections & MBU_BLOB_BIT_PLANES)) {
         uint32_t *P = reinterpret_cast<uint32_t *>(blob + L.off_pos);
         uint32_t *G = reinterpret_cast<uint32_t *>(blob + L.off_neg);
         size_t at = ((size_t)tap * L.cin_words + k) * L.cout_pad64 + o;
@@ -124,26 +124,35 @@ __global__ __launch_bounds__(256) void pack_weights_kernel(const int8_t *__restr
 }
 
 // Kept-weight counts per (tap, output channel), their total, and the sum of the weights of
-// an output channel (row 10; the matrix path's activations are 0 / 1, see conv_mfma.hip),
-// from the planes.
-__global__ __launch_bounds__(256) void count_kept_kernel(BlobLayout L, uint8_t *__restrict__ blob)
+// an output channel (row 10; the matrix path's activations are 0 / 1, see conv_mfma.hip).
+// One wave per output channel: the lanes stride over the input channels of a tap.
+__global__ __launch_bounds__(256) void count_kept_kernel(const int8_t *__restrict__ w, BlobLayout L,
+                                                         uint8_t *__restrict__ blob)
 {
-    int o = blockIdx.x * blockDim.x + threadIdx.x;
+    const int o = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int lane = threadIdx.x & 63;
     if (o >= L.cout_pad64) return;
-    const uint32_t *P = reinterpret_cast<const uint32_t *>(blob + L.off_pos);
-    const uint32_t *G = reinterpret_cast<const uint32_t *>(blob + L.off_neg);
     int32_t *cnt = reinterpret_cast<int32_t *>(blob + L.off_cnt);
     int total = 0, wsum = 0;
     for (int tap = 0; tap < 9; ++tap) {
-        int c = 0;
-        for (int k = 0; k < L.cin_words; ++k) {
-            size_t at = ((size_t)tap * L.cin_words + k) * L.cout_pad64 + o;
-            c += __popc(P[at] | G[at]);
-            wsum += __popc(P[at]) - __popc(G[at]);
+        int c = 0, sgn = 0;
+        if (o < L.cout) {
+            const int8_t *src = w + ((long)o * 9 + tap) * L.cin;
+            for (int i = lane; i < L.cin; i += 64) {
+                const int v = src[i];
+                c += v != 0;
+                sgn += (v > 0) - (v < 0);
+            }
         }
-        cnt[(size_t)tap * L.cout_pad64 + o] = c;
+        for (int off = 32; off > 0; off >>= 1) {
+            c += __shfl_xor(c, off);
+            sgn += __shfl_xor(sgn, off);
+        }
+        wsum += sgn;
+        if (lane == 0) cnt[(size_t)tap * L.cout_pad64 + o] = c;
         total += c;
     }
+    if (lane != 0) return;
     cnt[(size_t)9 * L.cout_pad64 + o] = total;
     cnt[(size_t)10 * L.cout_pad64 + o] = wsum;
 }
@@ -155,10 +164,10 @@ int launch_pack_weights(const int8_t *w, const BlobLayout &L, void *blob, hipStr
     MBU_LAUNCH(pack_weights_kernel, dim3(blocks), dim3(256), 0, s, w, L, (uint8_t *)blob);
     int rc = check_launch("pack_weights");
     if (rc) return rc;
-    MBU_LAUNCH(count_kept_kernel, dim3(ceil_div(L.cout_pad64, 256)), dim3(256), 0, s, L,
+    MBU_LAUNCH(count_kept_kernel, dim3(ceil_div(L.cout_pad64, 4)), dim3(256), 0, s, w, L,
                        (uint8_t *)blob);
     rc = check_launch("count_kept");
-    if (rc) return rc;
+    if (rc || !(L.sections & MBU_BLOB_SUMMED_TAPS)) return rc;
     return launch_pack_upcat(w, L, blob, s);
 }
 

@@ -16,10 +16,11 @@
 //   fast estimate  every scaled float is split into two fp16 terms v = vh + vl + r, both
 //                  rounded to nearest, |r| <= 2^-22 |v|; yf = sum wh*xh + wh*xl + wl*xh on
 //                  v_mfma_f32_32x32x16_f16 (fp16 products are exact in the fp32 accumulator);
-//   error budget   |yf - y| <= kappa * ||w_o||_2 * ||x_patch||_2 (in scaled units) covers the
-//                  dropped terms (3 * 2^-22 = 7e-7), the accumulation rounding of the matrix
-//                  instruction and the rounding of the sequential chain itself
-//                  (27 * 2^-24 = 1.6e-6), all relative to sum |w||x| <= ||w||_2 ||x||_2;
+//   error budget   |yf - y| <= kappa * ||w_o||_2 * ||x_patch||_2 (in scaled units), every term
+//                  relative to S = sum |w||x| <= ||w||_2 ||x||_2 (see STEM_KAPPA below): the
+//                  rounding of the sequential chain itself, the terms the split drops, and the
+//                  additions inside the matrix instructions, bounded for ANY order of addition
+//                  and for rounding to nearest or truncation to 24 bits alike;
 //   decision       |yf| >  T = kappa * max_o ||w_o|| * ||x_patch||  ->  sign(y) = sign(yf);
 //                  otherwise the output is recomputed by the sequential chain itself, on the
 //                  unscaled float32 inputs.
@@ -46,10 +47,21 @@ typedef _Float16 v8h __attribute__((ext_vector_type(8)));
 typedef _Float16 v2h __attribute__((ext_vector_type(2)));
 typedef float v2f __attribute__((ext_vector_type(2)));
 
-// Error budget of the fast estimate relative to ||w||_2 ||x||_2 (see the header comment):
-// sequential chain 27 * 2^-24 = 1.6e-6, dropped terms 7e-7, matrix accumulation measured
-// below 5e-7; 2^-18 = 3.8e-6.
-constexpr float STEM_KAPPA = 0x1p-18f;
+// Error budget of the fast estimate relative to S = sum |w_k||x_k| <= ||w||_2 ||x||_2, worst
+// case, no measured term:
+//   sequential chain (the definition's own rounding): 27 fused multiply-adds, each within 2^-24
+//     of a partial sum that is at most S in magnitude                       27 * 2^-24 = 1.61e-6
+//   terms the split drops: wl*xl, rw*x, w*rx with |wl|, |xl| <= 2^-11, |rw|, |rx| <= 2^-22
+//     of the value                                                        ~  3 * 2^-22 = 0.72e-6
+//   additions inside the matrix instructions.  The products of two fp16 values are exact in
+//     fp32; what is assumed of the hardware is only that every addition it performs - in
+//     whatever order - is accurate to 2^-23 of its result (round to nearest gives 2^-24,
+//     truncation to 24 bits 2^-23).  The two groups of small products (wl*xh, wh*xl; at most
+//     2^-10 S in total) are accumulated FIRST, while the accumulator is below 2^-10 S, so
+//     their 56 additions contribute below 1e-8; the 28 additions of the wh*xh group (27 terms
+//     and the constant) happen on partial sums of at most S(1 + 2^-9)        28 * 2^-23 = 3.34e-6
+//   total 5.68e-6 < kappa = 2^-17 = 7.63e-6.
+constexpr float STEM_KAPPA = 0x1p-17f;
 constexpr uint32_t OOB = 0x80000000u;   // byte offset beyond any accepted image
 
 // (a, b) -> packed fp16 pairs hi and lo with v = hi + lo + r, |r| <= 2^-22 |v| (+ 2^-25):

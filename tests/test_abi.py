@@ -125,6 +125,17 @@ def test_unet_plan_with_transposed_decoder():
 
 def test_packed_weight_size_and_path_switch():
     assert B.packed_weights_bytes(64, 64) > 2 * 9 * 64 * 64 // 8
+    # optional sections: each one adds its size, the matrix fragments are always there
+    full = B.packed_weights_bytes(512, 1536)
+    lean = B.packed_weights_bytes(512, 1536, B.BLOB_MATRIX)
+    assert B.packed_weights_bytes(512, 1536, 0) == lean and B.packed_weights_bytes(512, 1536, B.BLOB_ALL) == full
+    planes = B.packed_weights_bytes(512, 1536, B.BLOB_BIT_PLANES) - lean
+    taps = B.packed_weights_bytes(512, 1536, B.BLOB_SUMMED_TAPS) - lean
+    assert planes >= 2 * 9 * 1536 * 512 // 8 and taps >= 16 * 1536 * 512 // 2 and lean + planes + taps == full
+    assert lean >= 9 * 1536 * 512 // 2 and lean < 0.4 * full
+    n_ = ctypes.c_size_t()
+    assert B.lib().mbu_packed_weights_bytes_sections(64, 64, 8, ctypes.byref(n_)) == B.MBU_ERR_ARG
+    assert B.lib().mbu_pack_weights_sections(0x10000, 64, 64, 16, 0x20000, None) == B.MBU_ERR_ARG
     with pytest.raises(B.MbuError):
         B.packed_weights_bytes(40, 64)
     n = ctypes.c_size_t()

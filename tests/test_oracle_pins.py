@@ -498,6 +498,17 @@ def test_cost_scores_properties():
     _, order = O.cost_scores([o for o, _ in layers], [p for _, p in layers], 1.0)
     assert set(order[:4].tolist()) == set(range(len(pairs), len(pairs) + 4))
     assert 5 * max(o for o, _ in ups) <= min(o for o, _ in pairs)
+    # Appendix A.4 (cost scores with w_op = w_param = 0.5): ranks 1-4 are the four transposed
+    # layers, ordered from the full-resolution one (fewest parameters, rank 1) to the deepest
+    # (rank 4); their operation counts are equal, so the parameter count decides.  This plan
+    # reproduces that order and the scores' magnitudes (all four below 0.13, as printed); the
+    # scores of the double convolutions depend on the channel plan of the missing architecture
+    # figure and are not reproduced.
+    s, order = O.cost_scores([o for o, _ in layers], [p for _, p in layers], 0.5)
+    n = len(pairs)
+    assert order[:4].tolist() == [n + 0, n + 1, n + 2, n + 3]      # up1 (full resolution) ... up4 (deepest)
+    assert (np.diff(s[n:n + 4]) > 0).all() and s[n + 3] < 0.13 and s[n] < 0.02
+    assert s[n + 3] < s[:n].min()
 
 
 def test_upsampled_channels_collapse_to_2x2_kernels_at_low_resolution():

@@ -67,3 +67,24 @@ def test_dropped_terms_of_the_window_scaled_split_stay_inside_the_budget():
     # and the kernel's constant 2^-9 covers it
     assert worst_abs_used and np.sqrt(27.0) * 2.0 ** 13 * 2.0 ** -25 < 2.0 ** -9
     assert worst_rel <= 1.0
+
+
+def test_decision_threshold_covers_the_worst_case_budget():
+    """kappa of the first layer's decision rule against the sum of the worst-case terms, none of
+    them measured: the reference chain's own rounding (27 fused multiply-adds), the products the
+    two-term split drops, and the additions inside the matrix instructions under the weakest
+    assumption (any order, each accurate to 2^-23 of its result; small product groups first)."""
+    kappa = 2.0 ** -17
+    chain = 27 * 2.0 ** -24
+    dropped = (2.0 ** -11) ** 2 + 2 * 2.0 ** -22 + 2.0 ** -33          # wl*xl + rw*x + w*rx + rw*rx
+    small_groups = 56 * 2.0 ** -23 * 2.0 ** -10                         # accumulator below 2^-10 S
+    main_group = 28 * 2.0 ** -23 * (1 + 2.0 ** -9)
+    total = chain + dropped + small_groups + main_group
+    assert total < kappa and total > 0.5 * kappa                         # covered, and not by a mile
+    # the library's constant and the documented budget agree
+    import os
+    import re
+    src = open(os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))),
+                            "paper_2601_11660_amd", "csrc", "stem_mfma.hip")).read()
+    m = re.search(r"STEM_KAPPA = 0x1p-(\d+)f", src)
+    assert m and int(m.group(1)) == 17
