@@ -750,6 +750,19 @@ __global__ __launch_bounds__(256, 3) void stem_rows_kernel(
                         if (chunk * 64 + m * 32 + 16 * half >= Co) fl[m] = 0;
                     }
                     const uint32_t pb = (uint32_t)((((size_t)n * 3 * H + y) * W + xo) * 4);
+                    // the 27 patch values of this pixel, fetched once and in one batch (a tap
+                    // outside the image is skipped in the chain below)
+                    float pv[27];
+                    uint32_t okm = 0;
+#pragma unroll
+                    for (int u = 0; u < 27; ++u) {
+                        const int ky = u / 9, kx = (u % 9) / 3, ci = u % 3;
+                        const bool ok = !((ky == 0 && y == 0) || (ky == 2 && y == H - 1) ||
+                                          (kx == 0 && xo == 0) || (kx == 2 && xo == W - 1));
+                        const uint32_t o = pb + (uint32_t)(((long)ci * H * W + (long)(ky - 1) * W + (kx - 1)) * 4);
+                        pv[u] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, ok ? o : OOB, 0, 0));
+                        okm |= (ok ? 1u : 0u) << u;
+                    }
 #pragma unroll
                     for (int m = 0; m < 2; ++m) {
                         const int cb = chunk * 64 + m * 32 + 16 * half;
@@ -757,28 +770,15 @@ __global__ __launch_bounds__(256, 3) void stem_rows_kernel(
                             const int e = __builtin_ctz(fl[m]);
                             fl[m] &= fl[m] - 1;
                             const float *wp = w + (size_t)(cb + e) * KV;
-                            // the sum in its defined order; a tap outside the image is skipped
+                            float wv[27];
+#pragma unroll
+                            for (int u = 0; u < 27; ++u) wv[u] = wp[u];
+                            // the sum in its defined order: ky, kx, ci
                             float sum = 0.0f;
-#pragma unroll 1
-                            for (int ky = 0; ky < 3; ++ky) {
-                                float pv[9], wv[9];
-                                uint32_t okm = 0;
 #pragma unroll
-                                for (int u = 0; u < 9; ++u) {
-                                    const int kx = u / 3, ci = u - kx * 3;
-                                    const bool ok = !((ky == 0 && y == 0) || (ky == 2 && y == H - 1) ||
-                                                      (kx == 0 && xo == 0) || (kx == 2 && xo == W - 1));
-                                    const uint32_t o =
-                                        pb + (uint32_t)(((long)ci * H * W + (long)(ky - 1) * W + (kx - 1)) * 4);
-                                    pv[u] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rsrc, ok ? o : OOB, 0, 0));
-                                    wv[u] = wp[ky * 9 + u];
-                                    okm |= (ok ? 1u : 0u) << u;
-                                }
-#pragma unroll
-                                for (int u = 0; u < 9; ++u) {
-                                    const float f = __builtin_fmaf(wv[u], pv[u], sum);
-                                    sum = ((okm >> u) & 1u) ? f : sum;
-                                }
+                            for (int u = 0; u < 27; ++u) {
+                                const float f = __builtin_fmaf(wv[u], pv[u], sum);
+                                sum = ((okm >> u) & 1u) ? f : sum;
                             }
                             ep.sg[m] = (ep.sg[m] & ~(1u << e)) | ((sum >= 0.0f ? 0u : 1u) << e);   // NaN -> bit 0
                         }

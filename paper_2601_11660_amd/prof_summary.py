@@ -4,6 +4,7 @@
     python -m paper_2601_11660_amd.prof_summary traffic <fetch>_counter_collection.csv \
                                                         <write>_counter_collection.csv
     python -m paper_2601_11660_amd.prof_summary counters <file>_counter_collection.csv [...]
+    python -m paper_2601_11660_amd.prof_summary ramp <bench --ramp output> [<SQ_BUSY_CU_CYCLES csv>]
 
 `traffic` expects the two counter passes of `bench.py --calibrate-copy` (FETCH_SIZE, then
 WRITE_SIZE): the three plain 256 MiB device copies at the end of that run give the scale factor
@@ -123,6 +124,37 @@ def counters(paths):
         print(f"| {k} | {n} | " + " | ".join(cells) + " |")
 
 
+def ramp(json_path, pmc_csv=None):
+    """Pass time against pass index after an idle period (bench.py --ramp), in blocks of ten
+    passes; with a counter file of the same command, the shader clock of each block =
+    SQ_BUSY_CU_CYCLES / 256 compute units / dispatch duration over the block's forward-pass
+    dispatches."""
+    import json
+    ms = json.load(open(json_path))["ramp_ms_per_pass"]
+    clock = None
+    if pmc_csv:
+        rows = [r for r in csv.DictReader(open(pmc_csv))
+                if r["Counter_Name"] == "SQ_BUSY_CU_CYCLES" and "mbu::" in r["Kernel_Name"]
+                and "pack" not in r["Kernel_Name"] and "count_kept" not in r["Kernel_Name"]]
+        rows.sort(key=lambda r: int(r["Dispatch_Id"]))
+        per_pass = 20
+        rows = rows[3 * per_pass:]                     # the three passes before the idle period
+        clock = []
+        for b in range(len(ms) // 10):
+            blk = rows[b * 10 * per_pass:(b + 1) * 10 * per_pass]
+            if len(blk) < 10 * per_pass:
+                break
+            cyc = sum(float(r["Counter_Value"]) for r in blk) / 256.0
+            ns = sum(int(r["End_Timestamp"]) - int(r["Start_Timestamp"]) for r in blk)
+            clock.append(cyc / ns)
+    print("| passes | mean ms per pass | frames/s |" + (" shader clock GHz (counter pass) |" if clock else ""))
+    print("|---|---|---|" + ("---|" if clock else ""))
+    for b in range(len(ms) // 10):
+        m = sum(ms[b * 10:(b + 1) * 10]) / 10
+        extra = f" {clock[b]:.2f} |" if clock and b < len(clock) else (" - |" if clock else "")
+        print(f"| {b * 10 + 1}-{b * 10 + 10} | {m:.4f} | {1e3 / m:.0f} |" + extra)
+
+
 if __name__ == "__main__":
     mode = sys.argv[1]
     if mode == "stats":
@@ -131,5 +163,7 @@ if __name__ == "__main__":
         traffic(sys.argv[2], sys.argv[3])
     elif mode == "counters":
         counters(sys.argv[2:])
+    elif mode == "ramp":
+        ramp(sys.argv[2], sys.argv[3] if len(sys.argv) > 3 else None)
     else:
         raise SystemExit(__doc__)

@@ -702,6 +702,8 @@ PADDED_SHAPES = [
     (2, 7, 70, 64, 128, 128, 1),
     (1, 37, 65, 128, 256, 64, 1),
     (1, 16, 64, 64, 128, 64, 1),      # nothing missing: the general entry point on a full extent
+    (1, 9, 70, 64, 64, 64, 0, 2, 3),  # a second input far smaller than the frame: 2 x 3 pixels
+    (2, 12, 40, 32, 96, 32, 1, 1, 1), # ... one pixel, up-sampled to 2 x 2
 ]
 
 
@@ -709,22 +711,27 @@ PADDED_SHAPES = [
 def test_two_input_layer_with_padded_second_input(shape):
     """Decoder layer of a frame whose size is not a multiple of 2^levels (Appendix A.3): the
     second input covers the top left of the frame, the rest of its channels are zeros."""
-    N, H, W, Ca, Cb, Cout, ups = shape
-    say(f"conv two inputs N={N} H={H} W={W} Ca={Ca} Cb={Cb} Cout={Cout} upsample={ups}")
+    N, H, W, Ca, Cb, Cout, ups = shape[:7]
+    say(f"conv two inputs {shape}")
     rng = np.random.default_rng(Ca + Cb + H + W)
-    Hb, Wb = (H // 2, W // 2) if ups else (H - (H & 1), W - (W & 1))
+    Hb, Wb = shape[7:] if len(shape) > 7 else (H // 2, W // 2) if ups else (H - (H & 1), W - (W & 1))
     a = synth.pm1_bits(rng, (N, H, W, Ca))
     b = synth.pm1_bits(rng, (N, Hb, Wb, Cb))
     w = synth.ternary_weights(14, 0, 0, Cout, Ca + Cb, 0.6)
     th = synth.thresholds(14, 0, 0, Cout, (9 * (Ca + Cb)) // 16)
     bb = O.upsample2x(b) if ups else b
-    x = O.concat(a, O.zero_pad_to(bb, H, W))
+    # the second input sits at the top left of the frame: zeros below and to the right of it
+    pad = np.zeros((N, H, W, Cb), np.int8)
+    pad[:, :bb.shape[1], :bb.shape[2]] = bb
+    if len(shape) == 7:
+        assert np.array_equal(pad, O.zero_pad_to(bb, H, W))     # the decoder's padding is this placement
+    x = O.concat(a, pad)
     _, out_ref = O.masked_binary_layer(x, w, th)
     bits, _ = B.conv3x3_masked_binary_two_inputs(B.pack_act(dev(a)), Ca, B.pack_act(dev(b)), Cb, bool(ups),
                                                  B.pack_weights(dev(w)), Cout, dev(th))
     torch.cuda.synchronize()
     assert np.array_equal(host_u32(bits), bitref.pack_pm1(out_ref))
-    if ups:
+    if ups and len(shape) == 7:
         # the fused entry point takes the same layer for odd sizes (low = floor(H/2) x floor(W/2))
         bits2, _ = B.conv3x3_masked_binary_fused(B.pack_act(dev(a)), Ca, B.pack_act(dev(b)), Cb,
                                                  B.pack_weights(dev(w)), Cout, dev(th), True, False)
@@ -960,15 +967,11 @@ def test_blob_sections():
             assert np.array_equal(host_u32(lean.step_output(1, 64, 96, s)), host_u32(full.step_output(1, 64, 96, s)))
     # without the summed taps the decoder layers fall back to the 9-tap kernel: same bits
     none = build_unet(case, True)
-    for i in range(len(none.sections)):
-        none._layers[i].sections = B.BLOB_MATRIX
-        none._layers[i].packed_w = lean.blobs[i].data_ptr() if lean.sections[i] == B.BLOB_MATRIX else \
-            B.pack_weights(dev(case.convs[i][0]), B.BLOB_MATRIX).data_ptr()
-    assert none.step_kernel(1, 64, 96, 10) == "conv_mfma_block_kernel"
-    # (the re-packed blobs above are temporaries: pack them again and keep them alive)
     keep = [B.pack_weights(dev(w), B.BLOB_MATRIX) for w, _ in case.convs]
     for i, blob in enumerate(keep):
+        none._layers[i].sections = B.BLOB_MATRIX
         none._layers[i].packed_w = blob.data_ptr()
+    assert none.step_kernel(1, 64, 96, 10) == "conv_mfma_block_kernel"
     c = none.forward(dev(case.image))
     torch.cuda.synchronize()
     assert np.array_equal(host(c), host(b))
