@@ -435,6 +435,23 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
         }
     };
 
+    // One word of that commit (word i & 1 of staged pixel i >> 1), slotted between the matrix
+    // instructions of a step's last fragments: vector work hides only behind matrix instructions
+    // of the same wave.  No branch: a slot with control flow makes the compiler drain the
+    // vector-memory counter there.
+    auto commit_word = [&](int ks, uint4 *buf, int i) {
+        const int j = i >> 1;
+        int p = tid + NT * j;
+        p = p < NPIX ? p : 0;
+        const int r = p / HALO_W, c = p - r * HALO_W;
+        const int k = 2 * ks + (i & 1);
+        const bool have = (i & 1) == 0 || CW_EVEN || (k < Cw);
+        const bool in = ((TWO_SRC && k >= Cwa ? inside_b : inside) >> j) & 1u;
+        buf[(r * 2 + (i & 1)) * HALO_W + c] =
+            expand_word_masked((i & 1) ? gq[j].y : gq[j].x, (have && in) ? 0x22222222u : 0u,
+                               (have && !in) ? 0x11111111u : 0u);
+    };
+
     // ---- weight fragments: [tile64][kstep][tap][m][lane], 18 KB per step and tile
     const uint4 *wk = wfrag + (size_t)ct * ksteps * (18 * 64) + lane;
     // the same fragments through a buffer resource: lane offset in a register, step and tap
@@ -528,10 +545,11 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
                         wrs, wlane, ((j < 3 ? ks : kn) * 18 + (ky * 3 + g) * 2 + m) * 1024, 0);
                     Wg[g][ky][m] = (v4i){(int)w[0], (int)w[1], (int)w[2], (int)w[3]};
                 }
+                // the next step's window (fetched at the start of this one): one word per slot
+                if (j >= NF - 1 - 2 * NLD && j < NF - 1) commit_word(kn, tile[buf ^ 1], j - (NF - 1 - 2 * NLD));
                 __builtin_amdgcn_sched_barrier(0);
             }
             buf ^= 1;
-            stage_commit(kn, tile[buf]);
             __syncthreads();
         }
 
