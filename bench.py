@@ -326,6 +326,31 @@ def ramp_table(args, net, image, logits, B, torch):
                       "mean_last_20": round(float(np.mean(ms[-20:])), 4)}))
 
 
+def frames_in_flight(B, torch, net, case, image, n_frames, passes):
+    """Serving mode: n_frames independent frames in flight, each on a stream and a workspace of
+    its own (the C ABI is re-entrant; weights are shared).  The kernels of one frame fill the
+    whole chip, so nothing runs side by side for long, but the ramp-up of one frame's kernel
+    overlaps the drain of the other's.  Frames/s over `passes` forward passes in total."""
+    N, _, H, W = image.shape
+    nets = [net] + [net.clone_for_stream() for _ in range(n_frames - 1)]
+    outs = [torch.empty((N, case.n_classes, H, W), dtype=torch.float32, device="cuda") for _ in nets]
+    streams = [torch.cuda.Stream() for _ in nets]
+    for nt, o, st in zip(nets, outs, streams):
+        with torch.cuda.stream(st):
+            nt.forward(image, o)
+    torch.cuda.synchronize()
+    best = 0.0
+    for _ in range(2):
+        t0 = time.perf_counter()
+        for k in range(passes):
+            i = k % n_frames
+            with torch.cuda.stream(streams[i]):
+                nets[i].forward(image, outs[i])
+        torch.cuda.synchronize()
+        best = max(best, passes / (time.perf_counter() - t0))
+    return best
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -527,6 +552,15 @@ def main():
         "roofline_all_conv": all_conv,
         "per_layer": per_layer,
     }
+    if not args.no_sweep:
+        passes = max(40, min(K, 400))
+        out["frames_in_flight"] = {
+            "note": "throughput of the same forward pass with 2 / 3 independent frames in flight, "
+                    "each on a stream and workspace of its own (serving mode); `value` above is one "
+                    "frame at a time on one stream",
+            "passes": passes,
+            "frames_per_s_2": round(frames_in_flight(B, torch, net, case, image, 2, passes), 1),
+            "frames_per_s_3": round(frames_in_flight(B, torch, net, case, image, 3, passes), 1)}
     del net, image, logits
     torch.cuda.empty_cache()
     if args.calibrate_copy:

@@ -458,6 +458,21 @@ class UNet:
         self._events: Optional[EventSet] = None
         self.workspace: Optional[torch.Tensor] = None
 
+    def clone_for_stream(self) -> "UNet":
+        """A second handle on the same network for another frame in flight: shares the weight
+        blobs, thresholds and float weights (read-only), owns its descriptor, events and
+        workspace.  Forward passes of the two handles may overlap on different streams."""
+        import copy
+        other = copy.copy(self)
+        other.desc = UNetDesc(levels=self.levels, base=self.base, in_channels=self.in_channels,
+                              n_classes=self.n_classes, stem_w=self.stem_w.data_ptr(),
+                              convs=self._layers, cls_w=self.cls_w.data_ptr(),
+                              cls_b=self.cls_b.data_ptr(), step_events=None,
+                              fuse=self.desc.fuse, up_convs=self._up_layers)
+        other._events = None
+        other.workspace = None
+        return other
+
     def workspace_bytes(self, N: int, H: int, W: int) -> int:
         n = ctypes.c_size_t(0)
         check(lib().mbu_unet_workspace_bytes(ctypes.byref(self.desc), N, H, W, ctypes.byref(n)))

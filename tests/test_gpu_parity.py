@@ -947,6 +947,34 @@ def test_layer_with_folded_batchnorm(shape):
     assert sure.mean() > 0.999 and np.array_equal(got[sure], s[sure])
 
 
+def test_two_frames_in_flight_on_two_streams():
+    """Two handles on one network (shared weights, own workspace) with forward passes
+    interleaved on two streams: the same logits and layer outputs as one frame at a time."""
+    say("two frames in flight")
+    case = synth.unet_case(2, 4, 1, 128, 192, base=64, levels=3, n_classes=7)
+    rng = np.random.default_rng(9)
+    img2 = rng.standard_normal(case.image.shape, dtype=np.float32)
+    net = build_unet(case, True)
+    ref1 = host(net.forward(dev(case.image)))
+    last1 = host_u32(net.step_output(1, 128, 192, net.num_steps - 2)).copy()
+    ref2 = host(net.forward(dev(img2)))
+    twin = net.clone_for_stream()
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    i1, i2 = dev(case.image), dev(img2)
+    o1 = torch.empty((1, 7, 128, 192), dtype=torch.float32, device="cuda")
+    o2 = torch.empty_like(o1)
+    torch.cuda.synchronize()
+    for _ in range(20):
+        with torch.cuda.stream(s1):
+            net.forward(i1, o1)
+        with torch.cuda.stream(s2):
+            twin.forward(i2, o2)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(o1), ref1) and np.array_equal(host(o2), ref2)
+    assert np.array_equal(host_u32(net.step_output(1, 128, 192, net.num_steps - 2)), last1)
+    assert twin.workspace.data_ptr() != net.workspace.data_ptr()
+
+
 def test_blob_sections():
     """Blobs packed with only the sections a layer's place in the network reads: the network
     object packs them that way by default; same bits as with complete blobs; a blob without the
