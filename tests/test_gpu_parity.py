@@ -424,9 +424,6 @@ def build_unet(case, fuse=True):
                   dev(case.cls_w), dev(case.cls_b), levels=case.levels, fuse=fuse, up_convs=ups)
 
 
-TAP_OF_STEP = {"stem": "stem", "classifier": None}
-
-
 def compare_unet_all_taps(case, N, H, W, fuse=True, images=None):
     """Every element of every step's output and of the logits against the oracle's network.
     images: which images of the batch to compare (default all); the oracle runs on those
