@@ -944,6 +944,21 @@ def test_layer_with_folded_batchnorm(shape):
     assert sure.mean() > 0.999 and np.array_equal(got[sure], s[sure])
 
 
+@pytest.mark.parametrize("fuse", [True, False])
+def test_unet_smallest_frames_and_one_image_channel(fuse):
+    """Degenerate sizes of the network: a frame of exactly 2^levels pixels a side (the bottleneck
+    is a single pixel, every tap but the centre is padding), the same plus one (every level
+    odd), and a one-channel image."""
+    say(f"unet smallest frames fuse={fuse}")
+    for H, W in ((16, 16), (17, 19), (16, 48)):
+        case = synth.unet_case(16, H, 2, H, W, base=32, levels=4, n_classes=3)
+        compare_unet_all_taps(case, 2, H, W, fuse)
+    case = synth.unet_case(16, 1, 1, 40, 56, base=64, levels=2, n_classes=2)
+    case.image = np.ascontiguousarray(case.image[:, :1])
+    case.stem_w = np.ascontiguousarray(case.stem_w[..., :1])
+    compare_unet_all_taps(case, 1, 40, 56, fuse)
+
+
 def test_two_frames_in_flight_on_two_streams():
     """Two handles on one network (shared weights, own workspace) with forward passes
     interleaved on two streams: the same logits and layer outputs as one frame at a time."""
