@@ -158,9 +158,9 @@ int mbu_conv3x3_masked_binary(const uint32_t *act, int N, int H, int W, int Cin,
  *             last Clow channels are the value 0 (they add nothing)
  *   packed_w  blob packed for (Cout, Cin = Ca + Clow)
  *   out_bits  packed [N][H][W][Cout/32], or NULL
- *   out_pool  packed [N][H/2][W/2][Cout/32] = bitwise OR of each 2x2 window of the layer's
- *             output, or NULL
- * H and W must be even when `out_pool` is given; at least one output non-NULL.
+ *   out_pool  packed [N][H/2][W/2][Cout/32] (sizes rounded down: an odd last row / column is in
+ *             no window) = bitwise OR of each 2x2 window of the layer's output, or NULL
+ * H, W >= 2 when `low` or `out_pool` is given; at least one output non-NULL.
  * Errors as for mbu_conv3x3_masked_binary. */
 int mbu_conv3x3_masked_binary_fused(const uint32_t *act, int Ca, const uint32_t *low, int Clow,
                                     int N, int H, int W, const void *packed_w, int Cout,

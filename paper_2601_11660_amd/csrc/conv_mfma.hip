@@ -578,15 +578,15 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_block_kernel(
         for (int r = 0; r < RW; ++r)
             if (ok && yb + r < H && out_bits) orow[r * row_stride] = words[r];
         if (POOL) {
-            // H, W even and the tile origin even: every 2x2 window lies inside one wave's
-            // rows and inside one lane pair
+            // the tile origin is even: every 2x2 window lies inside one wave's rows and inside
+            // one lane pair; an odd last row / column of the image belongs to no window
 #pragma unroll
             for (int r = 0; r < RW; r += 2) {
                 const int y = yb + r;
                 uint32_t v = words[r] | words[r + 1];
                 // neighbouring lane (quad permute [1,0,3,2]) holds the next pixel of the row
                 v |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xf, 0xf, true);
-                if (ok && y < H && (col & 1) == 0)
+                if (ok && (y >> 1) < Hl && (x >> 1) < Wl && (col & 1) == 0)
                     out_pool[(((size_t)n * Hl + (y >> 1)) * Wl + (x >> 1)) * Cow + widx] = v;
             }
         }
@@ -740,7 +740,7 @@ static int rows_kernel_waves()
 
 bool conv_writes_pooled(int H, int W, const BlobLayout &L)
 {
-    if ((H & 1) || (W & 1)) return false;
+    if (H < 2 || W < 2) return false;
     return L.ksteps > 1 || (rows_kernel_waves() && conv_rows_supported(H, W, L, true));
 }
 

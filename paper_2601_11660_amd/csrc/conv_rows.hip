@@ -227,7 +227,8 @@ __global__ __launch_bounds__(256, WPS) void conv_mfma_rows_kernel(
         const int widx = ct * 2 + half;
         const bool ok = x < W && widx < Cow;
         c.out_voff = ok ? (uint32_t)((x * Cow + widx) * 4) : RS_BAD_LANE;
-        c.pool_voff = (ok && (col & 1) == 0) ? (uint32_t)(((x >> 1) * Cow + widx) * 4) : RS_BAD_LANE;
+        // (an odd last column has no 2x2 window; an odd last row has no partner row to trigger a store)
+        c.pool_voff = (ok && (col & 1) == 0 && (x >> 1) < (W >> 1)) ? (uint32_t)(((x >> 1) * Cow + widx) * 4) : RS_BAD_LANE;
         c.psel = half ? 0x07060302u : 0x05040100u;
     }
 
@@ -525,7 +526,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_rows2k_kernel(
         const int x = sx * 32 + col;
         const bool ok = x < W && half == 0;   // both halves hold the finished word: one stores it
         c.out_voff = ok ? (uint32_t)((x * Cow + ct) * 4) : RS_BAD_LANE;
-        c.pool_voff = (ok && (col & 1) == 0) ? (uint32_t)(((x >> 1) * Cow + ct) * 4) : RS_BAD_LANE;
+        c.pool_voff = (ok && (col & 1) == 0 && (x >> 1) < (W >> 1)) ? (uint32_t)(((x >> 1) * Cow + ct) * 4) : RS_BAD_LANE;
         c.psel = 0;
     }
 
@@ -700,7 +701,6 @@ int launch_conv_mfma_rows2k(const uint32_t *act, int N, int H, int W, const Blob
 {
     if (!conv_rows2k_supported(H, W, L, out_bits != nullptr))
         return fail(MBU_ERR_SHAPE, "row-streaming kernel for two input steps: layer not supported");
-    if (out_pool && ((H & 1) || (W & 1))) return fail(MBU_ERR_SHAPE, "pooled output needs even H and W");
     const uint4 *wfrag = (const uint4 *)((const uint8_t *)blob + L.off_f4);
     if (out_pool) return launch_rows2k_t<true>(act, N, H, W, L, wfrag, thresh, out_bits, out_pool, s);
     return launch_rows2k_t<false>(act, N, H, W, L, wfrag, thresh, out_bits, out_pool, s);
@@ -712,7 +712,6 @@ int launch_conv_mfma_rows(const uint32_t *act, int N, int H, int W, const BlobLa
 {
     if (!conv_rows_supported(H, W, L, out_bits != nullptr))
         return fail(MBU_ERR_SHAPE, "row-streaming kernel: layer not supported");
-    if (out_pool && ((H & 1) || (W & 1))) return fail(MBU_ERR_SHAPE, "pooled output needs even H and W");
     const uint4 *wfrag = (const uint4 *)((const uint8_t *)blob + L.off_f4);
     if (waves_per_simd == 1) {
         if (out_pool) return launch_rows_t<true, 1>(act, N, H, W, L, wfrag, thresh, out_bits, out_pool, s);

@@ -417,8 +417,8 @@ int mbu_conv3x3_masked_binary_fused(const uint32_t *act, int Ca, const uint32_t 
     if ((low != nullptr) != (Clow > 0) || Clow < 0)
         return fail(MBU_ERR_SHAPE, "%s: Clow must be positive exactly when low is given (Clow=%d)", fn, Clow);
     if (low && Ca % 32) return fail(MBU_ERR_SHAPE, "%s: Ca must be a multiple of 32 when low is given, got %d", fn, Ca);
-    if (out_pool && ((H & 1) || (W & 1)))
-        return fail(MBU_ERR_SHAPE, "%s: H and W must be even with out_pool (H=%d W=%d)", fn, H, W);
+    if (out_pool && (H < 2 || W < 2))
+        return fail(MBU_ERR_SHAPE, "%s: H and W must be at least 2 with out_pool (H=%d W=%d)", fn, H, W);
     if (low && (H < 2 || W < 2))
         return fail(MBU_ERR_SHAPE, "%s: H and W must be at least 2 with low (H=%d W=%d)", fn, H, W);
     if (Cout <= 0 || Cout % 32) return fail(MBU_ERR_SHAPE, "%s: Cout must be a positive multiple of 32, got %d", fn, Cout);
@@ -454,8 +454,8 @@ int mbu_conv3x3_masked_binary_concat(const uint32_t *a, int Ca, const uint32_t *
     if (rc) return rc;
     if (Cb <= 0) return fail(MBU_ERR_SHAPE, "%s: Cb must be positive, got %d", fn, Cb);
     if (Ca % 32) return fail(MBU_ERR_SHAPE, "%s: Ca must be a multiple of 32, got %d", fn, Ca);
-    if (out_pool && ((H & 1) || (W & 1)))
-        return fail(MBU_ERR_SHAPE, "%s: H and W must be even with out_pool (H=%d W=%d)", fn, H, W);
+    if (out_pool && (H < 2 || W < 2))
+        return fail(MBU_ERR_SHAPE, "%s: H and W must be at least 2 with out_pool (H=%d W=%d)", fn, H, W);
     if (Cout <= 0 || Cout % 32) return fail(MBU_ERR_SHAPE, "%s: Cout must be a positive multiple of 32, got %d", fn, Cout);
     if (Cout > 65536 || Ca + Cb > 65536) return fail(MBU_ERR_SHAPE, "%s: channel count too large", fn);
     rc = check_dims4(fn, N, H, W, Cout);
@@ -491,8 +491,8 @@ int mbu_conv3x3_masked_binary_two_inputs(const uint32_t *a, int Ca, const uint32
     if (Hb <= 0 || Wb <= 0 || (Hb << upsample) > H || (Wb << upsample) > W)
         return fail(MBU_ERR_SHAPE, "%s: the second input (%d x %d pixels%s) must be non-empty and fit into "
                     "%d x %d", fn, Hb, Wb, upsample ? ", read 2x up-sampled" : "", H, W);
-    if (out_pool && ((H & 1) || (W & 1)))
-        return fail(MBU_ERR_SHAPE, "%s: H and W must be even with out_pool (H=%d W=%d)", fn, H, W);
+    if (out_pool && (H < 2 || W < 2))
+        return fail(MBU_ERR_SHAPE, "%s: H and W must be at least 2 with out_pool (H=%d W=%d)", fn, H, W);
     if (Cout <= 0 || Cout % 32) return fail(MBU_ERR_SHAPE, "%s: Cout must be a positive multiple of 32, got %d", fn, Cout);
     if (Cout > 65536 || Ca + Cb > 65536) return fail(MBU_ERR_SHAPE, "%s: channel count too large", fn);
     rc = check_dims4(fn, N, H, W, Cout);

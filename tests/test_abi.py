@@ -63,8 +63,8 @@ def test_fused_conv_argument_validation():
     assert f(a, 64, lo, 0, 1, 8, 8, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
     assert f(a, 48, lo, 128, 1, 8, 8, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
     assert f(a, 64, lo, 128, 1, 1, 8, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
-    assert f(a, 64, lo, 128, 1, 7, 8, w, 64, t, o, p, None) == B.MBU_ERR_SHAPE
-    assert f(a, 64, None, 0, 1, 8, 9, w, 64, t, o, p, None) == B.MBU_ERR_SHAPE
+    assert f(a, 64, None, 0, 1, 1, 8, w, 64, t, o, p, None) == B.MBU_ERR_SHAPE     # no 2x2 window
+    assert f(a, 64, None, 0, 1, 8, 1, w, 64, t, o, p, None) == B.MBU_ERR_SHAPE
     assert f(a, 64, lo, 128, 1, 8, 8, w, 64, t, lo, None, None) == B.MBU_ERR_ARG
     assert f(a, 64, lo + 4, 128, 1, 8, 8, w, 64, t, o, None, None) == B.MBU_ERR_ALIGN
 
@@ -95,7 +95,7 @@ def test_tconv_and_concat_argument_validation():
     assert h(a, 64, b, 64, 0, 4, 1, 1, 9, 9, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
     assert h(a, 64, b, 64, 4, 4, 2, 1, 9, 9, w, 64, t, o, None, None) == B.MBU_ERR_ARG
     assert h(a, 48, b, 64, 4, 4, 1, 1, 9, 9, w, 64, t, o, None, None) == B.MBU_ERR_SHAPE
-    assert h(a, 64, b, 64, 4, 4, 1, 1, 9, 9, w, 64, t, o, a + 64, None) == B.MBU_ERR_SHAPE  # pool, odd
+    assert h(a, 64, b, 64, 1, 1, 0, 1, 1, 9, w, 64, t, o, a + 64, None) == B.MBU_ERR_SHAPE  # pool, H = 1
     assert h(a, 64, b, 64, 4, 4, 1, 1, 9, 9, w, 64, t, b, None, None) == B.MBU_ERR_ARG
 
 

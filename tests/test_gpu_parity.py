@@ -157,6 +157,10 @@ ROWS_SHAPES = [
     (1, 160, 2048, 64, 128),
     (1, 110, 2048, 40, 128),
     (1, 96, 2048, 64, 128),
+    # odd sizes: the pooled output rounds down (the last row / column is in no window)
+    (1, 37, 71, 64, 64),
+    (2, 9, 33, 40, 96),
+    (1, 3, 3, 64, 32),
 ]
 
 
@@ -189,6 +193,8 @@ ROWS2K_SHAPES = [
     (3, 6, 200, 128, 128),
     (1, 160, 2048, 128, 128),  # row segments of 20 rows (6-row loop body + remainder)
     (1, 110, 2048, 96, 64),    # ... 8 rows
+    (1, 39, 65, 128, 128),     # odd sizes: pooled output rounds down
+    (2, 7, 35, 100, 64),
 ]
 
 
@@ -219,6 +225,8 @@ FUSED_SHAPES = [
     (1, 20, 40, 128, 256, 256),
     (1, 6, 10, 64, 40, 32),        # low channels not a multiple of 32
     (1, 4, 4, 512, 1024, 128),
+    (1, 13, 37, 96, 160, 96),      # odd sizes: low is 6 x 18, its up-sampling is zero-padded; pool rounds down
+    (2, 9, 35, 128, 128, 256),
 ]
 
 
@@ -233,7 +241,7 @@ def test_fused_concat_upsample_pool(shape):
     low = synth.pm1_bits(rng, (N, H // 2, W // 2, Clow))
     w = synth.ternary_weights(9, 0, 0, Cout, Ca + Clow, 0.6)
     th = synth.thresholds(9, 0, 0, Cout, (9 * (Ca + Clow)) // 16)
-    x = O.concat(skip, O.upsample2x(low))
+    x = O.concat(skip, O.zero_pad_to(O.upsample2x(low), H, W))
     _, out_ref = O.masked_binary_layer(x, w, th)
     pool_ref = O.maxpool2x2(out_ref)
     blob = B.pack_weights(dev(w))
