@@ -2,6 +2,7 @@
 // the float image into the first binary feature map, and the 1x1 classifier that
 // turns the last binary feature map into float logits.
 #include "mbu_internal.h"
+#include <algorithm>
 
 namespace mbu {
 
@@ -254,6 +255,71 @@ __global__ __launch_bounds__(256, CW == 4 ? 2 : 3) void classifier_kernel(const 
     }
 }
 
+// ---------------------------------------------------------------------------------
+// Classifier for up to four classes (binary segmentation, the paper's tasks, Sec. 4.1): with so
+// few outputs per pixel the matrix-core kernel above spends its time turning bits into fp16
+// operands.  Here the block builds, once, a table per byte position of the packed words:
+//   table[j][v][k] = sum_{i < 8} (bit i of v ? +w : -w)[k][8 j + i]          (float32, KP per entry)
+// and a thread sums C / 8 table entries per pixel: logit[k] = b[k] + sum_j table[j][byte j][k].
+// The partial sums are formed in another order than the channel-by-channel definition; the
+// difference is a few float32 roundings (1e-7 relative), far inside the layer's 1e-4.
+template <int KP>
+__global__ __launch_bounds__(256) void classifier_lut_kernel(const uint32_t *__restrict__ act, long pixels,
+                                                             long HW, int CW, const float *__restrict__ w,
+                                                             const float *__restrict__ b, int K,
+                                                             float *__restrict__ out)
+{
+    __shared__ float lut[16 * 256 * KP];
+    const int nb = 4 * CW;            // byte positions
+    {
+        const int v = threadIdx.x;
+        for (int j = 0; j < nb; ++j)
+#pragma unroll
+            for (int k = 0; k < KP; ++k) {
+                float sum = 0.0f;
+                if (k < K) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const float wv = w[(size_t)k * (32 * CW) + 8 * j + i];
+                        sum += ((v >> i) & 1) ? wv : -wv;
+                    }
+                }
+                lut[(j * 256 + v) * KP + k] = sum;
+            }
+    }
+    float bias[KP];
+#pragma unroll
+    for (int k = 0; k < KP; ++k) bias[k] = k < K ? b[k] : 0.0f;
+    __syncthreads();
+
+    const long stride = (long)gridDim.x * 256;
+    long p = (long)blockIdx.x * 256 + threadIdx.x;
+    // (image, pixel inside the image) of p, advanced by the stride without divisions
+    long n = p / HW, rem = p - n * HW;
+    const long dn = stride / HW, dr = stride - dn * HW;
+    for (; p < pixels; p += stride) {
+        float acc[KP];
+#pragma unroll
+        for (int k = 0; k < KP; ++k) acc[k] = bias[k];
+        for (int q = 0; q < CW; ++q) {
+            const uint32_t word = act[p * CW + q];
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const float *e = lut + ((q * 4 + jj) * 256 + ((word >> (8 * jj)) & 255u)) * KP;
+#pragma unroll
+                for (int k = 0; k < KP; ++k) acc[k] += e[k];
+            }
+        }
+        float *o = out + (size_t)n * K * HW + rem;
+#pragma unroll
+        for (int k = 0; k < KP; ++k)
+            if (k < K) __builtin_nontemporal_store(acc[k], o + (size_t)k * HW);
+        n += dn;
+        rem += dr;
+        if (rem >= HW) { rem -= HW; ++n; }
+    }
+}
+
 int launch_classifier(const uint32_t *act, int N, int H, int W, int C, const float *w,
                       const float *b, int K, float *out, hipStream_t s)
 {
@@ -262,6 +328,15 @@ int launch_classifier(const uint32_t *act, int N, int H, int W, int C, const flo
     // a lane's offset from its group's image base must fit 32 bits
     if ((double)(K + 5) * (double)HW * 4.0 >= 4294967296.0)
         return fail(MBU_ERR_SHAPE, "classifier: image too large (%ld pixels, %d classes)", HW, K);
+    if (K <= 4 && (C == 32 || C == 64 || C == 128)) {
+        // few classes: table look-up, many pixels per thread so that building the table is amortised
+        const unsigned blocks = (unsigned)std::max(1L, std::min((pixels + 2047) / 2048, 1024L));
+        const int CW = C / 32;
+        if (K == 1) MBU_LAUNCH(classifier_lut_kernel<1>, dim3(blocks), dim3(256), 0, s, act, pixels, HW, CW, w, b, K, out);
+        else if (K == 2) MBU_LAUNCH(classifier_lut_kernel<2>, dim3(blocks), dim3(256), 0, s, act, pixels, HW, CW, w, b, K, out);
+        else MBU_LAUNCH(classifier_lut_kernel<4>, dim3(blocks), dim3(256), 0, s, act, pixels, HW, CW, w, b, K, out);
+        return check_launch("classifier");
+    }
     long groups = (pixels + 31) / 32;
     // all waves resident at once, many pixel groups per wave to amortise splitting the weights.
     // Two blocks per compute unit: the kernel is bound by writing the logits, and measured on

@@ -909,7 +909,10 @@ def test_stem_full_size_frame():
 
 @pytest.mark.parametrize("shape", [(1, 9, 33, 32, 5), (2, 16, 40, 64, 19), (1, 7, 100, 128, 32),
                                    (1, 64, 64, 64, 1),
-                                   (3, 5, 7, 64, 19), (4, 3, 5, 32, 3), (5, 1, 1, 64, 19)])   # 32-pixel groups across images
+                                   (3, 5, 7, 64, 19), (4, 3, 5, 32, 3), (5, 1, 1, 64, 19),    # 32-pixel groups across images
+                                   # few classes (table look-up kernel): all widths, strides across images
+                                   (2, 33, 70, 64, 2), (1, 600, 700, 64, 2), (3, 40, 50, 128, 4), (1, 9, 9, 32, 1),
+                                   (7, 11, 13, 128, 3), (1, 1100, 1900, 64, 1)])
 def test_classifier_matches_oracle(shape):
     N, H, W, C, K = shape
     say(f"classifier {shape}")
