@@ -998,6 +998,55 @@ def test_two_frames_in_flight_on_two_streams():
     assert twin.workspace.data_ptr() != net.workspace.data_ptr()
 
 
+def test_forward_passes_from_two_host_threads():
+    """The entry points are re-entrant: two host threads, each with its own handle, stream and
+    workspace, run forward passes at the same time (ctypes releases the interpreter lock during
+    the calls) while a third thread keeps re-writing the process-wide settings with the values
+    they already have; every pass gives the single-threaded result."""
+    import threading
+    say("forward passes from two host threads")
+    case = synth.unet_case(2, 5, 1, 96, 160, base=64, levels=3, n_classes=4)
+    imgs = [case.image, np.random.default_rng(10).standard_normal(case.image.shape, dtype=np.float32)]
+    net = build_unet(case, True)
+    refs = [host(net.forward(dev(im))).copy() for im in imgs]
+    handles = [net, net.clone_for_stream()]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    d_imgs = [dev(im) for im in imgs]
+    outs = [torch.empty((1, 4, 96, 160), dtype=torch.float32, device="cuda") for _ in imgs]
+    torch.cuda.synchronize()
+    errors, stop = [], threading.Event()
+
+    def worker(i):
+        try:
+            torch.cuda.set_device(0)
+            for _ in range(60):
+                with torch.cuda.stream(streams[i]):
+                    handles[i].forward(d_imgs[i], outs[i])
+                streams[i].synchronize()
+                if not np.array_equal(host(outs[i]), refs[i]):
+                    errors.append(f"thread {i}: logits differ")
+                    return
+        except Exception as e:          # noqa: BLE001 - reported through the list
+            errors.append(f"thread {i}: {e!r}")
+
+    def setter():
+        while not stop.is_set():
+            B.set_conv_path(B.PATH_AUTO)
+            B.set_conv_tuning(0)
+            B.set_stem_path(B.STEM_AUTO)
+
+    ts = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    st = threading.Thread(target=setter)
+    st.start()
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join()
+    stop.set()
+    st.join()
+    assert not errors, errors
+
+
 def test_blob_sections():
     """Blobs packed with only the sections a layer's place in the network reads: the network
     object packs them that way by default; same bits as with complete blobs; a blob without the
