@@ -861,7 +861,7 @@ int launch_conv_mfma(const uint32_t *act, int N, int H, int W, const BlobLayout 
     // with several steps the block-cooperative kernel stages least per wave and wins.
     const int mode = t_cfg.tune_rw;   // 0 = automatic; see mbu_set_conv_tuning
     if (use_rows2k(N, H, W, L, out_bits != nullptr))
-        return launch_conv_mfma_rows2k(act, N, H, W, L, blob, thresh, out_bits, nullptr, s);
+        return launch_conv_mfma_rows2k(act, nullptr, 0, 0, N, H, W, L, blob, thresh, out_bits, nullptr, s);
     const bool want_block = mode == 1 || ((mode == 0 || mode == 9) && L.ksteps > 1);
     if (want_block) {
         ConvIO io{act, nullptr, 0, 0, 0, L.cin_words, 0, out_bits, nullptr};
@@ -887,7 +887,11 @@ int launch_conv_mfma_two(const uint32_t *act, int Ca, const uint32_t *low, int C
     if (!low && rows_kernel_waves() && conv_rows_supported(H, W, L, out_bits != nullptr))
         return launch_conv_mfma_rows(act, N, H, W, L, blob, thresh, out_bits, out_pool, rows_kernel_waves(), s);
     if (!low && use_rows2k(N, H, W, L, out_bits != nullptr))
-        return launch_conv_mfma_rows2k(act, N, H, W, L, blob, thresh, out_bits, out_pool, s);
+        return launch_conv_mfma_rows2k(act, nullptr, 0, 0, N, H, W, L, blob, thresh, out_bits, out_pool, s);
+    // [64 channels | 64 channels of a second tensor of the layer's resolution] (first layer of the
+    // last decoder level behind a transposed layer): the two-source form of the same kernel
+    if (low && low_shift == 0 && Ca == 64 && Clow == 64 && t_cfg.tune_rw != 1 && use_rows2k(N, H, W, L, out_bits != nullptr))
+        return launch_conv_mfma_rows2k(act, low, Hb, Wb, N, H, W, L, blob, thresh, out_bits, out_pool, s);
     const uint4 *wfrag = (const uint4 *)((const uint8_t *)blob + L.off_f4);
     ConvIO io{act, low, low ? low_shift : 0, low ? Hb : 0, low ? Wb : 0, ceil_div(Ca, 32),
               low ? ceil_div(Clow, 32) : 0, out_bits, out_pool};

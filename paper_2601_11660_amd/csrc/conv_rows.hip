@@ -50,6 +50,11 @@ struct RowsCtx {
     const uint4 *rd;       // LDS: this lane's fragment of tap column 0, ring slot 0
     int H, y0;
     int in_row_bytes, out_row_bytes, pool_row_bytes;
+    // second input of the two-source form of the two-step kernel: words 2 and 3 of a pixel come
+    // from a tensor of Hb rows (it may cover less than the frame: zeros where it has no pixel)
+    __amdgpu_buffer_rsrc_t in2;
+    uint32_t in2_voff, mx2b;
+    int Hb, in2_row_bytes;
 };
 
 // the two packed words of this lane's halo pixel in image row yy (clamped into the image)
@@ -369,12 +374,19 @@ struct Rows2Tmp {
     uint32_t s;
 };
 
-// the (three or) four packed words of this lane's halo pixel in image row yy (clamped)
+// the (three or) four packed words of this lane's halo pixel in image row yy (clamped); TWO: two
+// words from each of two tensors
+template <bool TWO>
 __device__ __forceinline__ void fetch_row4(const RowsCtx &c, int yy, uint4 &g, bool four)
 {
     const int yc = min(max(yy, 0), c.H - 1);
     const int soff = yc * c.in_row_bytes;
-    if (four) {
+    if (TWO) {
+        const auto v = __builtin_amdgcn_raw_buffer_load_b64(c.in, c.in_voff, soff, 0);
+        const int yb = min(max(yy, 0), c.Hb - 1);
+        const auto u = __builtin_amdgcn_raw_buffer_load_b64(c.in2, c.in2_voff, yb * c.in2_row_bytes, 0);
+        g = make_uint4(v[0], v[1], u[0], u[1]);
+    } else if (four) {
         const auto v = __builtin_amdgcn_raw_buffer_load_b128(c.in, c.in_voff, soff, 0);
         g = make_uint4(v[0], v[1], v[2], v[3]);
     } else {
@@ -405,7 +417,7 @@ __device__ __forceinline__ void store_row32(const RowsCtx &c, uint32_t s, int i_
 
 // Matrix instruction t (of 18) of one image row and the vector work behind it; P, R3, COPY as
 // in rows_step above.
-template <bool CW4, bool POOL, int P, int R3, bool COPY>
+template <bool CW4, bool POOL, bool TWO, int P, int R3, bool COPY>
 __device__ __forceinline__ void rows2_step(const RowsCtx &c, const int i, const v4i (&Wg)[2][3][3],
                                            const v16f &init, Rows2Stream &st)
 {
@@ -422,11 +434,15 @@ __device__ __forceinline__ void rows2_step(const RowsCtx &c, const int i, const 
         if (t == 0) {
             const bool rin = c.y0 + i + 3 < c.H;
             const uint32_t m2 = rin ? c.mx2 : 0u, p1 = (~m2 >> 1) & 0x11111111u;
+            // words 2 and 3 of the two-source form: inside the frame but possibly outside the
+            // second tensor, whose missing pixels are zeros like pixels outside the frame
+            const uint32_t m2b = (TWO && rin && c.y0 + i + 3 < c.Hb) ? c.mx2b : 0u;
+            const uint32_t p1b = rin ? ((~m2b >> 1) & 0x11111111u) : p1;
             tm.w[0] = st.gq[P].x; tm.w[1] = st.gq[P].y; tm.w[2] = st.gq[P].z; tm.w[3] = st.gq[P].w;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                tm.m2[k] = (k < 3 || CW4) ? m2 : 0u;
-                tm.p1[k] = (k < 3 || CW4) ? p1 : 0u;
+                tm.m2[k] = (TWO && k >= 2) ? m2b : (k < 3 || CW4) ? m2 : 0u;
+                tm.p1[k] = (TWO && k >= 2) ? p1b : (k < 3 || CW4) ? p1 : 0u;
             }
             tm.s = 0;
         }
@@ -445,7 +461,7 @@ __device__ __forceinline__ void rows2_step(const RowsCtx &c, const int i, const 
 #pragma unroll
             for (int k = 0; k < 4; ++k) c.wr[WR * R2_ROW + (k >> 1) * RS_ROW + (k & 1) * RS_HW] = tm.e[k];
             // halo row i + 6 into the register just consumed
-            fetch_row4(c, c.y0 + i + 5, st.gq[P], CW4);
+            fetch_row4<TWO>(c, c.y0 + i + 5, st.gq[P], CW4);
         }
         if (COPY && (t == 5 || t == 11)) {
             const int k = t / 6;   // F[.][k] <- F[.][k + 1]
@@ -481,9 +497,10 @@ __device__ __forceinline__ void rows2_step(const RowsCtx &c, const int i, const 
     }
 }
 
-template <bool CW4, bool POOL>
+template <bool CW4, bool POOL, bool TWO = false>
 __global__ __launch_bounds__(256, 2) void conv_mfma_rows2k_kernel(
-    const uint32_t *__restrict__ act, int H, int W, int Cw, const uint4 *__restrict__ wfrag, int Cout,
+    const uint32_t *__restrict__ act, const uint32_t *__restrict__ act2, int Hb, int Wb, int H, int W, int Cw,
+    const uint4 *__restrict__ wfrag, int Cout,
     int ctiles, int strips, int nseg, int seg_rows, int units, const int32_t *__restrict__ thresh,
     const int32_t *__restrict__ wsum, uint32_t *__restrict__ out_bits, uint32_t *__restrict__ out_pool)
 {
@@ -506,11 +523,16 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_rows2k_kernel(
     RowsCtx c;
     c.H = H;
     c.y0 = y0;
+    // two-source form: Cw counts the words of the first tensor (2), the second has 2 as well
     c.in_row_bytes = W * Cw * 4;
     c.out_row_bytes = W * Cow * 4;
     c.pool_row_bytes = (W >> 1) * Cow * 4;
     c.in = __builtin_amdgcn_make_buffer_rsrc((void *)(act + (size_t)n * H * W * Cw), 0, H * c.in_row_bytes,
                                              0x00020000);
+    c.Hb = TWO ? Hb : H;
+    c.in2_row_bytes = TWO ? Wb * 2 * 4 : 0;
+    c.in2 = __builtin_amdgcn_make_buffer_rsrc((void *)(TWO ? act2 + (size_t)n * Hb * Wb * 2 : act), 0,
+                                              TWO ? Hb * c.in2_row_bytes : 0, 0x00020000);
     c.out = __builtin_amdgcn_make_buffer_rsrc((void *)(out_bits + (size_t)n * H * W * Cow), 0,
                                               H * c.out_row_bytes, 0x00020000);
     c.pool = __builtin_amdgcn_make_buffer_rsrc(
@@ -521,6 +543,8 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_rows2k_kernel(
         const int xx = sx * 32 + p - 1;
         c.in_voff = (uint32_t)(min(max(xx, 0), W - 1) * Cw * 4);
         c.mx2 = (xx >= 0 && xx < W) ? 0x22222222u : 0u;
+        c.in2_voff = TWO ? (uint32_t)(min(max(xx, 0), Wb - 1) * 2 * 4) : 0u;
+        c.mx2b = (TWO && xx >= 0 && xx < Wb) ? 0x22222222u : 0u;
         c.wr = lds[wave] + p;
         c.rd = lds[wave] + half * RS_HW + col;
         const int x = sx * 32 + col;
@@ -565,18 +589,22 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_rows2k_kernel(
     {
         uint4 g4[4];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) fetch_row4(c, y0 - 1 + j, g4[j], CW4);
+        for (int j = 0; j < 4; ++j) fetch_row4<TWO>(c, y0 - 1 + j, g4[j], CW4);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) fetch_row4(c, y0 + 3 + j, st.gq[j], CW4);
+        for (int j = 0; j < 2; ++j) fetch_row4<TWO>(c, y0 + 3 + j, st.gq[j], CW4);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int yy = y0 - 1 + j;
-            const uint32_t m2 = (yy >= 0 && yy < H) ? c.mx2 : 0u, p1 = (~m2 >> 1) & 0x11111111u;
+            const bool rin = yy >= 0 && yy < H;
+            const uint32_t m2 = rin ? c.mx2 : 0u, p1 = (~m2 >> 1) & 0x11111111u;
+            const uint32_t m2b = (TWO && rin && yy < c.Hb) ? c.mx2b : 0u;
+            const uint32_t p1b = rin ? ((~m2b >> 1) & 0x11111111u) : p1;
             const uint32_t wv[4] = {g4[j].x, g4[j].y, g4[j].z, g4[j].w};
 #pragma unroll
             for (int k = 0; k < 4; ++k)
                 c.wr[(j & 1) * R2_ROW + (k >> 1) * RS_ROW + (k & 1) * RS_HW] =
-                    expand_word_masked(wv[k], (k < 3 || CW4) ? m2 : 0u, (k < 3 || CW4) ? p1 : 0u);
+                    expand_word_masked(wv[k], (TWO && k >= 2) ? m2b : (k < 3 || CW4) ? m2 : 0u,
+                                       (TWO && k >= 2) ? p1b : (k < 3 || CW4) ? p1 : 0u);
             __builtin_amdgcn_wave_barrier();
             if (j < 3) {
 #pragma unroll
@@ -606,17 +634,17 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_rows2k_kernel(
     int i = 0;
 #pragma unroll 1
     for (; i + 6 <= rows; i += 6) {
-        rows2_step<CW4, POOL, 0, 0, false>(c, i, Wg, init, st);
-        rows2_step<CW4, POOL, 1, 1, false>(c, i + 1, Wg, init, st);
-        rows2_step<CW4, POOL, 0, 2, false>(c, i + 2, Wg, init, st);
-        rows2_step<CW4, POOL, 1, 0, false>(c, i + 3, Wg, init, st);
-        rows2_step<CW4, POOL, 0, 1, false>(c, i + 4, Wg, init, st);
-        rows2_step<CW4, POOL, 1, 2, false>(c, i + 5, Wg, init, st);
+        rows2_step<CW4, POOL, TWO, 0, 0, false>(c, i, Wg, init, st);
+        rows2_step<CW4, POOL, TWO, 1, 1, false>(c, i + 1, Wg, init, st);
+        rows2_step<CW4, POOL, TWO, 0, 2, false>(c, i + 2, Wg, init, st);
+        rows2_step<CW4, POOL, TWO, 1, 0, false>(c, i + 3, Wg, init, st);
+        rows2_step<CW4, POOL, TWO, 0, 1, false>(c, i + 4, Wg, init, st);
+        rows2_step<CW4, POOL, TWO, 1, 2, false>(c, i + 5, Wg, init, st);
     }
 #pragma unroll 1
     for (; i < rows; i += 2) {
-        rows2_step<CW4, POOL, 0, 0, true>(c, i, Wg, init, st);
-        rows2_step<CW4, POOL, 1, 0, true>(c, i + 1, Wg, init, st);
+        rows2_step<CW4, POOL, TWO, 0, 0, true>(c, i, Wg, init, st);
+        rows2_step<CW4, POOL, TWO, 1, 0, true>(c, i + 1, Wg, init, st);
     }
 
     // ---- the signs of the last odd row, still in accumulator set 1
@@ -627,8 +655,9 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_rows2k_kernel(
 }
 
 template <bool POOL>
-static int launch_rows2k_t(const uint32_t *act, int N, int H, int W, const BlobLayout &L, const uint4 *wfrag,
-                           const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, hipStream_t s)
+static int launch_rows2k_t(const uint32_t *act, const uint32_t *act2, int Hb, int Wb, int N, int H, int W,
+                           const BlobLayout &L, const uint4 *wfrag, const int32_t *thresh, uint32_t *out_bits,
+                           uint32_t *out_pool, hipStream_t s)
 {
     const int32_t *wsum =
         (const int32_t *)((const uint8_t *)wfrag - L.off_f4 + L.off_cnt) + (size_t)10 * L.cout_pad64;
@@ -643,12 +672,17 @@ static int launch_rows2k_t(const uint32_t *act, int N, int H, int W, const BlobL
     const long units = base * nseg;
     if (units > 0x7fffffffL) return fail(MBU_ERR_SHAPE, "too many tiles for one launch");
     const int grid = (int)((units + 3) / 4);
-    if (L.cin_words == 4)
-        MBU_LAUNCH((conv_mfma_rows2k_kernel<true, POOL>), dim3(grid), dim3(256), 0, s, act, H, W, L.cin_words,
-                   wfrag, L.cout, ctiles, strips, nseg, seg_rows, (int)units, thresh, wsum, out_bits, out_pool);
+    if (act2)   // [64 channels | 64 channels] of two tensors
+        MBU_LAUNCH((conv_mfma_rows2k_kernel<true, POOL, true>), dim3(grid), dim3(256), 0, s, act, act2, Hb, Wb, H, W,
+                   2, wfrag, L.cout, ctiles, strips, nseg, seg_rows, (int)units, thresh, wsum, out_bits, out_pool);
+    else if (L.cin_words == 4)
+        MBU_LAUNCH((conv_mfma_rows2k_kernel<true, POOL>), dim3(grid), dim3(256), 0, s, act, act2, 0, 0, H, W,
+                   L.cin_words, wfrag, L.cout, ctiles, strips, nseg, seg_rows, (int)units, thresh, wsum, out_bits,
+                   out_pool);
     else
-        MBU_LAUNCH((conv_mfma_rows2k_kernel<false, POOL>), dim3(grid), dim3(256), 0, s, act, H, W, L.cin_words,
-                   wfrag, L.cout, ctiles, strips, nseg, seg_rows, (int)units, thresh, wsum, out_bits, out_pool);
+        MBU_LAUNCH((conv_mfma_rows2k_kernel<false, POOL>), dim3(grid), dim3(256), 0, s, act, act2, 0, 0, H, W,
+                   L.cin_words, wfrag, L.cout, ctiles, strips, nseg, seg_rows, (int)units, thresh, wsum, out_bits,
+                   out_pool);
     return check_launch("conv_mfma_rows2k");
 }
 
@@ -696,14 +730,17 @@ bool conv_rows2k_supported(int H, int W, const BlobLayout &L, bool wants_bits)
            (double)H * W * (L.cout >> 5) * 4 < 1073741824.0;
 }
 
-int launch_conv_mfma_rows2k(const uint32_t *act, int N, int H, int W, const BlobLayout &L, const void *blob,
-                            const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, hipStream_t s)
+int launch_conv_mfma_rows2k(const uint32_t *act, const uint32_t *act2, int Hb, int Wb, int N, int H, int W,
+                            const BlobLayout &L, const void *blob, const int32_t *thresh, uint32_t *out_bits,
+                            uint32_t *out_pool, hipStream_t s)
 {
     if (!conv_rows2k_supported(H, W, L, out_bits != nullptr))
         return fail(MBU_ERR_SHAPE, "row-streaming kernel for two input steps: layer not supported");
+    if (act2 && (L.cin != 128 || Hb < 1 || Wb < 1 || Hb > H || Wb > W))
+        return fail(MBU_ERR_SHAPE, "row-streaming kernel for two inputs: 64 + 64 channels, second input inside the frame");
     const uint4 *wfrag = (const uint4 *)((const uint8_t *)blob + L.off_f4);
-    if (out_pool) return launch_rows2k_t<true>(act, N, H, W, L, wfrag, thresh, out_bits, out_pool, s);
-    return launch_rows2k_t<false>(act, N, H, W, L, wfrag, thresh, out_bits, out_pool, s);
+    if (out_pool) return launch_rows2k_t<true>(act, act2, Hb, Wb, N, H, W, L, wfrag, thresh, out_bits, out_pool, s);
+    return launch_rows2k_t<false>(act, act2, Hb, Wb, N, H, W, L, wfrag, thresh, out_bits, out_pool, s);
 }
 
 int launch_conv_mfma_rows(const uint32_t *act, int N, int H, int W, const BlobLayout &L, const void *blob,

@@ -107,8 +107,10 @@ int launch_conv_mfma_two(const uint32_t *act, int Ca, const uint32_t *low, int C
 bool conv_rows_supported(int H, int W, const BlobLayout &L, bool wants_bits);
 // the same scheme for layers with two 64-channel input steps, 32 output channels per wave
 bool conv_rows2k_supported(int H, int W, const BlobLayout &L, bool wants_bits);
-int launch_conv_mfma_rows2k(const uint32_t *act, int N, int H, int W, const BlobLayout &L, const void *blob,
-                            const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, hipStream_t s);
+// act2 != NULL: the input is [act (64 channels) | act2 (64 channels, Hb x Wb pixels, zeros beyond)]
+int launch_conv_mfma_rows2k(const uint32_t *act, const uint32_t *act2, int Hb, int Wb, int N, int H, int W,
+                            const BlobLayout &L, const void *blob, const int32_t *thresh, uint32_t *out_bits,
+                            uint32_t *out_pool, hipStream_t s);
 int launch_conv_mfma_rows(const uint32_t *act, int N, int H, int W, const BlobLayout &L, const void *blob,
                           const int32_t *thresh, uint32_t *out_bits, uint32_t *out_pool, int waves_per_simd,
                           hipStream_t s);

@@ -362,6 +362,45 @@ def test_conv_on_plain_concatenation(shape):
     assert np.array_equal(host_u32(bits), bitref.pack_pm1(out_ref))
 
 
+@pytest.mark.parametrize("shape", [(1, 38, 70, 64, None, None), (2, 7, 33, 96, None, None), (1, 64, 64, 128, None, None),
+                                   (1, 9, 13, 64, 8, 12), (2, 21, 67, 32, 20, 66), (1, 12, 40, 64, 3, 5)])
+def test_row_streaming_kernel_on_two_inputs(shape):
+    """The two-step row-streaming kernel reading [64 channels | 64 channels] of two tensors in
+    place (first layer of the last decoder level behind a transposed layer, Sec. 2.1), the
+    second tensor possibly smaller than the frame; with the pooled second output where the
+    sizes allow; accumulators recovered through thresholds for one shape."""
+    N, H, W, Cout, Hb, Wb = shape
+    say(f"conv rows2k two inputs {shape}")
+    rng = np.random.default_rng(H * W + Cout)
+    a = synth.pm1_bits(rng, (N, H, W, 64))
+    b = synth.pm1_bits(rng, (N, Hb or H, Wb or W, 64))
+    w = synth.ternary_weights(17, 0, 0, Cout, 128, 0.6)
+    th = synth.thresholds(17, 0, 0, Cout, 72)
+    pad = np.zeros((N, H, W, 64), np.int8)
+    pad[:, :b.shape[1], :b.shape[2]] = b
+    acc_ref, out_ref = O.masked_binary_layer(O.concat(a, pad), w, th)
+    pa, pb, blob = B.pack_act(dev(a)), B.pack_act(dev(b)), B.pack_weights(dev(w))
+    B.set_conv_tuning(9)
+    if Hb is None:
+        bits, pool = B.conv3x3_masked_binary_concat(pa, 64, pb, 64, blob, Cout, dev(th), want_pool=True)
+        assert np.array_equal(host_u32(pool), bitref.pack_pm1(O.maxpool2x2(out_ref)))
+    else:
+        bits, _ = B.conv3x3_masked_binary_two_inputs(pa, 64, pb, 64, False, blob, Cout, dev(th))
+    torch.cuda.synchronize()
+    assert np.array_equal(host_u32(bits), bitref.pack_pm1(out_ref))
+    B.set_conv_tuning(1)      # the block kernel on the same call
+    if Hb is None:
+        bits1, _ = B.conv3x3_masked_binary_concat(pa, 64, pb, 64, blob, Cout, dev(th))
+    else:
+        bits1, _ = B.conv3x3_masked_binary_two_inputs(pa, 64, pb, 64, False, blob, Cout, dev(th))
+    assert np.array_equal(host_u32(bits1), host_u32(bits))
+    if shape[1] == 9:
+        B.set_conv_tuning(9)
+        got = recover_acc(lambda t: B.conv3x3_masked_binary_two_inputs(pa, 64, pb, 64, False, blob, Cout, t)[0],
+                          acc_ref, Cout)
+        assert np.array_equal(got, acc_ref)
+
+
 @pytest.mark.parametrize("fuse", [True, False])
 def test_unet_transposed_decoder_small_all_layers(fuse):
     """The paper-shaped decoder: masked transposed 2x2 layers instead of nearest up-sampling."""
