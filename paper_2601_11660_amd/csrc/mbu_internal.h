@@ -65,11 +65,12 @@ struct BlobLayout {
 };
 BlobLayout blob_layout(int cout, int cin, int sections = MBU_BLOB_ALL);
 
-// ---- packed blob of the transposed 2x2 stride-2 layer: 4-bit codes only,
-// uint4 [cout_pad64/64][ksteps][4 positions][2][64 lanes] after 256 bytes of header room
+// ---- packed blob of the transposed 2x2 stride-2 layer: 4-bit codes,
+// uint4 [cout_pad64/64][ksteps][4 positions][2][64 lanes] after 256 bytes of header room, then the
+// sum of the weights of every (position, output channel) (activations enter as 0 / 1)
 struct TconvLayout {
     int cout, cin, cin_words, cout_pad64, ksteps;
-    size_t off_f4, total;
+    size_t off_f4, off_sum, total;   // fragments; int32 [4 positions][cout_pad64] sums of the weights
 };
 TconvLayout tconv_layout(int cout, int cin);
 

@@ -6,7 +6,10 @@
 // With kernel = stride every output pixel (2y+dy, 2x+dx) receives exactly one tap, so the
 // layer is four independent 1x1 contractions, one per position p = 2*dy + dx:
 //   D_p[cout][pixel] = sum_c W[cout][p][c] * A[c][pixel].
-// Same FP4 encoding and operand layout as the 3x3 layer (exact integers in fp32).  No halo
+// Same FP4 encoding and operand layout as the 3x3 layer (exact integers in fp32), activations as
+// the packed bit itself (code 1.0 / 0): sum w a = 2 sum w a' - sum w, and the sum of the weights
+// of (position, channel) goes into the accumulators' start value with the threshold
+// (mfma_common.h) - there is no padding here, so no 0.5 code either.  No halo
 // and no reuse of activations between taps: the activation fragment of a lane is ONE packed
 // word, loaded straight from global memory and expanded in registers (7 vector ops),
 // and it feeds the two channel tiles of one position.  The four waves of a block are the four
@@ -28,14 +31,15 @@ TconvLayout tconv_layout(int cout, int cin)
     L.cout_pad64 = ceil_div(cout, 64) * 64;
     L.ksteps = ceil_div(cin, 64);
     L.off_f4 = 256;
-    L.total = round_up(L.off_f4 + (size_t)(L.cout_pad64 / 64) * L.ksteps * 8 * 64 * 16, 256);
+    L.off_sum = round_up(L.off_f4 + (size_t)(L.cout_pad64 / 64) * L.ksteps * 8 * 64 * 16, 256);
+    L.total = round_up(L.off_sum + (size_t)4 * L.cout_pad64 * sizeof(int32_t), 256);
     return L;
 }
 
 // Thread (o, position p, word k) packs 32 weights into one 16-byte fragment:
 // fragments are uint4 [cout_pad64/64][ksteps][4 positions][2][64 lanes]; nibble q of dword d
-// carries input channel 32k + 4q + d as the E2M1 code of -w (the activation side is negated
-// too); lane = 32*(k&1) + tile row of the output channel.
+// carries input channel 32k + 4q + d as the E2M1 code of w; lane = 32*(k&1) + tile row of the
+// output channel.
 __global__ __launch_bounds__(256) void pack_tconv_kernel(const int8_t *__restrict__ w,
                                                          TconvLayout L, uint8_t *__restrict__ blob)
 {
@@ -52,7 +56,7 @@ __global__ __launch_bounds__(256) void pack_tconv_kernel(const int8_t *__restric
         const int n = min(32, L.cin - k * 32);
         for (int i = 0; i < n; ++i) {
             const int v = src[i];
-            const uint32_t code = v > 0 ? 0xAu : (v < 0 ? 0x2u : 0x0u);
+            const uint32_t code = v > 0 ? 0x2u : (v < 0 ? 0xAu : 0x0u);
             d[i & 3] |= code << (4 * (i >> 2));
         }
     }
@@ -64,12 +68,32 @@ __global__ __launch_bounds__(256) void pack_tconv_kernel(const int8_t *__restric
     F[at] = make_uint4(d[0], d[1], d[2], d[3]);
 }
 
+// Sum of the weights of every (position, output channel): one wave per pair.
+__global__ __launch_bounds__(256) void sum_tconv_kernel(const int8_t *__restrict__ w, TconvLayout L,
+                                                        uint8_t *__restrict__ blob)
+{
+    const int idx = blockIdx.x * 4 + (threadIdx.x >> 6);    // p * cout_pad64 + o
+    const int lane = threadIdx.x & 63;
+    if (idx >= 4 * L.cout_pad64) return;
+    const int p = idx / L.cout_pad64, o = idx - p * L.cout_pad64;
+    int sum = 0;
+    if (o < L.cout) {
+        const int8_t *src = w + ((long)o * 4 + p) * L.cin;
+        for (int i = lane; i < L.cin; i += 64) sum += (src[i] > 0) - (src[i] < 0);
+    }
+    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+    if (lane == 0) reinterpret_cast<int32_t *>(blob + L.off_sum)[idx] = sum;
+}
+
 int launch_pack_tconv(const int8_t *w, const TconvLayout &L, void *blob, hipStream_t s)
 {
     const long total = (long)L.cout_pad64 * 4 * 2 * L.ksteps;
     MBU_LAUNCH(pack_tconv_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, w, L,
                (uint8_t *)blob);
-    return check_launch("pack_tconv_weights");
+    int rc = check_launch("pack_tconv_weights");
+    if (rc) return rc;
+    MBU_LAUNCH(sum_tconv_kernel, dim3((unsigned)L.cout_pad64), dim3(256), 0, s, w, L, (uint8_t *)blob);
+    return check_launch("pack_tconv_sums");
 }
 
 // weight fragments of one 64-channel step of one position: [m]
@@ -92,11 +116,12 @@ template <bool WRITE_ACC>
 __global__ __launch_bounds__(256, 2) void tconv_mfma_kernel(
     const uint32_t *__restrict__ act, int N, int H, int W, int Cw, int ksteps,
     const uint4 *__restrict__ wfrag, int Cout, long groups, int groups_x, int groups_y,
-    const int32_t *__restrict__ thresh, uint32_t *__restrict__ out_bits,
-    int32_t *__restrict__ out_acc)
+    const int32_t *__restrict__ thresh, const int32_t *__restrict__ wsum, int cout_pad64,
+    uint32_t *__restrict__ out_bits, int32_t *__restrict__ out_acc)
 {
     const int lane = threadIdx.x & 63;
     const int p = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // position of this wave
+    const int32_t *ws = wsum + (size_t)p * cout_pad64;               // sums of this position's weights
     const long g = blockIdx.x;                          // (n, row group, 32-pixel column group)
     const int ct = blockIdx.y;                          // 64-channel output tile
     const int col = lane & 31, half = lane >> 5;
@@ -115,7 +140,7 @@ __global__ __launch_bounds__(256, 2) void tconv_mfma_kernel(
         const bool in = in_x && y0 + r < H;
         const int yc = min(y0 + r, H - 1), xc = in_x ? x : W - 1;
         src[r] = act + (((size_t)n * H + yc) * W + xc) * Cw;
-        k8[r] = in ? 0x88888888u : 0u;
+        k8[r] = in ? 0x22222222u : 0u;
     }
 
     v16f acc[RG][2];
@@ -125,15 +150,16 @@ __global__ __launch_bounds__(256, 2) void tconv_mfma_kernel(
         float init[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) init[i] = 0.0f;
-        if (!WRITE_ACC && cbase < Cout) {              // accumulators start at -theta
+        if (!WRITE_ACC && cbase < Cout) {              // accumulators start at -(theta + sum w) / 2
             const int4 *tp = reinterpret_cast<const int4 *>(thresh + cbase);
+            const int4 *sp = reinterpret_cast<const int4 *>(ws + cbase);
 #pragma unroll
             for (int qq = 0; qq < 4; ++qq) {
-                const int4 t = tp[qq];
-                init[4 * qq] = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.x));
-                init[4 * qq + 1] = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.y));
-                init[4 * qq + 2] = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.z));
-                init[4 * qq + 3] = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.w));
+                const int4 t = tp[qq], u = sp[qq];
+                init[4 * qq] = start_value(t.x, u.x);
+                init[4 * qq + 1] = start_value(t.y, u.y);
+                init[4 * qq + 2] = start_value(t.z, u.z);
+                init[4 * qq + 3] = start_value(t.w, u.w);
             }
         }
 #pragma unroll
@@ -153,10 +179,10 @@ __global__ __launch_bounds__(256, 2) void tconv_mfma_kernel(
         const bool live = 2 * ks + half < Cw;          // second word of an odd word count
 #pragma unroll
         for (int r = 0; r < RG; ++r) {
-            const uint32_t m8 = live ? k8[r] : 0u, m2 = m8 >> 2;
+            const uint32_t m2 = live ? k8[r] : 0u;
             const uint32_t word = wd[r];
-            const v4i B = {(int)(((word << 3) & m8) | m2), (int)(((word << 2) & m8) | m2),
-                           (int)(((word << 1) & m8) | m2), (int)((word & m8) | m2)};
+            const v4i B = {(int)((word << 1) & m2), (int)(word & m2), (int)((word >> 1) & m2),
+                           (int)((word >> 2) & m2)};
 #pragma unroll
             for (int m = 0; m < 2; ++m) acc[r][m] = mfma_f4(Wt[m], B, acc[r][m]);
         }
@@ -193,7 +219,8 @@ __global__ __launch_bounds__(256, 2) void tconv_mfma_kernel(
                 int vals[16];
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    vals[i] = (int)acc[r][m][i];
+                    // the accumulator holds sum w a' (an integer): sum w a = 2 sum w a' - sum w
+                    vals[i] = 2 * (int)acc[r][m][i] - (cbase < Cout ? ws[cbase + i] : 0);
                     const int th = cbase < Cout ? thresh[cbase + i] : 0x7fffffff;
                     bits[m] |= (uint32_t)(vals[i] < th) << i;       // 1 = below threshold
                 }
@@ -240,11 +267,13 @@ template <int RG>
 __global__ __launch_bounds__(256, RG == 2 ? 4 : 2) void tconv_bits_kernel(
     const uint32_t *__restrict__ act, int N, int H, int W, int Cw, int ksteps,
     const uint4 *__restrict__ wfrag, int Cout, int groups, int groups_x, int groups_y,
-    const int32_t *__restrict__ thresh, uint32_t *__restrict__ out_bits)
+    const int32_t *__restrict__ thresh, const int32_t *__restrict__ wsum, int cout_pad64,
+    uint32_t *__restrict__ out_bits)
 {
     constexpr uint32_t BAD = 0x40000000u;   // beyond any tensor this kernel accepts (< 2^30 bytes)
     const int lane = threadIdx.x & 63;
     const int p = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // position of this wave
+    const int32_t *ws = wsum + (size_t)p * cout_pad64;
     const int ct = blockIdx.y;                                        // 64-channel output tile
     const int col = lane & 31, half = lane >> 5;
     const int Cow = Cout >> 5;
@@ -261,24 +290,26 @@ __global__ __launch_bounds__(256, RG == 2 ? 4 : 2) void tconv_bits_kernel(
     // output word of this lane inside a row of output pixels, for pixel group column 0
     const uint32_t out_lane = (ct * 2 + half < Cow) ? (uint32_t)(((2 * col + dx) * Cow + ct * 2 + half) * 4) : BAD;
 
-    // ---- -theta for the 2 x 16 channels of this lane
+    // ---- -(theta + sum w) / 2 for the 2 x 16 channels of this lane
     v16f init[2];
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
         const int cbase = ct * 64 + m * 32 + 16 * half;
-        int th[16];
+        int th[16], su[16];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) th[i] = 0;
+        for (int i = 0; i < 16; ++i) th[i] = su[i] = 0;
         if (cbase < Cout) {
             const int4 *tp = reinterpret_cast<const int4 *>(thresh + cbase);
+            const int4 *sp = reinterpret_cast<const int4 *>(ws + cbase);
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int4 t = tp[q];
+                const int4 t = tp[q], u = sp[q];
                 th[4 * q] = t.x; th[4 * q + 1] = t.y; th[4 * q + 2] = t.z; th[4 * q + 3] = t.w;
+                su[4 * q] = u.x; su[4 * q + 1] = u.y; su[4 * q + 2] = u.z; su[4 * q + 3] = u.w;
             }
         }
 #pragma unroll
-        for (int i = 0; i < 16; ++i) init[m][i] = 0.0f - (float)max(-(1 << 22), min(1 << 22, th[i]));
+        for (int i = 0; i < 16; ++i) init[m][i] = start_value(th[i], su[i]);
     }
 
     // ---- per-group plan: byte offset of the lane's word 0 of each of the RG pixels (clamped
@@ -297,7 +328,7 @@ __global__ __launch_bounds__(256, RG == 2 ? 4 : 2) void tconv_bits_kernel(
             const int y = P.gy * RG + r;
             const int yc = min(y, H - 1);
             P.off[r] = (uint32_t)((((P.n * H + yc) * W + xc) * Cw + half) * 4);
-            P.k8[r] = (x < W && y < H) ? 0x88888888u : 0u;
+            P.k8[r] = (x < W && y < H) ? 0x22222222u : 0u;
         }
         return P;
     };
@@ -346,10 +377,10 @@ __global__ __launch_bounds__(256, RG == 2 ? 4 : 2) void tconv_bits_kernel(
         v4i B[RG];
 #pragma unroll
         for (int r = 0; r < RG; ++r) {
-            const uint32_t m8 = live ? cur.k8[r] : 0u, m2 = m8 >> 2;
+            const uint32_t m2 = live ? cur.k8[r] : 0u;
             const uint32_t word = R.wd[r];
-            B[r] = (v4i){(int)(((word << 3) & m8) | m2), (int)(((word << 2) & m8) | m2),
-                         (int)(((word << 1) & m8) | m2), (int)((word & m8) | m2)};
+            B[r] = (v4i){(int)((word << 1) & m2), (int)(word & m2), (int)((word >> 1) & m2),
+                         (int)((word >> 2) & m2)};
         }
         if (ks == 0) {
 #pragma unroll
@@ -408,14 +439,15 @@ __global__ __launch_bounds__(256, RG == 2 ? 4 : 2) void tconv_bits_kernel(
 template <int KS, int RGX>
 __global__ __launch_bounds__(256, 2) void tconv_res_kernel(
     const uint32_t *__restrict__ act, int N, int H, int W, const uint4 *__restrict__ wfrag, int Cout,
-    int groups, int groups_x, int groups_y, const int32_t *__restrict__ thresh, uint32_t *__restrict__ out_bits)
+    int groups, int groups_x, int groups_y, const int32_t *__restrict__ thresh,
+    const int32_t *__restrict__ wsum, int cout_pad64, uint32_t *__restrict__ out_bits)
 {
     constexpr uint32_t BAD = 0x40000000u;   // beyond any tensor this kernel accepts (< 2^30 bytes)
     constexpr int CW = 2 * KS;              // words per pixel
     constexpr int TILE = RGX * CW * 32;     // words per pixel group
     constexpr int PW = TILE / 256;          // words per thread and group: 4 (2 for KS = 2)
     static_assert(PW == 4 || PW == 2, "one 16- or 8-byte fetch per thread");
-    __shared__ float4 init_tab[2][2][4];    // [half][m][4 x 4 channels]: -theta
+    __shared__ float4 init_tab[4][2][2][4]; // [position][half][m][4 x 4 channels]: -(theta + sum w) / 2
     __shared__ uint32_t words[2][TILE];     // [buffer][row][word][pixel]
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -426,17 +458,16 @@ __global__ __launch_bounds__(256, 2) void tconv_res_kernel(
     const int dy = p >> 1, dx = p & 1;
     const uint32_t psel = half ? 0x07060302u : 0x05040100u;
 
-    if (tid < 16) {   // thread (h, m, q) writes one float4 of the table (visible after the first barrier)
-        const int h = tid >> 3, m = (tid >> 2) & 1, q = tid & 3;
+    if (tid < 64) {   // thread (position, h, m, q) writes one float4 of the table (visible after the first barrier)
+        const int pp = tid >> 4, h = (tid >> 3) & 1, m = (tid >> 2) & 1, q = tid & 3;
         const int cbase = ct * 64 + m * 32 + 16 * h + 4 * q;
-        int4 t = make_int4(0, 0, 0, 0);
-        if (cbase < Cout) t = *reinterpret_cast<const int4 *>(thresh + cbase);
-        float4 f;
-        f.x = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.x));
-        f.y = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.y));
-        f.z = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.z));
-        f.w = 0.0f - (float)max(-(1 << 22), min(1 << 22, t.w));
-        init_tab[h][m][q] = f;
+        int4 t = make_int4(0, 0, 0, 0), u = make_int4(0, 0, 0, 0);
+        if (cbase < Cout) {
+            t = *reinterpret_cast<const int4 *>(thresh + cbase);
+            u = *reinterpret_cast<const int4 *>(wsum + (size_t)pp * cout_pad64 + cbase);
+        }
+        init_tab[pp][h][m][q] = make_float4(start_value(t.x, u.x), start_value(t.y, u.y),
+                                            start_value(t.z, u.z), start_value(t.w, u.w));
     }
 
     const __amdgpu_buffer_rsrc_t ars =
@@ -522,7 +553,7 @@ __global__ __launch_bounds__(256, 2) void tconv_res_kernel(
         for (int m = 0; m < 2; ++m)
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const float4 f = init_tab[half][m][q];
+                const float4 f = init_tab[p][half][m][q];
 #pragma unroll
                 for (int r = 0; r < RGX; ++r) {
                     acc[r][m][4 * q] = f.x; acc[r][m][4 * q + 1] = f.y;
@@ -532,16 +563,16 @@ __global__ __launch_bounds__(256, 2) void tconv_res_kernel(
         uint32_t k8[RGX];
 #pragma unroll
         for (int r = 0; r < RGX; ++r)
-            k8[r] = (cur.gx * 32 + col < W && cur.gy * RGX + r < H) ? 0x88888888u : 0u;
+            k8[r] = (cur.gx * 32 + col < W && cur.gy * RGX + r < H) ? 0x22222222u : 0u;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             v4i B[RGX];
 #pragma unroll
             for (int r = 0; r < RGX; ++r) {
-                const uint32_t m8 = k8[r], m2 = m8 >> 2;
+                const uint32_t m2 = k8[r];
                 const uint32_t word = srd[buf * TILE + (r * CW + 2 * ks) * 32];
-                B[r] = (v4i){(int)(((word << 3) & m8) | m2), (int)(((word << 2) & m8) | m2),
-                             (int)(((word << 1) & m8) | m2), (int)((word & m8) | m2)};
+                B[r] = (v4i){(int)((word << 1) & m2), (int)(word & m2), (int)((word >> 1) & m2),
+                             (int)((word >> 2) & m2)};
             }
 #pragma unroll
             for (int r = 0; r < RGX; ++r)
@@ -591,8 +622,9 @@ static int launch_tconv_res(const uint32_t *act, int N, int H, int W, const Tcon
     const int tiles64 = L.cout_pad64 / 64;
     // two blocks per compute unit in total, spread over the 64-channel tiles
     const int per_tile = (int)std::min(groups, (long)std::max(1, 512 / tiles64));
+    const int32_t *wsum = (const int32_t *)((const uint8_t *)wfrag - L.off_f4 + L.off_sum);
     MBU_LAUNCH((tconv_res_kernel<KS, RGX>), dim3((unsigned)per_tile, (unsigned)tiles64), dim3(256), 0, s, act, N, H,
-               W, wfrag, L.cout, (int)groups, groups_x, groups_y, thresh, out_bits);
+               W, wfrag, L.cout, (int)groups, groups_x, groups_y, thresh, wsum, L.cout_pad64, out_bits);
     return check_launch("tconv2x2_masked_binary");
 }
 
@@ -604,6 +636,7 @@ int launch_tconv_mfma(const uint32_t *act, int N, int H, int W, const TconvLayou
     const long groups = (long)N * groups_y * groups_x;
     if (groups > 0x7fffffffL) return fail(MBU_ERR_SHAPE, "too many pixel groups for one launch");
     const uint4 *wfrag = (const uint4 *)((const uint8_t *)blob + L.off_f4);
+    const int32_t *wsum = (const int32_t *)((const uint8_t *)blob + L.off_sum);
     // packed bits only, at least two input steps, every tensor below 1 GiB: the persistent
     // kernel, two blocks per compute unit spread over the 64-channel tiles
     const int tiles64 = L.cout_pad64 / 64;
@@ -623,16 +656,17 @@ int launch_tconv_mfma(const uint32_t *act, int N, int H, int W, const TconvLayou
         if (groups2 > 0x7fffffffL) return fail(MBU_ERR_SHAPE, "too many pixel groups for one launch");
         const int per_tile = (int)std::min(groups2, (long)std::max(1, 512 / tiles64));
         MBU_LAUNCH(tconv_bits_kernel<RGF>, dim3((unsigned)per_tile, (unsigned)tiles64), dim3(256), 0, s, act, N, H,
-                   W, L.cin_words, L.ksteps, wfrag, L.cout, (int)groups2, groups_x, gy2, thresh, out_bits);
+                   W, L.cin_words, L.ksteps, wfrag, L.cout, (int)groups2, groups_x, gy2, thresh, wsum, L.cout_pad64,
+                   out_bits);
         return check_launch("tconv2x2_masked_binary");
     }
     dim3 grid((unsigned)groups, (unsigned)(L.cout_pad64 / 64));   // 4 waves = the 4 positions
     if (out_acc)
         MBU_LAUNCH(tconv_mfma_kernel<true>, grid, dim3(256), 0, s, act, N, H, W, L.cin_words,
-                   L.ksteps, wfrag, L.cout, groups, groups_x, groups_y, thresh, out_bits, out_acc);
+                   L.ksteps, wfrag, L.cout, groups, groups_x, groups_y, thresh, wsum, L.cout_pad64, out_bits, out_acc);
     else
         MBU_LAUNCH(tconv_mfma_kernel<false>, grid, dim3(256), 0, s, act, N, H, W, L.cin_words,
-                   L.ksteps, wfrag, L.cout, groups, groups_x, groups_y, thresh, out_bits, out_acc);
+                   L.ksteps, wfrag, L.cout, groups, groups_x, groups_y, thresh, wsum, L.cout_pad64, out_bits, out_acc);
     return check_launch("tconv2x2_masked_binary");
 }
 
