@@ -417,7 +417,7 @@ def main():
     # ---- KP more passes with one HIP event per launched kernel (recorded by the library on
     # the launch stream): per-layer breakdown and the dominant kernel's duration.  Kept out of
     # the region above because 28 event records per pass cost about a tenth of it.
-    KP = max(20, min(K, 200))      # directly after the timed region: same device state
+    KP = max(100, min(K, 200))     # directly after the timed region: same device state
     ev_sets = [net.new_event_set() for _ in range(KP)]
     torch.cuda.synchronize()
     t2 = time.perf_counter()
